@@ -1,0 +1,211 @@
+/*
+ * minions_verify.h: C ABI of the LLM verification step of aggregated speculative execution
+ * (Minions, arXiv 2402.15678) for AMD MI355X (gfx950).
+ *
+ * One verification step is three calls on one HIP stream:
+ *
+ *   mn_mv_vote            tree-based weighted majority decision over the n SSM drafts of every
+ *                         sequence (paper section 3.2, "Tree-based Weighted Majority Decision").
+ *   mn_verify_forward     the LLM scores the pending token and the k_b voted tokens of every
+ *                         sequence in one decoder forward against the existing paged KV cache and
+ *                         takes the argmax per position (section 2.1; section 4, multi-token input
+ *                         with an existing KV cache).
+ *   mn_accept_and_commit  longest-prefix acceptance (the greedy case of section 2.1's rule) and
+ *                         removal of the rejected tokens' KV entries (section 4).
+ *
+ * General rules
+ *   - "dev" pointers are device (HBM) pointers, "host" pointers are host pointers.  The caller
+ *     owns every buffer.  The library allocates no device memory, frees nothing of the caller's
+ *     and keeps no reference to per-call buffers after the call returns.
+ *   - Every call is asynchronous on `stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream) and performs no device synchronisation.
+ *   - Every call returns an mn_status.  Problems the host can see (null pointer, bad shape,
+ *     unsupported configuration, workspace too small) are reported before anything is launched.
+ *     Problems only the device can see (a block table too short for a sequence, a block id out
+ *     of range, a device spec_len that disagrees with the host copy) set bits in *dev_status
+ *     (device int32, MN_DEV_* flags, OR-ed in; the caller zeroes it) and turn the affected
+ *     sequence into a no-op: nothing of it is written to the cache, its outputs are -1 / 0.
+ *   - Token ids are int32.  Padding value in voted/greedy/out_tokens is -1.
+ *   - All matrices are [out][in] row-major: the contraction index is contiguous.
+ */
+#ifndef MINIONS_VERIFY_H
+#define MINIONS_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mn_ctx mn_ctx; /* opaque; host memory only */
+
+typedef enum {
+  MN_OK = 0,
+  MN_EINVAL = -1,       /* argument out of range */
+  MN_ENULL = -2,        /* required pointer is NULL */
+  MN_ESHAPE = -3,       /* shapes inconsistent with the model or with each other */
+  MN_EUNSUPPORTED = -4, /* configuration not implemented (the message names it) */
+  MN_ECAPACITY = -5,    /* host-visible capacity exceeded (e.g. max_ctx beyond the block table) */
+  MN_EWORKSPACE = -6,   /* workspace smaller than mn_workspace_bytes() or misaligned */
+  MN_EHIP = -7          /* a HIP call failed; mn_last_error() has the HIP error string */
+} mn_status;
+
+enum { MN_ARCH_OPT = 0, MN_ARCH_LLAMA = 1 };
+enum { MN_DT_F32 = 0, MN_DT_BF16 = 1 };
+enum { MN_VOTE_TREE = 0, MN_VOTE_COLUMN = 1 };
+enum {
+  MN_DEV_BLOCK_TABLE = 1, /* block table does not cover ctx_b + k_b + 1 tokens, or a block id is out of range */
+  MN_DEV_SPEC_LEN = 2,    /* device spec_len differs from the host copy / exceeds k_max / is negative */
+  MN_DEV_TOKEN = 4,       /* an input token id or position is outside the vocabulary / position table */
+  MN_DEV_DRAFTS = 8       /* mv_vote: spec_len outside [0, k_max] */
+};
+
+/* Limits (checked; MN_EINVAL / MN_EUNSUPPORTED beyond them). */
+#define MN_MAX_DRAFTS 64   /* n, SSMs per sequence */
+#define MN_MAX_BATCH 4096  /* B */
+#define MN_MAX_SPLIT_K 16
+
+typedef struct {
+  int arch;  /* MN_ARCH_OPT: LayerNorm, biases, ReLU FFN, learned absolute positions, n_kv_heads == n_heads.
+                MN_ARCH_LLAMA: RMSNorm, no biases, SwiGLU FFN, rotary positions, grouped-query attention. */
+  int dtype; /* storage type of matrices, embeddings and KV pages: MN_DT_F32 or MN_DT_BF16.
+                Norm gains/shifts and biases are fp32 in both. */
+  int n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  int max_pos;     /* rows of pos_emb (OPT); upper bound on ctx_b + k_b + 1 in either arch */
+  float norm_eps;  /* inside the square root of both norms */
+  float rope_base; /* Llama: angle of pair (i, i + head_dim/2) at position p is p * base^(-2i/head_dim) */
+} mn_model_desc;
+
+/* Device pointers to the parameters.  The per-layer members are HOST arrays of n_layers device
+ * pointers; mn_create copies the arrays (not the parameters).  Unused members are NULL.
+ *   tok_emb [vocab][d]            pos_emb [max_pos][d] (OPT)       lm_head [vocab][d]
+ *   final_norm_g/b [d]            (b: OPT only)
+ *   ln1_g/ln1_b, ln2_g/ln2_b [d]  (b: OPT only)
+ *   wqkv [(H + 2 Hkv) hd][d]      rows: all query heads, then all key heads, then all value heads
+ *   bqkv [(H + 2 Hkv) hd] (OPT)   wo [d][H hd]    bo [d] (OPT)
+ *   w1: OPT [F][d], Llama [2F][d] with rows [0,F) = gate and [F,2F) = up;  b1 [F] (OPT)
+ *   w2 [d][F]                     b2 [d] (OPT)
+ */
+typedef struct {
+  const void *tok_emb, *pos_emb, *final_norm_g, *final_norm_b, *lm_head;
+  const void *const *ln1_g, *const *ln1_b, *const *wqkv, *const *bqkv, *const *wo, *const *bo;
+  const void *const *ln2_g, *const *ln2_b, *const *w1, *const *b1, *const *w2, *const *b2;
+} mn_weights;
+
+/* Paged KV cache (section 4: every cached token is addressed by a logical block id and an
+ * offset).  Token p of sequence b is in physical block block_tables[b][p / block_size] at offset
+ * p % block_size.  Per layer, in the model's storage type:
+ *   K pages [num_blocks][n_kv_heads][head_dim/8][block_size][8]   (8 consecutive head-dim
+ *                                                                  elements of one token together)
+ *   V pages [num_blocks][n_kv_heads][head_dim][block_size]        (one head-dim element of the
+ *                                                                  block's tokens together)
+ * k_layers / v_layers are HOST arrays of n_layers device pointers, read at each call.
+ * Rows at positions >= ctx_lens[b] are undefined; mn_verify_forward writes the k_b + 1 scored
+ * tokens' rows there tentatively, only mn_accept_and_commit advances ctx_lens. */
+typedef struct {
+  void *const *k_layers;
+  void *const *v_layers;
+  int block_size;              /* tokens per block; the MFMA attention kernel needs 16 */
+  int num_blocks;              /* physical blocks per layer */
+  int max_blocks_per_seq;      /* row length of block_tables */
+  const int32_t *block_tables; /* dev [B][max_blocks_per_seq] */
+  int32_t *ctx_lens;           /* dev [B]; written only by mn_accept_and_commit */
+} mn_kv;
+
+/* ---- lifetime --------------------------------------------------------------------------- */
+
+/* Validates the description, copies the pointer tables.  *out is NULL on failure; with out != NULL
+ * a failed create leaves a message retrievable through mn_last_error(NULL). */
+mn_status mn_create(mn_ctx **out, const mn_model_desc *desc, const mn_weights *weights);
+void mn_destroy(mn_ctx *ctx);
+
+/* Message of the last failed call on ctx (or of the last failed mn_create when ctx is NULL).
+ * The string is owned by the library and valid until the next failing call on the same ctx. */
+const char *mn_last_error(const mn_ctx *ctx);
+const char *mn_status_str(mn_status s);
+
+/* Bytes of device workspace mn_verify_forward needs for at most max_rows = sum_b (k_b + 1) scored
+ * positions, B sequences and contexts up to max_ctx tokens (including the scored ones).
+ * The workspace must be 256-byte aligned.  Returns 0 on invalid arguments. */
+size_t mn_workspace_bytes(const mn_ctx *ctx, int B, int max_rows, int max_ctx);
+
+/* ---- the verification step --------------------------------------------------------------- */
+
+/* Majority vote (section 3.2).  For every sequence b the n drafts drafts[b][j][0..k_b) form a
+ * token tree rooted at the last committed token; a node's weight is the fp32 sum, in ascending
+ * draft order, of ssm_w[j] over the drafts passing through it; from the root the heaviest child
+ * is taken at every level (ties: the child whose first supporting draft has the lowest index).
+ * voted[b][0..k_b) is the chosen branch (positions >= k_b are set to -1) and voted_ssm[b] the
+ * lowest-index draft equal to it (the paper's voted_SSM).
+ * mode MN_VOTE_COLUMN votes every position over all n drafts without the prefix filter;
+ * voted_ssm is then the lowest-index draft equal to the result, or -1 if there is none.
+ *   drafts    dev [B][n][k_max] int32          spec_len  dev [B] int32, 0 <= k_b <= k_max
+ *   ssm_w     dev [n] fp32                     voted     dev [B][k_max] int32 (out)
+ *   voted_ssm dev [B] int32 (out)              dev_status dev [1] int32 (flags OR-ed in) or NULL
+ * Limits: 1 <= n <= MN_MAX_DRAFTS, 0 <= k_max, 0 <= B <= MN_MAX_BATCH (B = 0 is a no-op).
+ * ctx may be NULL (the vote does not depend on the model). */
+mn_status mn_mv_vote(mn_ctx *ctx, const int32_t *drafts, const int32_t *spec_len, const float *ssm_w, int B, int n,
+                     int k_max, int mode, int32_t *voted, int32_t *voted_ssm, int32_t *dev_status, void *stream);
+
+/* Verification forward (sections 2.1 and 4).  Sequence b contributes q_b = k_b + 1 rows: input
+ * tokens [last_tok[b], voted[b][0..k_b)] at positions ctx_b .. ctx_b + k_b.  Row j attends to
+ * the cached tokens [0, ctx_b) and to rows 0..j of its own sequence (causal among the speculated
+ * tokens).  The rows' K/V are written into the cache at their positions (tentatively, beyond
+ * ctx_lens).  greedy[b][j] = lowest token id attaining the maximum logit of row j, j <= k_b;
+ * entries j > k_b are set to -1.  With ctx_b = 0 this call is a prefill.
+ *   last_tok   dev [B]            voted dev [B][k_max] (ignored where k_max == 0; may be NULL then)
+ *   spec_len   dev [B]            h_spec_len HOST [B], the same values: they size the launch
+ *   max_ctx    upper bound on ctx_b + k_b + 1 over the batch (sizes the attention launch)
+ *   greedy     dev [B][k_max+1] (out)
+ *   logits     dev [sum_b q_b][vocab] fp32 (out), rows packed in sequence order, or NULL
+ *   workspace  dev, >= mn_workspace_bytes(ctx, B, sum_b q_b, max_ctx), 256-byte aligned
+ * Arithmetic: fp32 residual stream, norm statistics, softmax and logits in both storage types;
+ * with MN_DT_BF16 the matrix products take bf16 inputs (round-to-nearest-even) with fp32
+ * accumulation. */
+mn_status mn_verify_forward(mn_ctx *ctx, const int32_t *last_tok, const int32_t *voted, const int32_t *spec_len,
+                            const int32_t *h_spec_len, int B, int k_max, int max_ctx, const mn_kv *kv,
+                            int32_t *greedy, float *logits, void *workspace, size_t workspace_bytes,
+                            int32_t *dev_status, void *stream);
+
+/* Acceptance and commit (section 2.1, greedy case; section 4).  a_b = length of the longest prefix
+ * of voted[b][0..k_b) equal to greedy[b][0..k_b).  The step emits the a_b + 1 tokens
+ * greedy[b][0..a_b] (the last one corrects the first mismatch, or is the bonus token when
+ * a_b == k_b).  The cache keeps the pending token and the a_b accepted drafts:
+ * ctx_lens[b] += a_b + 1; the k_b - a_b rejected tokens' entries fall outside ctx_lens and are
+ * thereby deleted (the accepted set is a prefix, so nothing moves).
+ *   accepted_len dev [B] (out)            out_tokens dev [B][k_max+1] (out, padded with -1)
+ *   n_out dev [B] (out) = a_b + 1         next_last_tok dev [B] (out) = greedy[b][a_b]
+ *   blocks_in_use dev [B] (out) = ceil(ctx_lens[b] / block_size) after the commit
+ * A sequence whose greedy[b][0] is -1 (made a no-op by mn_verify_forward) keeps its ctx_lens and
+ * reports accepted_len = 0, n_out = 0, next_last_tok = -1.  ctx may be NULL. */
+mn_status mn_accept_and_commit(mn_ctx *ctx, const int32_t *voted, const int32_t *greedy, const int32_t *spec_len,
+                               int B, int k_max, mn_kv *kv, int32_t *accepted_len, int32_t *out_tokens,
+                               int32_t *n_out, int32_t *next_last_tok, int32_t *blocks_in_use,
+                               int32_t *dev_status, void *stream);
+
+/* ---- component entry points (the kernels mn_verify_forward is made of, at their own shapes) -- */
+
+/* out[m][n] = sum_k a[m][k] * w[n][k] (+ bias[n]).  bf16 inputs, fp32 accumulation on MFMA,
+ * fp32 output.  a dev [M][K] bf16, w dev [N][K] bf16, bias dev [N] fp32 or NULL, out dev [M][N]
+ * fp32.  split_k in [0, MN_MAX_SPLIT_K]: 0 lets the library choose; with split_k > 1 `workspace`
+ * (dev, >= split_k*M*N*4 bytes, 256-byte aligned) holds the partial sums, which are added in a
+ * fixed order.  K must be a multiple of 64; M >= 0, N >= 1 arbitrary. */
+mn_status mn_gemm_bf16(mn_ctx *ctx, const void *a, const void *w, const float *bias, float *out, int M, int N, int K,
+                       int split_k, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Multi-token paged attention of one layer (section 4) on caller-supplied queries.  Rows are
+ * packed as in mn_verify_forward: sequence b has q_b = h_spec_len[b] + 1 query rows at positions
+ * ctx_b .. ctx_b + q_b - 1, whose K/V must already be in the cache.
+ *   q   dev [sum_b q_b][n_heads][head_dim]   in the model's storage type
+ *   out dev [sum_b q_b][n_heads*head_dim]    in the model's storage type
+ *   layer selects kv->k_layers[layer] / v_layers[layer].
+ * Uses the model's head counts and head_dim; workspace as for mn_verify_forward. */
+mn_status mn_attention(mn_ctx *ctx, const void *q, const int32_t *spec_len, const int32_t *h_spec_len, int B,
+                       int max_ctx, const mn_kv *kv, int layer, void *out, void *workspace, size_t workspace_bytes,
+                       int32_t *dev_status, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MINIONS_VERIFY_H */

@@ -1,0 +1,425 @@
+// C ABI of the verification step (declared in include/minions_verify.h): argument validation,
+// workspace layout and the launch sequence of one decoder forward.  Every step of the path runs
+// in the kernels of this library; this file only orders them on the caller's stream.
+#include "../../include/minions_verify.h"
+#include "launch.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+using namespace mn;
+
+struct mn_ctx {
+  mn_model_desc d;
+  const void *tok_emb, *pos_emb, *final_norm_g, *final_norm_b, *lm_head;
+  std::vector<const void*> ln1_g, ln1_b, wqkv, bqkv, wo, bo, ln2_g, ln2_b, w1, b1, w2, b2;
+  std::string err;
+};
+
+static std::string g_create_err;
+
+static mn_status fail(mn_ctx* c, mn_status s, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (c) c->err = buf;
+  else g_create_err = buf;
+  return s;
+}
+
+static mn_status hip_check(mn_ctx* c, const char* where) {
+  const hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return MN_OK;
+  return fail(c, MN_EHIP, "%s: %s", where, hipGetErrorString(e));
+}
+
+extern "C" const char* mn_status_str(mn_status s) {
+  switch (s) {
+    case MN_OK: return "MN_OK";
+    case MN_EINVAL: return "MN_EINVAL";
+    case MN_ENULL: return "MN_ENULL";
+    case MN_ESHAPE: return "MN_ESHAPE";
+    case MN_EUNSUPPORTED: return "MN_EUNSUPPORTED";
+    case MN_ECAPACITY: return "MN_ECAPACITY";
+    case MN_EWORKSPACE: return "MN_EWORKSPACE";
+    case MN_EHIP: return "MN_EHIP";
+  }
+  return "MN_?";
+}
+
+extern "C" const char* mn_last_error(const mn_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_err.c_str(); }
+
+static bool copy_ptrs(std::vector<const void*>& dst, const void* const* src, int n, bool required) {
+  dst.assign(n, nullptr);
+  if (!src) return !required;
+  for (int i = 0; i < n; ++i) {
+    dst[i] = src[i];
+    if (required && !src[i]) return false;
+  }
+  return true;
+}
+
+extern "C" mn_status mn_create(mn_ctx** out, const mn_model_desc* d, const mn_weights* w) {
+  if (!out) return fail(nullptr, MN_ENULL, "mn_create: out is NULL");
+  *out = nullptr;
+  if (!d || !w) return fail(nullptr, MN_ENULL, "mn_create: desc or weights is NULL");
+  if (d->arch != MN_ARCH_OPT && d->arch != MN_ARCH_LLAMA) return fail(nullptr, MN_EINVAL, "mn_create: arch %d", d->arch);
+  if (d->dtype != MN_DT_F32 && d->dtype != MN_DT_BF16) return fail(nullptr, MN_EINVAL, "mn_create: dtype %d", d->dtype);
+  if (d->n_layers < 0 || d->d_model <= 0 || d->n_heads <= 0 || d->n_kv_heads <= 0 || d->head_dim <= 0 || d->d_ffn <= 0 ||
+      d->vocab <= 0 || d->max_pos <= 0)
+    return fail(nullptr, MN_EINVAL, "mn_create: non-positive dimension");
+  if (d->n_heads % d->n_kv_heads) return fail(nullptr, MN_ESHAPE, "mn_create: n_heads %% n_kv_heads != 0");
+  if (d->arch == MN_ARCH_OPT && d->n_heads != d->n_kv_heads)
+    return fail(nullptr, MN_ESHAPE, "mn_create: OPT-style models have n_kv_heads == n_heads");
+  if (d->head_dim % 8 || 256 % d->head_dim)
+    return fail(nullptr, MN_EUNSUPPORTED, "mn_create: head_dim %d (supported: 8, 16, 32, 64, 128, 256)", d->head_dim);
+  if (d->d_model % 64 || d->d_model > 8192)
+    return fail(nullptr, MN_EUNSUPPORTED, "mn_create: d_model %d (must be a multiple of 64, at most 8192)", d->d_model);
+  if ((d->n_heads * d->head_dim) % 64 || d->d_ffn % 64)
+    return fail(nullptr, MN_EUNSUPPORTED, "mn_create: n_heads*head_dim and d_ffn must be multiples of 64");
+  if (!(d->norm_eps >= 0.f)) return fail(nullptr, MN_EINVAL, "mn_create: norm_eps");
+  if (d->arch == MN_ARCH_LLAMA && !(d->rope_base > 0.f)) return fail(nullptr, MN_EINVAL, "mn_create: rope_base");
+  if (!w->tok_emb || !w->lm_head || !w->final_norm_g) return fail(nullptr, MN_ENULL, "mn_create: tok_emb/lm_head/final_norm_g");
+  const bool opt = d->arch == MN_ARCH_OPT;
+  if (opt && (!w->pos_emb || !w->final_norm_b)) return fail(nullptr, MN_ENULL, "mn_create: pos_emb/final_norm_b (OPT)");
+  mn_ctx* c = new mn_ctx();
+  c->d = *d;
+  c->tok_emb = w->tok_emb;
+  c->pos_emb = opt ? w->pos_emb : nullptr;
+  c->final_norm_g = w->final_norm_g;
+  c->final_norm_b = opt ? w->final_norm_b : nullptr;
+  c->lm_head = w->lm_head;
+  const int L = d->n_layers;
+  bool good = copy_ptrs(c->ln1_g, w->ln1_g, L, true) && copy_ptrs(c->wqkv, w->wqkv, L, true) &&
+              copy_ptrs(c->wo, w->wo, L, true) && copy_ptrs(c->ln2_g, w->ln2_g, L, true) &&
+              copy_ptrs(c->w1, w->w1, L, true) && copy_ptrs(c->w2, w->w2, L, true) &&
+              copy_ptrs(c->ln1_b, w->ln1_b, L, opt) && copy_ptrs(c->ln2_b, w->ln2_b, L, opt) &&
+              copy_ptrs(c->bqkv, w->bqkv, L, opt) && copy_ptrs(c->bo, w->bo, L, opt) &&
+              copy_ptrs(c->b1, w->b1, L, opt) && copy_ptrs(c->b2, w->b2, L, opt);
+  if (!good) {
+    delete c;
+    return fail(nullptr, MN_ENULL, "mn_create: a per-layer parameter pointer is NULL");
+  }
+  if (!opt) {  // Llama-style models carry no biases and no norm shifts
+    for (auto* v : {&c->ln1_b, &c->ln2_b, &c->bqkv, &c->bo, &c->b1, &c->b2}) v->assign(L, nullptr);
+  }
+  *out = c;
+  return MN_OK;
+}
+
+extern "C" void mn_destroy(mn_ctx* ctx) { delete ctx; }
+
+// ---- workspace layout ---------------------------------------------------------------------------
+static size_t al(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Layout {
+  size_t row_seq, row_j, row_pos, row_tok, seq_row0, seq_ctx, seq_ok, rope_cos, rope_sin;
+  size_t x, h, q, attn, act, partials, logits, attn_scratch, total;
+  size_t partials_bytes, attn_scratch_bytes;
+};
+
+static Layout make_layout(const mn_model_desc& d, int B, int M, int max_ctx) {
+  Layout L{};
+  const size_t es = d.dtype == MN_DT_BF16 ? 2 : 4;
+  const size_t Mr = M > 0 ? M : 1;
+  size_t at = 0;
+  auto take = [&](size_t bytes) { size_t o = at; at += al(bytes); return o; };
+  L.row_seq = take(Mr * 4); L.row_j = take(Mr * 4); L.row_pos = take(Mr * 4); L.row_tok = take(Mr * 4);
+  L.seq_row0 = take(((size_t)B + 1) * 4); L.seq_ctx = take((size_t)B * 4 + 4); L.seq_ok = take((size_t)B * 4 + 4);
+  L.rope_cos = take(Mr * (d.head_dim / 2) * 4); L.rope_sin = take(Mr * (d.head_dim / 2) * 4);
+  L.x = take(Mr * d.d_model * 4);
+  L.h = take(Mr * d.d_model * es);
+  L.q = take(Mr * d.n_heads * d.head_dim * es);
+  L.attn = take(Mr * d.n_heads * d.head_dim * es);
+  L.act = take(Mr * d.d_ffn * es);
+  // partial sums of the widest projection at the largest split it can get
+  const int nqkv = (d.n_heads + 2 * d.n_kv_heads) * d.head_dim;
+  const int w1r = d.d_ffn * (d.arch == MN_ARCH_LLAMA ? 2 : 1);
+  size_t pmax = 0;
+  const int Ns[4] = {nqkv, d.d_model, w1r, d.d_model};
+  const int Ks[4] = {d.d_model, d.n_heads * d.head_dim, d.d_model, d.d_ffn};
+  for (int i = 0; i < 4; ++i) {
+    const size_t s = (size_t)gemm_pick_split(M, Ns[i], Ks[i], d.dtype);
+    const size_t b = s * Mr * Ns[i] * 4;
+    if (b > pmax) pmax = b;
+  }
+  L.partials_bytes = pmax;
+  L.partials = take(pmax);
+  L.logits = take(Mr * d.vocab * 4);
+  L.attn_scratch_bytes = attention_scratch_bytes(M, d.n_heads, d.head_dim, max_ctx, d.dtype);
+  L.attn_scratch = take(L.attn_scratch_bytes);
+  L.total = at;
+  return L;
+}
+
+extern "C" size_t mn_workspace_bytes(const mn_ctx* ctx, int B, int max_rows, int max_ctx) {
+  if (!ctx || B < 0 || B > MN_MAX_BATCH || max_rows < 0 || max_ctx < 0) return 0;
+  return make_layout(ctx->d, B, max_rows, max_ctx).total;
+}
+
+// ---- vote ---------------------------------------------------------------------------------------
+extern "C" mn_status mn_mv_vote(mn_ctx* ctx, const int32_t* drafts, const int32_t* spec_len, const float* ssm_w, int B,
+                                int n, int k_max, int mode, int32_t* voted, int32_t* voted_ssm, int32_t* dev_status,
+                                void* stream) {
+  if (B < 0 || B > MN_MAX_BATCH) return fail(ctx, MN_EINVAL, "mn_mv_vote: B = %d outside [0, %d]", B, MN_MAX_BATCH);
+  if (n < 1 || n > MN_MAX_DRAFTS) return fail(ctx, MN_EINVAL, "mn_mv_vote: n = %d outside [1, %d]", n, MN_MAX_DRAFTS);
+  if (k_max < 0) return fail(ctx, MN_EINVAL, "mn_mv_vote: k_max = %d", k_max);
+  if (mode != MN_VOTE_TREE && mode != MN_VOTE_COLUMN) return fail(ctx, MN_EINVAL, "mn_mv_vote: mode = %d", mode);
+  if (B == 0) return MN_OK;
+  if (!spec_len || !ssm_w || !voted_ssm) return fail(ctx, MN_ENULL, "mn_mv_vote: spec_len/ssm_w/voted_ssm is NULL");
+  if (k_max > 0 && (!drafts || !voted)) return fail(ctx, MN_ENULL, "mn_mv_vote: drafts/voted is NULL");
+  launch_vote(drafts, spec_len, ssm_w, B, n, k_max, mode, voted, voted_ssm, dev_status, (hipStream_t)stream);
+  return hip_check(ctx, "mn_mv_vote");
+}
+
+// ---- accept + commit ----------------------------------------------------------------------------
+extern "C" mn_status mn_accept_and_commit(mn_ctx* ctx, const int32_t* voted, const int32_t* greedy,
+                                          const int32_t* spec_len, int B, int k_max, mn_kv* kv, int32_t* accepted_len,
+                                          int32_t* out_tokens, int32_t* n_out, int32_t* next_last_tok,
+                                          int32_t* blocks_in_use, int32_t* dev_status, void* stream) {
+  if (B < 0 || B > MN_MAX_BATCH) return fail(ctx, MN_EINVAL, "mn_accept_and_commit: B = %d", B);
+  if (k_max < 0) return fail(ctx, MN_EINVAL, "mn_accept_and_commit: k_max = %d", k_max);
+  if (B == 0) return MN_OK;
+  if (!kv || !kv->ctx_lens) return fail(ctx, MN_ENULL, "mn_accept_and_commit: kv/ctx_lens is NULL");
+  if (kv->block_size <= 0 || kv->max_blocks_per_seq <= 0) return fail(ctx, MN_EINVAL, "mn_accept_and_commit: block geometry");
+  if (!greedy || !spec_len || !accepted_len || !out_tokens || !n_out || !next_last_tok || !blocks_in_use)
+    return fail(ctx, MN_ENULL, "mn_accept_and_commit: a required pointer is NULL");
+  if (k_max > 0 && !voted) return fail(ctx, MN_ENULL, "mn_accept_and_commit: voted is NULL");
+  launch_accept_commit(voted, greedy, spec_len, B, k_max, kv->ctx_lens, kv->block_size, kv->max_blocks_per_seq,
+                       accepted_len, out_tokens, n_out, next_last_tok, blocks_in_use, dev_status, (hipStream_t)stream);
+  return hip_check(ctx, "mn_accept_and_commit");
+}
+
+// ---- shared checks --------------------------------------------------------------------------------
+static mn_status check_kv(mn_ctx* c, const mn_kv* kv, int max_ctx, const char* who) {
+  if (!kv) return fail(c, MN_ENULL, "%s: kv is NULL", who);
+  if (!kv->k_layers || !kv->v_layers || !kv->block_tables || !kv->ctx_lens) return fail(c, MN_ENULL, "%s: kv member is NULL", who);
+  if (kv->block_size <= 0 || kv->num_blocks <= 0 || kv->max_blocks_per_seq <= 0)
+    return fail(c, MN_EINVAL, "%s: block_size/num_blocks/max_blocks_per_seq", who);
+  if ((long)max_ctx > (long)kv->max_blocks_per_seq * kv->block_size)
+    return fail(c, MN_ECAPACITY, "%s: max_ctx %d exceeds the block table (%d blocks of %d)", who, max_ctx,
+                kv->max_blocks_per_seq, kv->block_size);
+  if (max_ctx > c->d.max_pos) return fail(c, MN_ECAPACITY, "%s: max_ctx %d exceeds max_pos %d", who, max_ctx, c->d.max_pos);
+  return MN_OK;
+}
+
+static mn_status count_rows(mn_ctx* c, const int32_t* h_spec_len, int B, int k_max, int* M, int* max_q, const char* who) {
+  long m = 0;
+  int mq = 0;
+  for (int b = 0; b < B; ++b) {
+    const int k = h_spec_len[b];
+    if (k < 0 || k > k_max) return fail(c, MN_EINVAL, "%s: h_spec_len[%d] = %d outside [0, %d]", who, b, k, k_max);
+    m += k + 1;
+    if (k + 1 > mq) mq = k + 1;
+  }
+  if (m > (1 << 20)) return fail(c, MN_EINVAL, "%s: %ld rows", who, m);
+  *M = (int)m;
+  *max_q = mq;
+  return MN_OK;
+}
+
+struct Ws {
+  unsigned char* base;
+  Layout L;
+  template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(base + off); }
+};
+
+static RowInfo row_info(const Ws& w) {
+  RowInfo r;
+  r.row_seq = w.at<int32_t>(w.L.row_seq);
+  r.row_j = w.at<int32_t>(w.L.row_j);
+  r.row_pos = w.at<int32_t>(w.L.row_pos);
+  r.row_tok = w.at<int32_t>(w.L.row_tok);
+  r.seq_row0 = w.at<int32_t>(w.L.seq_row0);
+  r.seq_ctx = w.at<int32_t>(w.L.seq_ctx);
+  r.seq_ok = w.at<int32_t>(w.L.seq_ok);
+  return r;
+}
+
+static void run_prepare(mn_ctx* c, const Ws& w, const int32_t* last_tok, const int32_t* voted, const int32_t* spec_len,
+                        int B, int k_max, int M, const mn_kv* kv, bool tokens, int32_t* dev_status, hipStream_t st) {
+  PrepArgs p{};
+  p.last_tok = tokens ? last_tok : nullptr;
+  p.voted = voted;
+  p.spec_len = spec_len;
+  p.ctx_lens = kv->ctx_lens;
+  p.block_tables = kv->block_tables;
+  p.B = B; p.k_max = k_max; p.M = M;
+  p.vocab = tokens ? c->d.vocab : 0;
+  p.max_pos = c->d.max_pos;
+  p.block_size = kv->block_size; p.num_blocks = kv->num_blocks; p.max_blocks_per_seq = kv->max_blocks_per_seq;
+  p.rope_half = (tokens && c->d.arch == MN_ARCH_LLAMA) ? c->d.head_dim / 2 : 0;
+  p.rope_base = c->d.rope_base;
+  p.row_seq = w.at<int32_t>(w.L.row_seq); p.row_j = w.at<int32_t>(w.L.row_j);
+  p.row_pos = w.at<int32_t>(w.L.row_pos); p.row_tok = w.at<int32_t>(w.L.row_tok);
+  p.seq_row0 = w.at<int32_t>(w.L.seq_row0); p.seq_ctx = w.at<int32_t>(w.L.seq_ctx); p.seq_ok = w.at<int32_t>(w.L.seq_ok);
+  p.rope_cos = w.at<float>(w.L.rope_cos); p.rope_sin = w.at<float>(w.L.rope_sin);
+  p.dev_status = dev_status;
+  launch_prepare(p, st);
+}
+
+// ---- verify forward -------------------------------------------------------------------------------
+extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const int32_t* voted, const int32_t* spec_len,
+                                       const int32_t* h_spec_len, int B, int k_max, int max_ctx, const mn_kv* kv,
+                                       int32_t* greedy, float* logits, void* workspace, size_t workspace_bytes,
+                                       int32_t* dev_status, void* stream) {
+  const char* who = "mn_verify_forward";
+  if (!c) return MN_ENULL;
+  if (B < 0 || B > MN_MAX_BATCH) return fail(c, MN_EINVAL, "%s: B = %d outside [0, %d]", who, B, MN_MAX_BATCH);
+  if (k_max < 0) return fail(c, MN_EINVAL, "%s: k_max = %d", who, k_max);
+  if (max_ctx < 0) return fail(c, MN_EINVAL, "%s: max_ctx = %d", who, max_ctx);
+  if (B == 0) return MN_OK;
+  if (!last_tok || !spec_len || !h_spec_len || !greedy) return fail(c, MN_ENULL, "%s: a required pointer is NULL", who);
+  if (k_max > 0 && !voted) return fail(c, MN_ENULL, "%s: voted is NULL", who);
+  if (mn_status s = check_kv(c, kv, max_ctx, who)) return s;
+  int M = 0, max_q = 0;
+  if (mn_status s = count_rows(c, h_spec_len, B, k_max, &M, &max_q, who)) return s;
+  if (max_ctx < max_q) return fail(c, MN_EINVAL, "%s: max_ctx %d smaller than the longest scored run %d", who, max_ctx, max_q);
+  if (!workspace) return fail(c, MN_ENULL, "%s: workspace is NULL", who);
+  if ((uintptr_t)workspace & 255) return fail(c, MN_EWORKSPACE, "%s: workspace not 256-byte aligned", who);
+  const mn_model_desc& d = c->d;
+  Ws w{reinterpret_cast<unsigned char*>(workspace), make_layout(d, B, M, max_ctx)};
+  if (workspace_bytes < w.L.total)
+    return fail(c, MN_EWORKSPACE, "%s: workspace %zu bytes, need %zu", who, workspace_bytes, w.L.total);
+  for (int l = 0; l < d.n_layers; ++l)
+    if (!kv->k_layers[l] || !kv->v_layers[l]) return fail(c, MN_ENULL, "%s: kv layer %d pointer is NULL", who, l);
+
+  hipStream_t st = (hipStream_t)stream;
+  run_prepare(c, w, last_tok, voted, spec_len, B, k_max, M, kv, true, dev_status, st);
+  const RowInfo rows = row_info(w);
+  const bool llama = d.arch == MN_ARCH_LLAMA;
+  const int nqkv = (d.n_heads + 2 * d.n_kv_heads) * d.head_dim;
+  const int w1r = d.d_ffn * (llama ? 2 : 1);
+  const int hdim = d.n_heads * d.head_dim;
+  float* x = w.at<float>(w.L.x);
+  void* h = w.at<void>(w.L.h);
+  float* part = w.at<float>(w.L.partials);
+
+  // partial sums of the previous projection, folded into the next norm
+  const float* pend = nullptr;
+  int pend_n = 0;
+  const float* pend_bias = nullptr;
+
+  auto norm = [&](const float* gain, const float* shift, bool embed) {
+    NormArgs n{};
+    n.x = x; n.partials = pend; n.n_partials = pend_n; n.bias = pend_bias;
+    n.tok_emb = embed ? c->tok_emb : nullptr;
+    n.pos_emb = embed ? c->pos_emb : nullptr;
+    n.row_tok = rows.row_tok; n.row_pos = rows.row_pos;
+    n.gain = gain; n.shift = shift; n.eps = d.norm_eps; n.h = h; n.M = M; n.d = d.d_model; n.dtype = d.dtype;
+    launch_norm(n, st);
+    pend = nullptr; pend_n = 0; pend_bias = nullptr;
+  };
+  auto gemm = [&](const void* a, const void* wt, float* out, int N, int K, int split) {
+    GemmArgs g{};
+    g.a = a; g.w = wt; g.out = out; g.bias = nullptr; g.M = M; g.N = N; g.K = K; g.split_k = split; g.dtype = d.dtype;
+    launch_gemm(g, st);
+  };
+
+  for (int l = 0; l < d.n_layers; ++l) {
+    norm((const float*)c->ln1_g[l], (const float*)c->ln1_b[l], l == 0);
+    int s = gemm_pick_split(M, nqkv, d.d_model, d.dtype);
+    gemm(h, c->wqkv[l], part, nqkv, d.d_model, s);
+    RopeAppendArgs r{};
+    r.qkv = part; r.n_partials = s; r.bias = (const float*)c->bqkv[l];
+    r.rope_cos = llama ? w.at<float>(w.L.rope_cos) : nullptr;
+    r.rope_sin = llama ? w.at<float>(w.L.rope_sin) : nullptr;
+    r.rows = rows;
+    r.kv = KvView{kv->k_layers[l], kv->v_layers[l], kv->block_tables, kv->block_size, kv->num_blocks, kv->max_blocks_per_seq};
+    r.q = w.at<void>(w.L.q);
+    r.M = M; r.H = d.n_heads; r.Hkv = d.n_kv_heads; r.hd = d.head_dim; r.dtype = d.dtype;
+    launch_rope_append(r, st);
+    AttnArgs at{};
+    at.q = r.q; at.out = w.at<void>(w.L.attn); at.rows = rows; at.kv = r.kv;
+    at.B = B; at.M = M; at.H = d.n_heads; at.Hkv = d.n_kv_heads; at.hd = d.head_dim; at.dtype = d.dtype;
+    at.max_ctx = max_ctx; at.max_q = max_q;
+    at.scratch = w.at<float>(w.L.attn_scratch); at.scratch_bytes = w.L.attn_scratch_bytes;
+    launch_attention(at, st);
+    s = gemm_pick_split(M, d.d_model, hdim, d.dtype);
+    gemm(at.out, c->wo[l], part, d.d_model, hdim, s);
+    pend = part; pend_n = s; pend_bias = (const float*)c->bo[l];
+    norm((const float*)c->ln2_g[l], (const float*)c->ln2_b[l], false);
+    s = gemm_pick_split(M, w1r, d.d_model, d.dtype);
+    gemm(h, c->w1[l], part, w1r, d.d_model, s);
+    ActArgs ac{};
+    ac.partials = part; ac.n_partials = s; ac.bias = (const float*)c->b1[l]; ac.act = w.at<void>(w.L.act);
+    ac.M = M; ac.F = d.d_ffn; ac.swiglu = llama ? 1 : 0; ac.dtype = d.dtype;
+    launch_act(ac, st);
+    s = gemm_pick_split(M, d.d_model, d.d_ffn, d.dtype);
+    gemm(ac.act, c->w2[l], part, d.d_model, d.d_ffn, s);
+    pend = part; pend_n = s; pend_bias = (const float*)c->b2[l];
+  }
+  norm((const float*)c->final_norm_g, (const float*)c->final_norm_b, d.n_layers == 0);
+  float* lg = logits ? logits : w.at<float>(w.L.logits);
+  gemm(h, c->lm_head, lg, d.vocab, d.d_model, 1);
+  launch_argmax_rows(lg, M, d.vocab, rows, k_max, greedy, B, st);
+  return hip_check(c, who);
+}
+
+// ---- component entry points -----------------------------------------------------------------------
+extern "C" mn_status mn_gemm_bf16(mn_ctx* c, const void* a, const void* w, const float* bias, float* out, int M, int N,
+                                  int K, int split_k, void* workspace, size_t workspace_bytes, void* stream) {
+  const char* who = "mn_gemm_bf16";
+  if (M < 0 || N < 1 || K < 64 || K % 64) return fail(c, MN_ESHAPE, "%s: M=%d N=%d K=%d (K must be a positive multiple of 64)", who, M, N, K);
+  if (split_k < 0 || split_k > MN_MAX_SPLIT_K) return fail(c, MN_EINVAL, "%s: split_k = %d", who, split_k);
+  if (M == 0) return MN_OK;
+  if (!a || !w || !out) return fail(c, MN_ENULL, "%s: a/w/out is NULL", who);
+  int s = split_k ? split_k : gemm_pick_split(M, N, K, MN_DT_BF16);
+  if (s > K / 64) s = K / 64;
+  hipStream_t st = (hipStream_t)stream;
+  GemmArgs g{};
+  g.a = a; g.w = w; g.bias = bias; g.M = M; g.N = N; g.K = K; g.split_k = s; g.dtype = MN_DT_BF16;
+  if (s == 1) {
+    g.out = out;
+    launch_gemm(g, st);
+  } else {
+    const size_t need = (size_t)s * M * N * 4;
+    if (!workspace) return fail(c, MN_ENULL, "%s: workspace is NULL (split_k = %d)", who, s);
+    if ((uintptr_t)workspace & 255) return fail(c, MN_EWORKSPACE, "%s: workspace not 256-byte aligned", who);
+    if (workspace_bytes < need) return fail(c, MN_EWORKSPACE, "%s: workspace %zu bytes, need %zu", who, workspace_bytes, need);
+    g.out = reinterpret_cast<float*>(workspace);
+    launch_gemm(g, st);
+    launch_reduce_partials(g.out, s, (size_t)M * N, out, (size_t)M * N, st);
+  }
+  return hip_check(c, who);
+}
+
+extern "C" mn_status mn_attention(mn_ctx* c, const void* q, const int32_t* spec_len, const int32_t* h_spec_len, int B,
+                                  int max_ctx, const mn_kv* kv, int layer, void* out, void* workspace,
+                                  size_t workspace_bytes, int32_t* dev_status, void* stream) {
+  const char* who = "mn_attention";
+  if (!c) return MN_ENULL;
+  if (B < 0 || B > MN_MAX_BATCH) return fail(c, MN_EINVAL, "%s: B = %d", who, B);
+  if (max_ctx < 0) return fail(c, MN_EINVAL, "%s: max_ctx = %d", who, max_ctx);
+  if (B == 0) return MN_OK;
+  if (!q || !spec_len || !h_spec_len || !out) return fail(c, MN_ENULL, "%s: a required pointer is NULL", who);
+  if (mn_status s = check_kv(c, kv, max_ctx, who)) return s;
+  if (layer < 0 || layer >= (c->d.n_layers > 0 ? c->d.n_layers : 1)) return fail(c, MN_EINVAL, "%s: layer %d", who, layer);
+  if (!kv->k_layers[layer] || !kv->v_layers[layer]) return fail(c, MN_ENULL, "%s: kv layer pointer is NULL", who);
+  int k_max = 0;
+  for (int b = 0; b < B; ++b) if (h_spec_len[b] > k_max) k_max = h_spec_len[b];
+  int M = 0, max_q = 0;
+  if (mn_status s = count_rows(c, h_spec_len, B, k_max, &M, &max_q, who)) return s;
+  if (max_ctx < max_q) return fail(c, MN_EINVAL, "%s: max_ctx %d smaller than the longest scored run %d", who, max_ctx, max_q);
+  if (!workspace) return fail(c, MN_ENULL, "%s: workspace is NULL", who);
+  if ((uintptr_t)workspace & 255) return fail(c, MN_EWORKSPACE, "%s: workspace not 256-byte aligned", who);
+  const mn_model_desc& d = c->d;
+  Ws w{reinterpret_cast<unsigned char*>(workspace), make_layout(d, B, M, max_ctx)};
+  if (workspace_bytes < w.L.total) return fail(c, MN_EWORKSPACE, "%s: workspace %zu bytes, need %zu", who, workspace_bytes, w.L.total);
+  hipStream_t st = (hipStream_t)stream;
+  // row bookkeeping only (no tokens): positions are ctx_b + j, the rows' K/V are already cached
+  run_prepare(c, w, nullptr, nullptr, spec_len, B, k_max, M, kv, false, dev_status, st);
+  AttnArgs at{};
+  at.q = q; at.out = out; at.rows = row_info(w);
+  at.kv = KvView{kv->k_layers[layer], kv->v_layers[layer], kv->block_tables, kv->block_size, kv->num_blocks, kv->max_blocks_per_seq};
+  at.B = B; at.M = M; at.H = d.n_heads; at.Hkv = d.n_kv_heads; at.hd = d.head_dim; at.dtype = d.dtype;
+  at.max_ctx = max_ctx; at.max_q = max_q;
+  at.scratch = w.at<float>(w.L.attn_scratch); at.scratch_bytes = w.L.attn_scratch_bytes;
+  launch_attention(at, st);
+  return hip_check(c, who);
+}

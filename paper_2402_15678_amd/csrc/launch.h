@@ -1,0 +1,96 @@
+// Internal launchers: one per kernel family.  Host-side shape checks happen in api.hip; the
+// launchers assume validated arguments and only translate them into grids.
+#pragma once
+#include "common.h"
+
+namespace mn {
+
+// ---- vote_accept.hip ----
+void launch_vote(const int32_t* drafts, const int32_t* spec_len, const float* ssm_w, int B, int n, int k_max, int mode,
+                 int32_t* voted, int32_t* voted_ssm, int32_t* dev_status, hipStream_t st);
+void launch_accept_commit(const int32_t* voted, const int32_t* greedy, const int32_t* spec_len, int B, int k_max,
+                          int32_t* ctx_lens, int block_size, int max_blocks_per_seq, int32_t* accepted_len,
+                          int32_t* out_tokens, int32_t* n_out, int32_t* next_last_tok, int32_t* blocks_in_use,
+                          int32_t* dev_status, hipStream_t st);
+
+// ---- rows.hip ----
+struct PrepArgs {
+  const int32_t *last_tok, *voted, *spec_len, *ctx_lens, *block_tables;
+  int B, k_max, M, vocab, max_pos, block_size, num_blocks, max_blocks_per_seq;
+  int rope_half;     // head_dim/2 for rotary models, 0 otherwise
+  float rope_base;
+  int32_t *row_seq, *row_j, *row_pos, *row_tok, *seq_row0, *seq_ctx, *seq_ok;
+  float *rope_cos, *rope_sin;  // [M][rope_half]
+  int32_t* dev_status;
+};
+void launch_prepare(const PrepArgs& a, hipStream_t st);
+
+struct NormArgs {
+  // source of the row: either the residual stream x (+ partial sums + bias), or the embeddings
+  float* x;               // [M][d] residual stream, updated in place
+  const float* partials;  // [S][M][d] or null
+  int n_partials;
+  const float* bias;      // [d] or null
+  const void* tok_emb;    // when non-null the row is tok_emb[row_tok] (+ pos_emb[row_pos])
+  const void* pos_emb;
+  const int32_t *row_tok, *row_pos;
+  const float *gain, *shift;  // shift null => RMSNorm
+  float eps;
+  void* h;                // [M][d] normalised output in the storage type
+  int M, d, dtype;
+};
+void launch_norm(const NormArgs& a, hipStream_t st);
+
+struct RopeAppendArgs {
+  const float* qkv;  // [S][M][(H+2Hkv)*hd] partial sums
+  int n_partials;
+  const float* bias;  // [(H+2Hkv)*hd] or null
+  const float *rope_cos, *rope_sin;  // [M][hd/2] or null (no rotation)
+  RowInfo rows;
+  KvView kv;
+  void* q;  // [M][H][hd] storage type
+  int M, H, Hkv, hd, dtype;
+};
+void launch_rope_append(const RopeAppendArgs& a, hipStream_t st);
+
+// act[m][f] = relu(sum_s p[s][m][f] + b[f])  or  silu(gate) * up with gate = column f, up = column F + f
+struct ActArgs {
+  const float* partials;  // [S][M][ncols]
+  int n_partials;
+  const float* bias;
+  void* act;  // [M][F] storage type
+  int M, F, swiglu, dtype;
+};
+void launch_act(const ActArgs& a, hipStream_t st);
+
+void launch_argmax_rows(const float* logits, int M, int V, const RowInfo& rows, int k_max, int32_t* greedy, int B,
+                        hipStream_t st);
+
+// ---- gemm.hip ----
+struct GemmArgs {
+  const void* a;  // [M][K] storage type
+  const void* w;  // [N][K] storage type
+  float* out;     // [S][M][N] fp32 partial sums (S = split_k); bias added to split 0 when given
+  const float* bias;
+  int M, N, K, split_k, dtype;
+};
+int gemm_pick_split(int M, int N, int K, int dtype);
+void launch_gemm(const GemmArgs& a, hipStream_t st);
+void launch_reduce_partials(const float* partials, int S, size_t stride, float* out, size_t n, hipStream_t st);
+
+// ---- attention.hip ----
+struct AttnArgs {
+  const void* q;  // [M][H][hd] storage type
+  void* out;      // [M][H*hd] storage type
+  RowInfo rows;
+  KvView kv;
+  int B, M, H, Hkv, hd, dtype, max_ctx;
+  int max_q;       // largest number of rows of one sequence (host knowledge)
+  float* scratch;  // split-KV partials
+  size_t scratch_bytes;
+};
+size_t attention_scratch_bytes(int M, int H, int hd, int max_ctx, int dtype);
+bool attention_mfma_supported(int H, int Hkv, int hd, int block_size, int dtype);
+void launch_attention(const AttnArgs& a, hipStream_t st);
+
+}  // namespace mn

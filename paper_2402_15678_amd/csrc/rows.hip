@@ -1,0 +1,367 @@
+// Row-wise kernels of the verification forward: row bookkeeping, embedding + LayerNorm/RMSNorm with
+// the residual update folded in, rotary embedding + tentative KV append, FFN activation, vocabulary
+// argmax.  The paper (section 4) only states that every scored token's cache entry is addressed
+// by a logical block id and an offset; the decoder body is the standard pre-norm one.
+#include "launch.h"
+#include "../../include/minions_verify.h"
+
+namespace mn {
+
+// ------------------------------------------------------------------------------------------
+// prepare: validate the batch on the device and lay out the packed rows
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) prepare_kernel(PrepArgs a) {
+  __shared__ int32_t s_row0[MN_MAX_BATCH + 1];
+  __shared__ int32_t s_ok[MN_MAX_BATCH];
+  __shared__ int s_bad;
+  const int tid = threadIdx.x;
+  if (tid == 0) s_bad = 0;
+  __syncthreads();
+  // pass 1: per-sequence validation
+  for (int b = tid; b < a.B; b += blockDim.x) {
+    const int k = a.spec_len[b];
+    const int ctx = a.ctx_lens[b];
+    int ok = 1;
+    int flags = 0;
+    if (k < 0 || k > a.k_max) { ok = 0; flags |= MN_DEV_SPEC_LEN; }
+    s_row0[b + 1] = (k < 0 || k > a.k_max) ? 1 : k + 1;
+    if (ok) {
+      const long need = (long)ctx + k + 1;
+      if (ctx < 0 || need > (long)a.max_blocks_per_seq * a.block_size) { ok = 0; flags |= MN_DEV_BLOCK_TABLE; }
+      if (ok && need > a.max_pos) { ok = 0; flags |= MN_DEV_TOKEN; }
+      if (ok) {
+        const int nb = (int)((need + a.block_size - 1) / a.block_size);
+        for (int i = 0; i < nb; ++i) {
+          const int pb = a.block_tables[(size_t)b * a.max_blocks_per_seq + i];
+          if (pb < 0 || pb >= a.num_blocks) { ok = 0; flags |= MN_DEV_BLOCK_TABLE; break; }
+        }
+      }
+      if (ok && a.last_tok) {
+        for (int j = 0; j <= k; ++j) {
+          const int tok = (j == 0) ? a.last_tok[b] : a.voted[(size_t)b * a.k_max + j - 1];
+          if (tok < 0 || tok >= a.vocab) { ok = 0; flags |= MN_DEV_TOKEN; break; }
+        }
+      }
+    }
+    s_ok[b] = ok;
+    if (flags) {
+      if (a.dev_status) atomicOr(a.dev_status, flags);
+      if (flags & MN_DEV_SPEC_LEN) atomicOr(&s_bad, 1);
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    s_row0[0] = 0;
+    for (int b = 0; b < a.B; ++b) s_row0[b + 1] += s_row0[b];
+    if (s_row0[a.B] != a.M) {
+      s_bad = 1;
+      if (a.dev_status) atomicOr(a.dev_status, MN_DEV_SPEC_LEN);
+    }
+  }
+  __syncthreads();
+  const bool bad = s_bad != 0;
+  // a device spec_len that disagrees with the launch geometry disables the whole batch
+  if (bad) {
+    for (int b = tid; b <= a.B; b += blockDim.x) a.seq_row0[b] = 0;
+    for (int b = tid; b < a.B; b += blockDim.x) { a.seq_ctx[b] = 0; a.seq_ok[b] = 0; }
+    for (int m = tid; m < a.M; m += blockDim.x) { a.row_seq[m] = 0; a.row_j[m] = 0; a.row_pos[m] = -1; a.row_tok[m] = 0; }
+    return;
+  }
+  for (int b = tid; b <= a.B; b += blockDim.x) a.seq_row0[b] = s_row0[b];
+  for (int b = tid; b < a.B; b += blockDim.x) {
+    const int ok = s_ok[b];
+    const int ctx = ok ? a.ctx_lens[b] : 0;
+    a.seq_ctx[b] = ctx;
+    a.seq_ok[b] = ok;
+    const int r0 = s_row0[b], q = s_row0[b + 1] - s_row0[b];
+    for (int j = 0; j < q; ++j) {
+      a.row_seq[r0 + j] = b;
+      a.row_j[r0 + j] = j;
+      a.row_pos[r0 + j] = ok ? ctx + j : -1;
+      a.row_tok[r0 + j] = (ok && a.last_tok) ? ((j == 0) ? a.last_tok[b] : a.voted[(size_t)b * a.k_max + j - 1]) : 0;
+    }
+  }
+}
+
+// cos/sin of the rotary angles, evaluated in double once per step and shared by all layers.
+__global__ void rope_table_kernel(const int32_t* __restrict__ row_pos, int half, float base, float* __restrict__ c,
+                                  float* __restrict__ s) {
+  const int m = blockIdx.x;
+  const int p = row_pos[m] < 0 ? 0 : row_pos[m];
+  for (int i = threadIdx.x; i < half; i += blockDim.x) {
+    const double inv = pow((double)base, -2.0 * (double)i / (double)(2 * half));
+    const double ang = (double)p * inv;
+    c[(size_t)m * half + i] = (float)cos(ang);
+    s[(size_t)m * half + i] = (float)sin(ang);
+  }
+}
+
+void launch_prepare(const PrepArgs& a, hipStream_t st) {
+  prepare_kernel<<<1, 256, 0, st>>>(a);
+  if (a.rope_half > 0 && a.M > 0) rope_table_kernel<<<a.M, 64, 0, st>>>(a.row_pos, a.rope_half, a.rope_base, a.rope_cos, a.rope_sin);
+}
+
+// ------------------------------------------------------------------------------------------
+// norm: x += sum of partials + bias (or x = embedding), then LayerNorm / RMSNorm -> h
+// ------------------------------------------------------------------------------------------
+constexpr int NORM_THREADS = 256;
+constexpr int NORM_MAX_VEC = 8;  // float4 per thread: d <= 256*8*4 = 8192
+
+template <typename T>
+__device__ __forceinline__ float4 load4(const T* p);
+template <>
+__device__ __forceinline__ float4 load4<float>(const float* p) { return *reinterpret_cast<const float4*>(p); }
+template <>
+__device__ __forceinline__ float4 load4<bf16_t>(const bf16_t* p) {
+  const uint2 u = *reinterpret_cast<const uint2*>(p);
+  return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u), __uint_as_float(u.y << 16),
+                     __uint_as_float(u.y & 0xFFFF0000u));
+}
+template <typename T>
+__device__ __forceinline__ void store4(T* p, float4 v);
+template <>
+__device__ __forceinline__ void store4<float>(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+template <>
+__device__ __forceinline__ void store4<bf16_t>(bf16_t* p, float4 v) {
+  *reinterpret_cast<uint2*>(p) = make_uint2(pack2bf(v.x, v.y), pack2bf(v.z, v.w));
+}
+
+template <typename T>
+__global__ void __launch_bounds__(NORM_THREADS) norm_kernel(NormArgs a) {
+  __shared__ float red[NORM_THREADS / 64];
+  const int m = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int d = a.d;
+  const int nvec = d >> 2;
+  float4 v[NORM_MAX_VEC];
+  float* xr = a.x + (size_t)m * d;
+  const bool embed = a.tok_emb != nullptr;
+  const T* te = embed ? reinterpret_cast<const T*>(a.tok_emb) + (size_t)a.row_tok[m] * d : nullptr;
+  const int pos = (embed && a.pos_emb) ? (a.row_pos[m] < 0 ? 0 : a.row_pos[m]) : 0;
+  const T* pe = (embed && a.pos_emb) ? reinterpret_cast<const T*>(a.pos_emb) + (size_t)pos * d : nullptr;
+  float sum = 0.f;
+#pragma unroll
+  for (int it = 0; it < NORM_MAX_VEC; ++it) {
+    const int i4 = it * NORM_THREADS + tid;
+    float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i4 < nvec) {
+      const int e = i4 << 2;
+      if (embed) {
+        r = load4<T>(te + e);
+        if (pe) {
+          const float4 p = load4<T>(pe + e);
+          r.x += p.x; r.y += p.y; r.z += p.z; r.w += p.w;
+        }
+      } else {
+        r = *reinterpret_cast<const float4*>(xr + e);
+        if (a.partials) {
+          // fixed summation order: residual, then partial 0, 1, ..., then the bias
+          for (int s = 0; s < a.n_partials; ++s) {
+            const float4 p = *reinterpret_cast<const float4*>(a.partials + ((size_t)s * a.M + m) * d + e);
+            r.x += p.x; r.y += p.y; r.z += p.z; r.w += p.w;
+          }
+        }
+        if (a.bias) {
+          const float4 p = *reinterpret_cast<const float4*>(a.bias + e);
+          r.x += p.x; r.y += p.y; r.z += p.z; r.w += p.w;
+        }
+      }
+      if (embed || a.partials || a.bias) *reinterpret_cast<float4*>(xr + e) = r;
+      sum += (r.x + r.y) + (r.z + r.w);
+    }
+    v[it] = r;
+  }
+  const float inv_d = 1.f / (float)d;
+  float mean = 0.f;
+  if (a.shift) mean = block_sum<NORM_THREADS / 64>(sum, red) * inv_d;
+  float sq = 0.f;
+#pragma unroll
+  for (int it = 0; it < NORM_MAX_VEC; ++it) {
+    const int i4 = it * NORM_THREADS + tid;
+    if (i4 < nvec) {
+      const float4 r = v[it];
+      const float a0 = r.x - mean, a1 = r.y - mean, a2 = r.z - mean, a3 = r.w - mean;
+      sq += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
+    }
+  }
+  const float var = block_sum<NORM_THREADS / 64>(sq, red) * inv_d;
+  const float rstd = 1.f / sqrtf(var + a.eps);
+  T* hr = reinterpret_cast<T*>(a.h) + (size_t)m * d;
+#pragma unroll
+  for (int it = 0; it < NORM_MAX_VEC; ++it) {
+    const int i4 = it * NORM_THREADS + tid;
+    if (i4 < nvec) {
+      const int e = i4 << 2;
+      const float4 r = v[it];
+      const float4 g = *reinterpret_cast<const float4*>(a.gain + e);
+      float4 o = make_float4((r.x - mean) * rstd * g.x, (r.y - mean) * rstd * g.y, (r.z - mean) * rstd * g.z,
+                             (r.w - mean) * rstd * g.w);
+      if (a.shift) {
+        const float4 sh = *reinterpret_cast<const float4*>(a.shift + e);
+        o.x += sh.x; o.y += sh.y; o.z += sh.z; o.w += sh.w;
+      }
+      store4<T>(hr + e, o);
+    }
+  }
+}
+
+void launch_norm(const NormArgs& a, hipStream_t st) {
+  if (a.M <= 0) return;
+  if (a.dtype == MN_DT_BF16) norm_kernel<bf16_t><<<a.M, NORM_THREADS, 0, st>>>(a);
+  else norm_kernel<float><<<a.M, NORM_THREADS, 0, st>>>(a);
+}
+
+// ------------------------------------------------------------------------------------------
+// rotary embedding + tentative KV append
+// ------------------------------------------------------------------------------------------
+// grid (H + 2 Hkv, M), hd/2 threads: thread t owns the pair (t, t + hd/2) of one head of one row.
+template <typename T>
+__global__ void rope_append_kernel(RopeAppendArgs a) {
+  const int m = blockIdx.y;
+  const int head = blockIdx.x;
+  const int t = threadIdx.x;
+  const int hd = a.hd, half = hd >> 1;
+  const int ncols = (a.H + 2 * a.Hkv) * hd;
+  const int c0 = head * hd + t, c1 = c0 + half;
+  float v0 = 0.f, v1 = 0.f;
+  for (int s = 0; s < a.n_partials; ++s) {
+    const float* p = a.qkv + ((size_t)s * a.M + m) * ncols;
+    v0 += p[c0];
+    v1 += p[c1];
+  }
+  if (a.bias) { v0 += a.bias[c0]; v1 += a.bias[c1]; }
+  const bool is_v = head >= a.H + a.Hkv;
+  if (a.rope_cos && !is_v) {
+    const float c = a.rope_cos[(size_t)m * half + t], s = a.rope_sin[(size_t)m * half + t];
+    const float r0 = v0 * c - v1 * s;
+    const float r1 = v1 * c + v0 * s;
+    v0 = r0; v1 = r1;
+  }
+  if (head < a.H) {
+    T* q = reinterpret_cast<T*>(a.q) + ((size_t)m * a.H + head) * hd;
+    Store<T>::store(q + t, v0);
+    Store<T>::store(q + t + half, v1);
+    return;
+  }
+  const int pos = a.rows.row_pos[m];
+  if (pos < 0) return;  // disabled sequence: nothing is written to the cache
+  const int b = a.rows.row_seq[m];
+  const int bs = a.kv.block_size;
+  const int pb = a.kv.block_tables[(size_t)b * a.kv.max_blocks_per_seq + pos / bs];
+  const int off = pos % bs;
+  if (!is_v) {
+    const int kh = head - a.H;
+    T* base = reinterpret_cast<T*>(a.kv.k) + ((size_t)pb * a.Hkv + kh) * (size_t)hd * bs;
+    // [hd/8][bs][8]
+    Store<T>::store(base + ((size_t)(t >> 3) * bs + off) * 8 + (t & 7), v0);
+    const int t1 = t + half;
+    Store<T>::store(base + ((size_t)(t1 >> 3) * bs + off) * 8 + (t1 & 7), v1);
+  } else {
+    const int vh = head - a.H - a.Hkv;
+    T* base = reinterpret_cast<T*>(a.kv.v) + ((size_t)pb * a.Hkv + vh) * (size_t)hd * bs;
+    // [hd][bs]
+    Store<T>::store(base + (size_t)t * bs + off, v0);
+    Store<T>::store(base + (size_t)(t + half) * bs + off, v1);
+  }
+}
+
+void launch_rope_append(const RopeAppendArgs& a, hipStream_t st) {
+  if (a.M <= 0) return;
+  dim3 grid(a.H + 2 * a.Hkv, a.M);
+  if (a.dtype == MN_DT_BF16) rope_append_kernel<bf16_t><<<grid, a.hd / 2, 0, st>>>(a);
+  else rope_append_kernel<float><<<grid, a.hd / 2, 0, st>>>(a);
+}
+
+// ------------------------------------------------------------------------------------------
+// FFN activation on the first projection's partial sums
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) act_kernel(ActArgs a) {
+  const size_t nvec = (size_t)a.M * (a.F >> 2);
+  const int ncols = a.swiglu ? 2 * a.F : a.F;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += (size_t)gridDim.x * blockDim.x) {
+    const int m = (int)(i / (a.F >> 2));
+    const int f = (int)(i % (a.F >> 2)) << 2;
+    float4 g = make_float4(0.f, 0.f, 0.f, 0.f), u = g;
+    for (int s = 0; s < a.n_partials; ++s) {
+      const float* p = a.partials + ((size_t)s * a.M + m) * ncols;
+      const float4 x = *reinterpret_cast<const float4*>(p + f);
+      g.x += x.x; g.y += x.y; g.z += x.z; g.w += x.w;
+      if (a.swiglu) {
+        const float4 y = *reinterpret_cast<const float4*>(p + a.F + f);
+        u.x += y.x; u.y += y.y; u.z += y.z; u.w += y.w;
+      }
+    }
+    float4 o;
+    if (a.swiglu) {
+      o.x = g.x / (1.f + __expf(-g.x)) * u.x;
+      o.y = g.y / (1.f + __expf(-g.y)) * u.y;
+      o.z = g.z / (1.f + __expf(-g.z)) * u.z;
+      o.w = g.w / (1.f + __expf(-g.w)) * u.w;
+    } else {
+      if (a.bias) {
+        const float4 bb = *reinterpret_cast<const float4*>(a.bias + f);
+        g.x += bb.x; g.y += bb.y; g.z += bb.z; g.w += bb.w;
+      }
+      o = make_float4(fmaxf(g.x, 0.f), fmaxf(g.y, 0.f), fmaxf(g.z, 0.f), fmaxf(g.w, 0.f));
+    }
+    store4<T>(reinterpret_cast<T*>(a.act) + (size_t)m * a.F + f, o);
+  }
+}
+
+void launch_act(const ActArgs& a, hipStream_t st) {
+  if (a.M <= 0) return;
+  const size_t nvec = (size_t)a.M * (a.F >> 2);
+  int blocks = (int)((nvec + 255) / 256);
+  if (blocks > 4096) blocks = 4096;
+  if (a.dtype == MN_DT_BF16) act_kernel<bf16_t><<<blocks, 256, 0, st>>>(a);
+  else act_kernel<float><<<blocks, 256, 0, st>>>(a);
+}
+
+// ------------------------------------------------------------------------------------------
+// vocabulary argmax: lowest id attaining the row maximum; NaN never wins
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void arg_better(float& bv, int& bi, float v, int i) {
+  if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+}
+
+__global__ void __launch_bounds__(256) argmax_rows_kernel(const float* __restrict__ logits, int M, int V, RowInfo rows,
+                                                          int k_max, int32_t* __restrict__ greedy, int B) {
+  __shared__ float sv[4];
+  __shared__ int si[4];
+  const int tid = threadIdx.x;
+  if ((int)blockIdx.x >= M) {
+    // padding blocks: one per sequence
+    const int b = blockIdx.x - M;
+    const int q = rows.seq_ok[b] ? rows.seq_row0[b + 1] - rows.seq_row0[b] : 0;
+    for (int j = q + tid; j <= k_max; j += blockDim.x) greedy[(size_t)b * (k_max + 1) + j] = -1;
+    return;
+  }
+  const int m = blockIdx.x;
+  const float* r = logits + (size_t)m * V;
+  float bv = -INFINITY;
+  int bi = 0x7FFFFFFF;
+  for (int i = tid; i < V; i += blockDim.x) arg_better(bv, bi, r[i], i);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ov = __shfl_xor(bv, o, 64);
+    const int oi = __shfl_xor(bi, o, 64);
+    arg_better(bv, bi, ov, oi);
+  }
+  if ((tid & 63) == 0) { sv[tid >> 6] = bv; si[tid >> 6] = bi; }
+  __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < 4; ++w) arg_better(bv, bi, sv[w], si[w]);
+    if (bi >= V) bi = 0;
+    const int b = rows.row_seq[m];
+    if (rows.seq_ok[b]) greedy[(size_t)b * (k_max + 1) + rows.row_j[m]] = bi;
+  }
+}
+
+void launch_argmax_rows(const float* logits, int M, int V, const RowInfo& rows, int k_max, int32_t* greedy, int B,
+                        hipStream_t st) {
+  if (M + B <= 0) return;
+  argmax_rows_kernel<<<M + B, 256, 0, st>>>(logits, M, V, rows, k_max, greedy, B);
+}
+
+}  // namespace mn

@@ -1,0 +1,202 @@
+"""Device-side plumbing for tests and benchmarks: PyTorch tensors own the HBM buffers, the HIP
+library (through ``binding``) does all the computing.  Nothing here implements any step of the
+verification path."""
+from __future__ import annotations
+
+import ctypes as C
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as B
+from . import synth
+
+
+def _dev() -> torch.device:
+    if not torch.cuda.is_available():
+        raise RuntimeError("a GPU is required: the verification path has no CPU fallback")
+    return torch.device("cuda:0")
+
+
+def to_device(a: np.ndarray, dtype: int) -> torch.Tensor:
+    """Host values (fp32, already representable in the storage type) -> device tensor in the storage type."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if dtype == synth.DT_BF16:
+        bits = synth.f32_to_bf16_bits(a).view(np.int16)
+        return torch.from_numpy(bits).to(_dev()).view(torch.bfloat16)
+    return torch.from_numpy(a).to(_dev())
+
+
+def stream_ptr() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+class DeviceModel:
+    """Weights on the device + the library context."""
+
+    def __init__(self, desc: synth.ModelDesc, tensors: Dict[str, object]):
+        self.desc = desc
+        self.t = tensors  # keeps the tensors alive
+        L = desc.n_layers
+        layers: List[Dict[str, torch.Tensor]] = tensors["layers"]
+        self._arrays = {}
+        w = B.Weights()
+        p = lambda t: t.data_ptr() if t is not None else None
+        w.tok_emb = p(tensors["tok_emb"])
+        w.pos_emb = p(tensors.get("pos_emb"))
+        w.final_norm_g = p(tensors["final_norm_g"])
+        w.final_norm_b = p(tensors.get("final_norm_b"))
+        w.lm_head = p(tensors["lm_head"])
+        for key in ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2"):
+            arr = B.ptr_array([p(layers[l].get(key)) for l in range(L)])
+            self._arrays[key] = arr
+            setattr(w, key, C.cast(arr, C.POINTER(C.c_void_p)))
+        self.cdesc = B.ModelDesc(desc.arch, desc.dtype, desc.n_layers, desc.d_model, desc.n_heads, desc.n_kv_heads,
+                                 desc.head_dim, desc.d_ffn, desc.vocab, desc.max_pos, desc.norm_eps, desc.rope_base)
+        self.ctx = B.mn_create(self.cdesc, w)
+
+    def close(self) -> None:
+        if self.ctx:
+            B.mn_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @classmethod
+    def from_host(cls, desc: synth.ModelDesc, W: Dict[str, object]) -> "DeviceModel":
+        mats = ("tok_emb", "pos_emb", "lm_head", "wqkv", "wo", "w1", "w2")
+        conv = lambda k, a: to_device(a, desc.dtype if k in mats else synth.DT_F32)
+        t: Dict[str, object] = {k: conv(k, v) for k, v in W.items() if k != "layers"}
+        t["layers"] = [{k: conv(k, v) for k, v in Lw.items()} for Lw in W["layers"]]
+        return cls(desc, t)
+
+    @classmethod
+    def random_on_device(cls, desc: synth.ModelDesc, seed: int, std: float = 0.02) -> "DeviceModel":
+        """Random-init weights generated directly in HBM (full-size models never visit the host)."""
+        dev = _dev()
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(int(seed))
+        st = torch.bfloat16 if desc.dtype == synth.DT_BF16 else torch.float32
+
+        def mat(rows, cols):
+            out = torch.empty((rows, cols), dtype=st, device=dev)
+            chunk = max(1, (1 << 28) // cols)  # fp32 staging of at most 1 GiB
+            for r in range(0, rows, chunk):
+                n = min(chunk, rows - r)
+                out[r:r + n] = (torch.randn((n, cols), generator=gen, device=dev, dtype=torch.float32) * std).to(st)
+            return out
+
+        vec = lambda n, mean=0.0: torch.randn((n,), generator=gen, device=dev, dtype=torch.float32) * std + mean
+        d, hd = desc.d_model, desc.head_dim
+        t: Dict[str, object] = {"tok_emb": mat(desc.vocab, d), "lm_head": mat(desc.vocab, d), "final_norm_g": vec(d, 1.0)}
+        opt = desc.arch == synth.ARCH_OPT
+        if opt:
+            t["pos_emb"] = mat(desc.max_pos, d)
+            t["final_norm_b"] = vec(d)
+        layers = []
+        for _ in range(desc.n_layers):
+            Lw = {"wqkv": mat(desc.n_qkv, d), "wo": mat(d, desc.n_heads * hd), "w1": mat(desc.w1_rows, d),
+                  "w2": mat(d, desc.d_ffn), "ln1_g": vec(d, 1.0), "ln2_g": vec(d, 1.0)}
+            if opt:
+                Lw.update({"ln1_b": vec(d), "ln2_b": vec(d), "bqkv": vec(desc.n_qkv), "bo": vec(d),
+                           "b1": vec(desc.d_ffn), "b2": vec(d)})
+            layers.append(Lw)
+        t["layers"] = layers
+        return cls(desc, t)
+
+
+class DeviceKV:
+    """Paged KV cache on the device."""
+
+    def __init__(self, desc: synth.ModelDesc, block_size: int, num_blocks: int, block_tables: np.ndarray,
+                 ctx_lens: Sequence[int], k_pages: List[torch.Tensor], v_pages: List[torch.Tensor]):
+        self.desc = desc
+        self.block_size, self.num_blocks = block_size, num_blocks
+        self.k_pages, self.v_pages = k_pages, v_pages
+        self.block_tables = torch.from_numpy(np.ascontiguousarray(block_tables, np.int32)).to(_dev())
+        self.ctx_lens = torch.tensor(np.asarray(ctx_lens, np.int32), device=_dev())
+        self.max_blocks_per_seq = int(block_tables.shape[1])
+        self._k = B.ptr_array([t.data_ptr() for t in k_pages])
+        self._v = B.ptr_array([t.data_ptr() for t in v_pages])
+        self.c = B.KV(C.cast(self._k, C.POINTER(C.c_void_p)), C.cast(self._v, C.POINTER(C.c_void_p)), block_size,
+                      num_blocks, self.max_blocks_per_seq, self.block_tables.data_ptr(), self.ctx_lens.data_ptr())
+
+    @classmethod
+    def from_host(cls, desc: synth.ModelDesc, kv: synth.PagedKV) -> "DeviceKV":
+        ks = [to_device(a, desc.dtype) for a in kv.k_pages]
+        vs = [to_device(a, desc.dtype) for a in kv.v_pages]
+        return cls(desc, kv.block_size, kv.num_blocks, kv.block_tables, kv.ctx_lens, ks, vs)
+
+    @classmethod
+    def random_on_device(cls, desc: synth.ModelDesc, ctx_lens: Sequence[int], spec_lens: Sequence[int], seed: int,
+                         block_size: int = 16, scatter: bool = True, std: float = 1.0) -> "DeviceKV":
+        bt, nb = synth.make_block_tables(ctx_lens, spec_lens, block_size, seed, scatter)
+        dev = _dev()
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(int(seed) + 77)
+        st = torch.bfloat16 if desc.dtype == synth.DT_BF16 else torch.float32
+        hk, hd = desc.n_kv_heads, desc.head_dim
+        ks, vs = [], []
+        for _ in range(desc.n_layers):
+            ks.append((torch.randn((nb, hk, hd // 8, block_size, 8), generator=gen, device=dev) * std).to(st))
+            vs.append((torch.randn((nb, hk, hd, block_size), generator=gen, device=dev) * std).to(st))
+        return cls(desc, block_size, nb, bt, ctx_lens, ks, vs)
+
+    def download(self, layer: int):
+        """K and V pages of one layer as fp32 numpy arrays (layout unchanged)."""
+        return (self.k_pages[layer].float().cpu().numpy(), self.v_pages[layer].float().cpu().numpy())
+
+
+class VerifySession:
+    """Output buffers + workspace for batches of up to B sequences / max_rows scored positions."""
+
+    def __init__(self, model: DeviceModel, kv: DeviceKV, B_: int, k_max: int, n_drafts: int, max_ctx: int,
+                 max_rows: Optional[int] = None, want_logits: bool = False):
+        dev = _dev()
+        self.model, self.kv = model, kv
+        self.B, self.k_max, self.n, self.max_ctx = B_, k_max, n_drafts, max_ctx
+        self.max_rows = max_rows if max_rows is not None else B_ * (k_max + 1)
+        i32 = lambda *s: torch.full(s, -7, dtype=torch.int32, device=dev)
+        self.voted = i32(B_, max(1, k_max))
+        self.voted_ssm = i32(B_)
+        self.greedy = i32(B_, k_max + 1)
+        self.accepted_len, self.n_out, self.next_last_tok, self.blocks_in_use = i32(B_), i32(B_), i32(B_), i32(B_)
+        self.out_tokens = i32(B_, k_max + 1)
+        self.dev_status = torch.zeros((1,), dtype=torch.int32, device=dev)
+        self.logits = (torch.empty((self.max_rows, model.desc.vocab), dtype=torch.float32, device=dev)
+                       if want_logits else None)
+        self.ws_bytes = B.mn_workspace_bytes(model.ctx, B_, self.max_rows, max_ctx)
+        if self.ws_bytes == 0:
+            raise RuntimeError("mn_workspace_bytes rejected the shape")
+        self.workspace = torch.empty((self.ws_bytes,), dtype=torch.uint8, device=dev)
+
+    def vote(self, drafts: torch.Tensor, spec_len: torch.Tensor, ssm_w: torch.Tensor, mode: int = 0) -> None:
+        B.mn_mv_vote(self.model.ctx, drafts.data_ptr(), spec_len.data_ptr(), ssm_w.data_ptr(), self.B, self.n,
+                     self.k_max, mode, self.voted.data_ptr(), self.voted_ssm.data_ptr(), self.dev_status.data_ptr(),
+                     stream_ptr())
+
+    def forward(self, last_tok: torch.Tensor, spec_len: torch.Tensor, h_spec_len: Sequence[int],
+                voted: Optional[torch.Tensor] = None) -> None:
+        v = self.voted if voted is None else voted
+        B.mn_verify_forward(self.model.ctx, last_tok.data_ptr(), v.data_ptr(), spec_len.data_ptr(),
+                            B.host_i32(h_spec_len), self.B, self.k_max, self.max_ctx, self.kv.c,
+                            self.greedy.data_ptr(), self.logits.data_ptr() if self.logits is not None else None,
+                            self.workspace.data_ptr(), self.ws_bytes, self.dev_status.data_ptr(), stream_ptr())
+
+    def accept(self, spec_len: torch.Tensor, voted: Optional[torch.Tensor] = None) -> None:
+        v = self.voted if voted is None else voted
+        B.mn_accept_and_commit(self.model.ctx, v.data_ptr(), self.greedy.data_ptr(), spec_len.data_ptr(), self.B,
+                               self.k_max, self.kv.c, self.accepted_len.data_ptr(), self.out_tokens.data_ptr(),
+                               self.n_out.data_ptr(), self.next_last_tok.data_ptr(), self.blocks_in_use.data_ptr(),
+                               self.dev_status.data_ptr(), stream_ptr())
+
+    def step(self, last_tok, drafts, spec_len, h_spec_len, ssm_w, mode: int = 0) -> None:
+        """vote -> verify forward -> accept + commit, back to back on the current stream."""
+        self.vote(drafts, spec_len, ssm_w, mode)
+        self.forward(last_tok, spec_len, h_spec_len)
+        self.accept(spec_len)

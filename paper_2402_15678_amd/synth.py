@@ -21,6 +21,7 @@ Conventions
 """
 from __future__ import annotations
 
+import concurrent.futures
 import dataclasses
 from dataclasses import dataclass
 from typing import Dict, List, Optional, Sequence, Tuple
@@ -127,12 +128,33 @@ def storage_round(x: np.ndarray, dtype: int) -> np.ndarray:
     return x
 
 
-def _normal(gen: np.random.Generator, shape, std: float, mean: float = 0.0) -> np.ndarray:
-    out = gen.standard_normal(size=shape, dtype=np.float32)
-    out *= np.float32(std)
-    if mean != 0.0:
-        out += np.float32(mean)
-    return out
+_CHUNK = 1 << 22      # elements per independently seeded chunk (fixed: it is part of the recipe)
+_THREADS = 8
+
+
+def _normal(key: Sequence[int], shape, std: float, mean: float = 0.0, dtype: int = DT_F32) -> np.ndarray:
+    """N(mean, std) tensor for the stream ``key`` = (seed, ids...), rounded to the storage type.  The
+    tensor is cut into fixed-size chunks, each drawn from its own Philox stream (key + chunk index), so
+    the values do not depend on how many threads fill it."""
+    n = int(np.prod(shape))
+    out = np.empty((n,), np.float32)
+
+    def fill(c: int) -> None:
+        lo, hi = c * _CHUNK, min(n, (c + 1) * _CHUNK)
+        v = stream(*key, c).standard_normal(size=hi - lo, dtype=np.float32)
+        v *= np.float32(std)
+        if mean != 0.0:
+            v += np.float32(mean)
+        out[lo:hi] = storage_round(v, dtype)
+
+    n_chunks = (n + _CHUNK - 1) // _CHUNK
+    if n_chunks <= 1:
+        for c in range(n_chunks):
+            fill(c)
+    else:
+        with concurrent.futures.ThreadPoolExecutor(_THREADS) as ex:
+            list(ex.map(fill, range(n_chunks)))
+    return out.reshape(shape)
 
 
 # --------------------------------------------------------------------------
@@ -153,30 +175,31 @@ def make_weights(desc: ModelDesc, seed: int, std: float = 0.02) -> Dict[str, obj
              "layers": [ {per-layer tensors} ]}.
     """
     d, hd = desc.d_model, desc.head_dim
-    g = lambda *ids: stream(seed, 100, *ids)
+    mat = lambda shape, *ids: _normal((seed, 100, *ids), shape, std, 0.0, desc.dtype)
+    vec = lambda shape, mean, *ids: _normal((seed, 100, *ids), shape, std, mean, DT_F32)
     W: Dict[str, object] = {}
-    W["tok_emb"] = storage_round(_normal(g(0), (desc.vocab, d), std), desc.dtype)
-    W["lm_head"] = storage_round(_normal(g(1), (desc.vocab, d), std), desc.dtype)
-    W["final_norm_g"] = _normal(g(2), (d,), std, 1.0)
+    W["tok_emb"] = mat((desc.vocab, d), 0)
+    W["lm_head"] = mat((desc.vocab, d), 1)
+    W["final_norm_g"] = vec((d,), 1.0, 2)
     if desc.arch == ARCH_OPT:
-        W["pos_emb"] = storage_round(_normal(g(3), (desc.max_pos, d), std), desc.dtype)
-        W["final_norm_b"] = _normal(g(4), (d,), std)
+        W["pos_emb"] = mat((desc.max_pos, d), 3)
+        W["final_norm_b"] = vec((d,), 0.0, 4)
     layers = []
     for l in range(desc.n_layers):
         L: Dict[str, np.ndarray] = {}
-        L["wqkv"] = storage_round(_normal(g(10, l), (desc.n_qkv, d), std), desc.dtype)
-        L["wo"] = storage_round(_normal(g(11, l), (d, desc.n_heads * hd), std), desc.dtype)
-        L["w1"] = storage_round(_normal(g(12, l), (desc.w1_rows, d), std), desc.dtype)
-        L["w2"] = storage_round(_normal(g(13, l), (d, desc.d_ffn), std), desc.dtype)
-        L["ln1_g"] = _normal(g(14, l), (d,), std, 1.0)
-        L["ln2_g"] = _normal(g(15, l), (d,), std, 1.0)
+        L["wqkv"] = mat((desc.n_qkv, d), 10, l)
+        L["wo"] = mat((d, desc.n_heads * hd), 11, l)
+        L["w1"] = mat((desc.w1_rows, d), 12, l)
+        L["w2"] = mat((d, desc.d_ffn), 13, l)
+        L["ln1_g"] = vec((d,), 1.0, 14, l)
+        L["ln2_g"] = vec((d,), 1.0, 15, l)
         if desc.arch == ARCH_OPT:
-            L["ln1_b"] = _normal(g(16, l), (d,), std)
-            L["ln2_b"] = _normal(g(17, l), (d,), std)
-            L["bqkv"] = _normal(g(18, l), (desc.n_qkv,), std)
-            L["bo"] = _normal(g(19, l), (d,), std)
-            L["b1"] = _normal(g(20, l), (desc.d_ffn,), std)
-            L["b2"] = _normal(g(21, l), (d,), std)
+            L["ln1_b"] = vec((d,), 0.0, 16, l)
+            L["ln2_b"] = vec((d,), 0.0, 17, l)
+            L["bqkv"] = vec((desc.n_qkv,), 0.0, 18, l)
+            L["bo"] = vec((d,), 0.0, 19, l)
+            L["b1"] = vec((desc.d_ffn,), 0.0, 20, l)
+            L["b2"] = vec((d,), 0.0, 21, l)
         layers.append(L)
     W["layers"] = layers
     return W
@@ -231,8 +254,8 @@ def make_paged_kv(desc: ModelDesc, ctx_lens: Sequence[int], spec_lens: Sequence[
     ks, vs = [], []
     for l in range(desc.n_layers):
         if fill:
-            k = storage_round(_normal(stream(seed, 201, l), (nb, hk, hd // 8, block_size, 8), std), desc.dtype)
-            v = storage_round(_normal(stream(seed, 202, l), (nb, hk, hd, block_size), std), desc.dtype)
+            k = _normal((seed, 201, l), (nb, hk, hd // 8, block_size, 8), std, 0.0, desc.dtype)
+            v = _normal((seed, 202, l), (nb, hk, hd, block_size), std, 0.0, desc.dtype)
         else:
             k = np.zeros((nb, hk, hd // 8, block_size, 8), np.float32)
             v = np.zeros((nb, hk, hd, block_size), np.float32)

@@ -1,0 +1,172 @@
+"""End-to-end GPU parity of the verification step (vote -> verify forward -> accept + commit) against
+the CPU oracle, through the C ABI: the tiny fp32 configuration in full, and full-width, layer-reduced
+versions of the bf16 configurations (the oracle cannot run 40/80 layers in test time)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import minions_oracle as orc
+from paper_2402_15678_amd import synth
+from tests import util
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hb():
+    from paper_2402_15678_amd import binding, harness
+    return harness, binding
+
+
+def _i32(a):
+    return torch.tensor(np.asarray(a, np.int32), dtype=torch.int32, device="cuda:0")
+
+
+def _compare_cache(desc, kvd, kvh_tables, block_size, caches, tol):
+    """Committed cache rows [0, ctx_b) on the device against the oracle's cache."""
+    worst = 0.0
+    for l in range(desc.n_layers):
+        kp, vp = kvd.download(l)
+        img = synth.PagedKV(block_size, kp.shape[0], kvh_tables.shape[1], kvh_tables, None, {l: kp}, {l: vp})
+        for b, c in enumerate(caches):
+            K, V = synth.gather_sequence_kv(img, l, b, c.ctx)
+            worst = max(worst, np.abs(K - c.K[l]).max(), np.abs(V - c.V[l]).max())
+    assert worst < tol, worst
+    return worst
+
+
+def test_config0_tiny_opt_fp32_end_to_end(hb):
+    harness, binding = hb
+    wl = synth.WORKLOADS[0]
+    desc = wl.desc
+    W = synth.make_weights(desc, wl.seed)
+    model = harness.DeviceModel.from_host(desc, W)
+    prompt = synth.stream(wl.seed, 400).integers(0, desc.vocab, size=64).astype(np.int32)
+    # empty cache with room for the prompt and the scored positions
+    kvh = synth.make_paged_kv(desc, [0], [64 + 4 + 1], wl.seed, scatter=True, fill=True)
+    kvd = harness.DeviceKV.from_host(desc, kvh)
+    # ---- prefill through the library: ctx = 0, 64 rows, causal among them ----
+    pre = harness.VerifySession(model, kvd, 1, 63, 1, 64, want_logits=True)
+    pre.forward(_i32(prompt[:1]), _i32([63]), [63], voted=_i32(prompt[None, 1:]))
+    torch.cuda.synchronize()
+    assert pre.dev_status.item() == 0
+    cache = orc.SeqCache(desc.n_layers, desc.n_kv_heads, desc.head_dim)
+    want_pre = orc.decoder_step(desc, W, [prompt.tolist()], [cache])[0]
+    got_pre = pre.logits.cpu().numpy()
+    assert np.abs(got_pre - want_pre).max() < 1e-4
+    assert np.array_equal(pre.greedy.cpu().numpy()[0], orc.greedy_tokens(want_pre))
+    kvd.ctx_lens.fill_(64)                                    # the caller commits the prompt
+    last = int(orc.greedy_tokens(want_pre)[-1])
+    # ---- drafts: greedy continuation / corrupted / random ----
+    (greedy,), (margin,) = util.greedy_continuations(desc, W, [cache], [last], [4])
+    assert margin > 2e-4
+    drafts, info = synth.drafts_config0(greedy[:4], desc.vocab, synth.stream(wl.seed, 401))
+    ssm_w = np.ones(3, np.float32)
+    want = orc.verify_step(desc, W, [cache], [last], drafts[None], [4], ssm_w)
+    ses = harness.VerifySession(model, kvd, 1, 4, 3, 64 + 5, want_logits=True)
+    ses.step(_i32([last]), _i32(drafts[None]), _i32([4]), [4], torch.ones(3, device="cuda:0"))
+    torch.cuda.synchronize()
+    assert ses.dev_status.item() == 0
+    assert np.array_equal(ses.voted.cpu().numpy(), want["voted"])
+    assert ses.voted_ssm.cpu().tolist() == want["voted_ssm"].tolist()
+    assert np.abs(ses.logits.cpu().numpy() - want["logits"][0]).max() < 1e-4
+    assert np.array_equal(ses.greedy.cpu().numpy(), want["greedy"])
+    assert ses.accepted_len.cpu().tolist() == want["accepted_len"].tolist()
+    assert np.array_equal(ses.out_tokens.cpu().numpy(), want["out_tokens"])
+    assert ses.n_out.cpu().tolist() == want["n_out"].tolist()
+    assert ses.next_last_tok.cpu().tolist() == want["next_last_tok"].tolist()
+    assert kvd.ctx_lens.cpu().tolist() == want["ctx_lens"].tolist()
+    assert ses.blocks_in_use.cpu().tolist() == want["blocks_in_use"].tolist()
+    _compare_cache(desc, kvd, kvh.block_tables, 16, [cache], 1e-4)
+
+
+def _reduced_case(hb, wl, n_layers, B, n_cand, ctx_override=None, k_override=None):
+    harness, binding = hb
+    desc = wl.desc.with_layers(n_layers)
+    tol = util.TOL[desc.dtype]
+    W = synth.make_weights(desc, wl.seed)
+    W64 = util.weights_f64(W)
+    model = harness.DeviceModel.from_host(desc, W)
+    g = synth.stream(wl.seed, 500)
+    wl_b = synth.Workload(wl.name, desc, B, wl.ctx_lo, wl.ctx_hi, wl.k_lo, wl.k_hi, wl.n_drafts, wl.p_corrupt, seed=wl.seed)
+    ctx = np.asarray(ctx_override, np.int32) if ctx_override is not None else synth.draw_ctx_lens(wl_b)
+    ks = np.asarray(k_override, np.int32) if k_override is not None else synth.draw_spec_lens(wl_b)
+    k_max = int(ks.max())
+    kvh = synth.make_paged_kv(desc, ctx, ks, wl.seed, scatter=True)
+    kvd = harness.DeviceKV.from_host(desc, kvh)
+    caches = util.oracle_caches(desc, kvh)
+    last, greedy, margin = util.pick_decisive_last_tokens(desc, W64, caches, ks, desc.vocab, g, tol, n_cand)
+    per = [synth.drafts_corrupted(greedy[b][:ks[b]], wl.n_drafts, wl.p_corrupt, desc.vocab, g) if ks[b] > 0
+           else np.zeros((wl.n_drafts, 0), np.int32) for b in range(B)]
+    drafts = synth.pack_drafts(per, k_max)
+    ssm_w = np.ones(wl.n_drafts, np.float32)
+    want = orc.verify_step(desc, W64, caches, last, drafts, ks, ssm_w)
+    M = int((ks + 1).sum())
+    ses = harness.VerifySession(model, kvd, B, k_max, wl.n_drafts, int((ctx + ks + 1).max()), max_rows=M, want_logits=True)
+    ses.step(_i32(last), _i32(drafts), _i32(ks), ks.tolist(), torch.ones(wl.n_drafts, device="cuda:0"))
+    torch.cuda.synchronize()
+    assert ses.dev_status.item() == 0
+    # votes: bit-exact
+    assert np.array_equal(ses.voted.cpu().numpy()[:, :k_max], want["voted"])
+    assert ses.voted_ssm.cpu().tolist() == want["voted_ssm"].tolist()
+    # logits within tolerance, element by element
+    got_logits = ses.logits.cpu().numpy()
+    want_logits = np.concatenate(want["logits"])
+    err = np.abs(got_logits - want_logits).max()
+    assert err < tol, err
+    # tokens: bit-exact wherever the oracle's margin is decisive; near ties must stay inside the tie set
+    got_g = ses.greedy.cpu().numpy()
+    row = 0
+    decisive_seqs = 0
+    for b in range(B):
+        mg = orc.top1_margin(want["logits"][b])
+        a = int(want["accepted_len"][b])
+        for j in range(ks[b] + 1):
+            if mg[j] >= 2 * tol:
+                assert got_g[b, j] == want["greedy"][b, j], (b, j)
+            else:
+                assert util.near_tie_ok(want["logits"][b][j], int(got_g[b, j]), tol), (b, j)
+        assert (got_g[b, ks[b] + 1:] == -1).all()
+        if (mg[:a + 1] >= 2 * tol).all():
+            decisive_seqs += 1
+            assert ses.accepted_len[b].item() == a
+            assert ses.n_out[b].item() == a + 1
+            assert np.array_equal(ses.out_tokens[b].cpu().numpy(), want["out_tokens"][b])
+            assert ses.next_last_tok[b].item() == want["next_last_tok"][b]
+            assert kvd.ctx_lens[b].item() == want["ctx_lens"][b]
+            assert ses.blocks_in_use[b].item() == want["blocks_in_use"][b]
+        row += ks[b] + 1
+    assert decisive_seqs >= (3 * B) // 4, (decisive_seqs, B)
+    # committed cache rows of the decisive sequences
+    ok_caches = [c if (orc.top1_margin(want["logits"][b])[:int(want["accepted_len"][b]) + 1] >= 2 * tol).all() else
+                 None for b, c in enumerate(caches)]
+    for l in range(desc.n_layers):
+        kp, vp = kvd.download(l)
+        img = synth.PagedKV(16, kp.shape[0], kvh.block_tables.shape[1], kvh.block_tables, None, {l: kp}, {l: vp})
+        for b, c in enumerate(ok_caches):
+            if c is None:
+                continue
+            K, V = synth.gather_sequence_kv(img, l, b, c.ctx)
+            assert np.abs(K - c.K[l]).max() < tol and np.abs(V - c.V[l]).max() < tol
+    return err, decisive_seqs
+
+
+def test_opt13b_width_two_layers(hb):
+    # full OPT-13B width and batch shape, 2 of 40 layers
+    err, dec = _reduced_case(hb, synth.WORKLOADS[1], 2, 8, 4)
+    print("opt13b-width L=2 max |dlogit| = %.2e, decisive %d/8" % (err, dec))
+
+
+def test_llama70b_width_one_layer_b16_k8(hb):
+    # full Llama-2-70B width, B=16, k=8, ctx=1024, 1 of 80 layers
+    err, dec = _reduced_case(hb, synth.WORKLOADS[2], 1, 16, 4)
+    print("llama70b-width L=1 max |dlogit| = %.2e, decisive %d/16" % (err, dec))
+
+
+def test_llama70b_width_ragged_paged(hb):
+    # ragged contexts and speculation lengths (the paged, adaptive-k configuration), reduced batch
+    wl = synth.WORKLOADS[3]
+    ctx = [256, 2048, 700, 1023, 257, 1500, 16, 333, 1024, 15, 640, 1999]
+    ks = [1, 16, 5, 9, 16, 2, 7, 12, 3, 1, 10, 4]
+    err, dec = _reduced_case(hb, wl, 1, 12, 3, ctx_override=ctx, k_override=ks)
+    print("llama70b-width ragged max |dlogit| = %.2e, decisive %d/12" % (err, dec))
