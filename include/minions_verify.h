@@ -160,9 +160,12 @@ mn_status mn_mv_vote(mn_ctx *ctx, const int32_t *drafts, const int32_t *spec_len
  *   greedy     dev [B][k_max+1] (out)
  *   logits     dev [sum_b q_b][vocab] fp32 (out), rows packed in sequence order, or NULL
  *   workspace  dev, >= mn_workspace_bytes(ctx, B, sum_b q_b, max_ctx), 256-byte aligned
- * Arithmetic: fp32 residual stream, norm statistics, softmax and logits in both storage types;
- * with MN_DT_BF16 the matrix products take bf16 inputs (round-to-nearest-even) with fp32
- * accumulation. */
+ * Arithmetic: fp32 residual stream, norm statistics, softmax and logits in both storage types.
+ * With MN_DT_BF16 the weights and cache entries are bf16 in memory and are widened exactly to
+ * fp16 in registers; the activations fed to the matrix products (norm outputs, queries, softmax
+ * probabilities, attention outputs, FFN activations) are rounded to fp16 (round-to-nearest-even)
+ * and the products run on the fp16 MFMA with fp32 accumulation.  New K/V rows are rounded to
+ * bf16 when they are written to the cache. */
 mn_status mn_verify_forward(mn_ctx *ctx, const int32_t *last_tok, const int32_t *voted, const int32_t *spec_len,
                             const int32_t *h_spec_len, int B, int k_max, int max_ctx, const mn_kv *kv,
                             int32_t *greedy, float *logits, void *workspace, size_t workspace_bytes,
@@ -186,19 +189,20 @@ mn_status mn_accept_and_commit(mn_ctx *ctx, const int32_t *voted, const int32_t 
 
 /* ---- component entry points (the kernels mn_verify_forward is made of, at their own shapes) -- */
 
-/* out[m][n] = sum_k a[m][k] * w[n][k] (+ bias[n]).  bf16 inputs, fp32 accumulation on MFMA,
- * fp32 output.  a dev [M][K] bf16, w dev [N][K] bf16, bias dev [N] fp32 or NULL, out dev [M][N]
+/* The projection GEMM of a bf16 model: out[m][n] = sum_k a[m][k] * w[n][k] (+ bias[n]).
+ * a dev [M][K] fp16 (the activation type of bf16 models), w dev [N][K] bf16 (widened exactly to
+ * fp16 in registers), fp16 MFMA with fp32 accumulation, bias dev [N] fp32 or NULL, out dev [M][N]
  * fp32.  split_k in [0, MN_MAX_SPLIT_K]: 0 lets the library choose; with split_k > 1 `workspace`
  * (dev, >= split_k*M*N*4 bytes, 256-byte aligned) holds the partial sums, which are added in a
  * fixed order.  K must be a multiple of 64; M >= 0, N >= 1 arbitrary. */
-mn_status mn_gemm_bf16(mn_ctx *ctx, const void *a, const void *w, const float *bias, float *out, int M, int N, int K,
+mn_status mn_proj_gemm(mn_ctx *ctx, const void *a, const void *w, const float *bias, float *out, int M, int N, int K,
                        int split_k, void *workspace, size_t workspace_bytes, void *stream);
 
 /* Multi-token paged attention of one layer (section 4) on caller-supplied queries.  Rows are
  * packed as in mn_verify_forward: sequence b has q_b = h_spec_len[b] + 1 query rows at positions
  * ctx_b .. ctx_b + q_b - 1, whose K/V must already be in the cache.
- *   q   dev [sum_b q_b][n_heads][head_dim]   in the model's storage type
- *   out dev [sum_b q_b][n_heads*head_dim]    in the model's storage type
+ *   q   dev [sum_b q_b][n_heads][head_dim]   fp32 in fp32 models, fp16 in bf16 models
+ *   out dev [sum_b q_b][n_heads*head_dim]    same type as q
  *   layer selects kv->k_layers[layer] / v_layers[layer].
  * Uses the model's head counts and head_dim; workspace as for mn_verify_forward. */
 mn_status mn_attention(mn_ctx *ctx, const void *q, const int32_t *spec_len, const int32_t *h_spec_len, int B,

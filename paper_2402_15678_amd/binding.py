@@ -21,7 +21,7 @@ MN_DEV_BLOCK_TABLE, MN_DEV_SPEC_LEN, MN_DEV_TOKEN, MN_DEV_DRAFTS = 1, 2, 4, 8
 MN_MAX_DRAFTS, MN_MAX_BATCH, MN_MAX_SPLIT_K = 64, 4096, 16
 
 EXPORTS = ("mn_create", "mn_destroy", "mn_last_error", "mn_status_str", "mn_workspace_bytes", "mn_mv_vote",
-           "mn_verify_forward", "mn_accept_and_commit", "mn_gemm_bf16", "mn_attention")
+           "mn_verify_forward", "mn_accept_and_commit", "mn_proj_gemm", "mn_attention")
 
 
 class ModelDesc(C.Structure):
@@ -67,8 +67,8 @@ def _load() -> C.CDLL:
     lib.mn_verify_forward.argtypes = [vp, vp, vp, vp, C.POINTER(C.c_int32), i32, i32, i32, C.POINTER(KV), vp, vp, vp, sz, vp, vp]
     lib.mn_accept_and_commit.restype = i32
     lib.mn_accept_and_commit.argtypes = [vp, vp, vp, vp, i32, i32, C.POINTER(KV), vp, vp, vp, vp, vp, vp, vp]
-    lib.mn_gemm_bf16.restype = i32
-    lib.mn_gemm_bf16.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, sz, vp]
+    lib.mn_proj_gemm.restype = i32
+    lib.mn_proj_gemm.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, sz, vp]
     lib.mn_attention.restype = i32
     lib.mn_attention.argtypes = [vp, vp, vp, C.POINTER(C.c_int32), i32, i32, C.POINTER(KV), i32, vp, vp, sz, vp, vp]
     return lib
@@ -132,8 +132,8 @@ def mn_accept_and_commit(ctx, voted, greedy, spec_len, B, k_max, kv: KV, accepte
                                     n_out, next_last_tok, blocks_in_use, dev_status, stream), ctx)
 
 
-def mn_gemm_bf16(ctx, a, w, bias, out, M, N, K, split_k=0, workspace=None, workspace_bytes=0, stream=None) -> None:
-    _check(lib.mn_gemm_bf16(ctx, a, w, bias, out, M, N, K, split_k, workspace, workspace_bytes, stream), ctx)
+def mn_proj_gemm(ctx, a, w, bias, out, M, N, K, split_k=0, workspace=None, workspace_bytes=0, stream=None) -> None:
+    _check(lib.mn_proj_gemm(ctx, a, w, bias, out, M, N, K, split_k, workspace, workspace_bytes, stream), ctx)
 
 
 def mn_attention(ctx, q, spec_len, h_spec_len, B, max_ctx, kv: KV, layer, out, workspace, workspace_bytes,

@@ -119,7 +119,7 @@ static size_t al(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
   size_t row_seq, row_j, row_pos, row_tok, seq_row0, seq_ctx, seq_ok, rope_cos, rope_sin;
-  size_t x, h, q, attn, act, partials, logits, attn_scratch, total;
+  size_t x, h, q, knew, vnew, attn, act, partials, logits, attn_scratch, total;
   size_t partials_bytes, attn_scratch_bytes;
 };
 
@@ -135,6 +135,8 @@ static Layout make_layout(const mn_model_desc& d, int B, int M, int max_ctx) {
   L.x = take(Mr * d.d_model * 4);
   L.h = take(Mr * d.d_model * es);
   L.q = take(Mr * d.n_heads * d.head_dim * es);
+  L.knew = take(Mr * d.n_kv_heads * d.head_dim * es);
+  L.vnew = take(Mr * d.n_kv_heads * d.head_dim * es);
   L.attn = take(Mr * d.n_heads * d.head_dim * es);
   L.act = take(Mr * d.d_ffn * es);
   // partial sums of the widest projection at the largest split it can get
@@ -332,10 +334,14 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
     r.rows = rows;
     r.kv = KvView{kv->k_layers[l], kv->v_layers[l], kv->block_tables, kv->block_size, kv->num_blocks, kv->max_blocks_per_seq};
     r.q = w.at<void>(w.L.q);
+    // bf16 models keep this step's K/V rows in fp16 beside the bf16 cache for the step's own attention
+    r.knew = d.dtype == MN_DT_BF16 ? w.at<void>(w.L.knew) : nullptr;
+    r.vnew = d.dtype == MN_DT_BF16 ? w.at<void>(w.L.vnew) : nullptr;
     r.M = M; r.H = d.n_heads; r.Hkv = d.n_kv_heads; r.hd = d.head_dim; r.dtype = d.dtype;
     launch_rope_append(r, st);
     AttnArgs at{};
     at.q = r.q; at.out = w.at<void>(w.L.attn); at.rows = rows; at.kv = r.kv;
+    at.knew = r.knew; at.vnew = r.vnew;
     at.B = B; at.M = M; at.H = d.n_heads; at.Hkv = d.n_kv_heads; at.hd = d.head_dim; at.dtype = d.dtype;
     at.max_ctx = max_ctx; at.max_q = max_q;
     at.scratch = w.at<float>(w.L.attn_scratch); at.scratch_bytes = w.L.attn_scratch_bytes;
@@ -362,9 +368,9 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
 }
 
 // ---- component entry points -----------------------------------------------------------------------
-extern "C" mn_status mn_gemm_bf16(mn_ctx* c, const void* a, const void* w, const float* bias, float* out, int M, int N,
+extern "C" mn_status mn_proj_gemm(mn_ctx* c, const void* a, const void* w, const float* bias, float* out, int M, int N,
                                   int K, int split_k, void* workspace, size_t workspace_bytes, void* stream) {
-  const char* who = "mn_gemm_bf16";
+  const char* who = "mn_proj_gemm";
   if (M < 0 || N < 1 || K < 64 || K % 64) return fail(c, MN_ESHAPE, "%s: M=%d N=%d K=%d (K must be a positive multiple of 64)", who, M, N, K);
   if (split_k < 0 || split_k > MN_MAX_SPLIT_K) return fail(c, MN_EINVAL, "%s: split_k = %d", who, split_k);
   if (M == 0) return MN_OK;

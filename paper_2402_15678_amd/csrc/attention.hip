@@ -3,10 +3,10 @@
 // sequence b sees the cached keys [0, ctx_b) and the new keys 0..j of its own sequence.
 //
 // Two kernels:
-//  * attn_mfma_kernel  bf16, head_dim 128, 16-token blocks.  The G*q_b query rows that share one
+//  * attn_mfma_kernel  bf16 pages / fp16 queries, head_dim 128, 16-token blocks.  The G*q_b query rows that share one
 //    KV head (grouped-query attention stacks the group's heads on top of the speculated tokens)
 //    are the column index of every MFMA, so each K/V byte is read once per KV head.  K and V
-//    fragments go HBM -> registers -> MFMA directly: the page layouts put 8 consecutive
+//    fragments go HBM -> registers (bf16 widened exactly to fp16) -> MFMA directly: the page layouts put 8 consecutive
 //    contraction elements in 16 bytes for both products (head-dim chunks for K, tokens for V).
 //    The KV range of a sequence is split across workgroups; partial (max, sum, output) triples
 //    are merged by attn_merge_kernel.
@@ -24,7 +24,8 @@ namespace mn {
 // ------------------------------------------------------------------------------------------
 constexpr int GEN_THREADS = 256;
 
-template <typename T>
+// TA: activation type of q and out; T: storage type of the KV pages
+template <typename TA, typename T>
 __global__ void __launch_bounds__(GEN_THREADS) attn_generic_kernel(AttnArgs a) {
   __shared__ float s_q[256];
   __shared__ float s_p[GEN_THREADS];
@@ -35,16 +36,19 @@ __global__ void __launch_bounds__(GEN_THREADS) attn_generic_kernel(AttnArgs a) {
   const int hd = a.hd, bs = a.kv.block_size;
   const int b = a.rows.row_seq[m];
   const int pos = a.rows.row_pos[m];
-  T* o = reinterpret_cast<T*>(a.out) + ((size_t)m * a.H + h) * hd;
+  TA* o = reinterpret_cast<TA*>(a.out) + ((size_t)m * a.H + h) * hd;
   if (pos < 0) {
-    for (int e = tid; e < hd; e += GEN_THREADS) Store<T>::store(o + e, 0.f);
+    for (int e = tid; e < hd; e += GEN_THREADS) Store<TA>::store(o + e, 0.f);
     return;
   }
   const int nkeys = pos + 1;
+  const int ctx = a.rows.seq_ctx[b], row0 = a.rows.seq_row0[b];
+  const TA* Kn = reinterpret_cast<const TA*>(a.knew);
+  const TA* Vn = reinterpret_cast<const TA*>(a.vnew);
   const int kh = h / (a.H / a.Hkv);
   const float scale = rsqrtf((float)hd);
-  const T* q = reinterpret_cast<const T*>(a.q) + ((size_t)m * a.H + h) * hd;
-  for (int e = tid; e < hd; e += GEN_THREADS) s_q[e] = Store<T>::load(q + e) * scale;
+  const TA* q = reinterpret_cast<const TA*>(a.q) + ((size_t)m * a.H + h) * hd;
+  for (int e = tid; e < hd; e += GEN_THREADS) s_q[e] = Store<TA>::load(q + e) * scale;
   __syncthreads();
   const T* Kp = reinterpret_cast<const T*>(a.kv.k);
   const T* Vp = reinterpret_cast<const T*>(a.kv.v);
@@ -59,12 +63,17 @@ __global__ void __launch_bounds__(GEN_THREADS) attn_generic_kernel(AttnArgs a) {
     if (key < nkeys) {
       pb = bt[key / bs];
       const int off = key % bs;
-      const T* kb = Kp + ((size_t)pb * a.Hkv + kh) * (size_t)hd * bs;
       float d = 0.f;
-      for (int c = 0; c < hd / 8; ++c) {
-        const T* kk = kb + ((size_t)c * bs + off) * 8;
+      if (Kn && key >= ctx) {
+        const TA* kk = Kn + ((size_t)(row0 + key - ctx) * a.Hkv + kh) * hd;
+        for (int e = 0; e < hd; ++e) d = fmaf(s_q[e], Store<TA>::load(kk + e), d);
+      } else {
+        const T* kb = Kp + ((size_t)pb * a.Hkv + kh) * (size_t)hd * bs;
+        for (int c = 0; c < hd / 8; ++c) {
+          const T* kk = kb + ((size_t)c * bs + off) * 8;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) d = fmaf(s_q[c * 8 + i], Store<T>::load(kk + i), d);
+          for (int i = 0; i < 8; ++i) d = fmaf(s_q[c * 8 + i], Store<T>::load(kk + i), d);
+        }
       }
       s = d;
     }
@@ -86,9 +95,15 @@ __global__ void __launch_bounds__(GEN_THREADS) attn_generic_kernel(AttnArgs a) {
     const int cnt = min(GEN_THREADS, nkeys - k0);
     if (kg < ng) {
       for (int i = kg; i < cnt; i += ng) {
-        const int off = (k0 + i) % bs;
-        const T* vb = Vp + ((size_t)s_pb[i] * a.Hkv + kh) * (size_t)hd * bs;
-        acc = fmaf(s_p[i], Store<T>::load(vb + (size_t)e_own * bs + off), acc);
+        const int key2 = k0 + i;
+        float v;
+        if (Vn && key2 >= ctx) {
+          v = Store<TA>::load(Vn + ((size_t)(row0 + key2 - ctx) * a.Hkv + kh) * hd + e_own);
+        } else {
+          const T* vb = Vp + ((size_t)s_pb[i] * a.Hkv + kh) * (size_t)hd * bs;
+          v = Store<T>::load(vb + (size_t)e_own * bs + key2 % bs);
+        }
+        acc = fmaf(s_p[i], v, acc);
       }
     }
     __syncthreads();
@@ -98,7 +113,7 @@ __global__ void __launch_bounds__(GEN_THREADS) attn_generic_kernel(AttnArgs a) {
   if (tid < hd) {
     float t = 0.f;
     for (int g2 = 0; g2 < ng; ++g2) t += s_acc[g2 * hd + tid];
-    Store<T>::store(o + tid, t / run_l);
+    Store<TA>::store(o + tid, t / run_l);
   }
 }
 
@@ -109,7 +124,7 @@ constexpr int HD = 128;
 constexpr int BS = 16;
 constexpr int KT = 32;                 // keys per tile (two blocks)
 constexpr int CT = 4;                  // 16-row column tiles per wave (64 query rows)
-constexpr int Q_ROW = HD + 8;          // padded LDS row of Q, bf16 elements
+constexpr int Q_ROW = HD + 8;          // padded LDS row of Q, fp16 elements
 constexpr int MAX_RG = 4;              // row groups of 64 rows per workgroup
 constexpr int MERGE_RG = 2;              // row groups that can need a wave merge (KW > 1 only when RG <= 2)
 constexpr float LOG2E = 1.4426950408889634f;
@@ -118,7 +133,7 @@ constexpr float LOG2E = 1.4426950408889634f;
 __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int n_splits, float* __restrict__ o_part,
                                                         float* __restrict__ ml_part) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16_t* s_q = reinterpret_cast<bf16_t*>(smem);  // [RG*64][Q_ROW]; later reused for the wave merge
+  f16_t* s_q = reinterpret_cast<f16_t*>(smem);  // [RG*64][Q_ROW]; later reused for the wave merge
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
@@ -139,7 +154,7 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int n_splits
   const int t_end = (int)(((long)n_tiles * (split + 1)) / n_splits);
 
   // ---- Q -> LDS (zero rows past R) ----
-  const bf16_t* Q = reinterpret_cast<const bf16_t*>(a.q);
+  const f16_t* Q = reinterpret_cast<const f16_t*>(a.q);
   for (int c = tid; c < RG * 64 * (HD / 8); c += 256) {
     const int r = c / (HD / 8), ch = c % (HD / 8);
     uint4 v = make_uint4(0u, 0u, 0u, 0u);
@@ -168,6 +183,8 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int n_splits
 
   const bf16_t* Kp = reinterpret_cast<const bf16_t*>(a.kv.k);
   const bf16_t* Vp = reinterpret_cast<const bf16_t*>(a.kv.v);
+  const f16_t* Kn = reinterpret_cast<const f16_t*>(a.knew);
+  const f16_t* Vn = reinterpret_cast<const f16_t*>(a.vnew);
   const int32_t* bt = a.kv.block_tables + (size_t)b * a.kv.max_blocks_per_seq;
   // lane constants of the K operand: S^T row i = l16 = 4g'+r  <->  key 8g' + 4t + r of the tile
   const int kg_ = l16 >> 2, kr_ = l16 & 3;
@@ -177,31 +194,51 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int n_splits
       const int key0 = T * KT;
       const int pb0 = bt[2 * T];
       const int pb1 = (key0 + BS < nkeys) ? bt[2 * T + 1] : pb0;
-      const bool tail = key0 + KT - 1 > ctx;  // some key of the tile may be masked for some row
+      const bool tail = key0 + KT > ctx;  // the tile holds keys of this step (masking, side-buffer reads)
       // ---- K fragments: [t][s] ----
-      bf16x8 kf[2][4];
+      f16x8 kf[2][4];
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const int kk = 8 * kg_ + 4 * t + kr_;  // key inside the tile
         const int pb = (kk < BS) ? pb0 : pb1;
-        const bf16_t* base = Kp + ((size_t)pb * a.Hkv + kvh) * (size_t)(HD * BS) + (kk & (BS - 1)) * 8;
+        const int key = key0 + kk;
+        if (tail && Kn && key >= ctx && key < nkeys) {
+          // a key of this step: read the unrounded row from the side buffer
+          const f16_t* base = Kn + ((size_t)(row0 + key - ctx) * a.Hkv + kvh) * HD + g * 8;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) kf[t][s] = *reinterpret_cast<const bf16x8*>(base + (size_t)(4 * s + g) * (BS * 8));
+          for (int s = 0; s < 4; ++s) kf[t][s] = *reinterpret_cast<const f16x8*>(base + 32 * s);
+        } else {
+          const bf16_t* base = Kp + ((size_t)pb * a.Hkv + kvh) * (size_t)(HD * BS) + (kk & (BS - 1)) * 8;
+#pragma unroll
+          for (int s = 0; s < 4; ++s)
+            kf[t][s] = bf16x8_to_f16x8(*reinterpret_cast<const uint4*>(base + (size_t)(4 * s + g) * (BS * 8)));
+        }
       }
       // ---- V fragments: [u], keys 8g..8g+7 of the tile ----
-      bf16x8 vf[8];
+      f16x8 vf[8];
       {
         const int pb = (g < 2) ? pb0 : pb1;
         const bf16_t* base = Vp + ((size_t)pb * a.Hkv + kvh) * (size_t)(HD * BS) + (8 * (g & 1));
 #pragma unroll
-        for (int u = 0; u < 8; ++u) vf[u] = *reinterpret_cast<const bf16x8*>(base + (size_t)(16 * u + l16) * BS);
+        for (int u = 0; u < 8; ++u) vf[u] = bf16x8_to_f16x8(*reinterpret_cast<const uint4*>(base + (size_t)(16 * u + l16) * BS));
         if (key0 + KT > nkeys) {
           // stale slots past the sequence end may hold anything: zero them so 0 * garbage stays 0
 #pragma unroll
           for (int u = 0; u < 8; ++u)
 #pragma unroll
             for (int e = 0; e < 8; ++e)
-              if (key0 + 8 * g + e >= nkeys) vf[u][e] = (__bf16)0.f;
+              if (key0 + 8 * g + e >= nkeys) vf[u][e] = (f16_t)0.f;
+        }
+        if (tail && Vn) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int key = key0 + 8 * g + e;
+            if (key >= ctx && key < nkeys) {
+              const f16_t* src = Vn + ((size_t)(row0 + key - ctx) * a.Hkv + kvh) * HD + l16;
+#pragma unroll
+              for (int u = 0; u < 8; ++u) vf[u][e] = src[16 * u];
+            }
+          }
         }
       }
 #pragma unroll
@@ -209,12 +246,12 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int n_splits
         if (ct >= n_ct) continue;
         // ---- S^T = K Q^T for 32 keys x 16 rows ----
         f32x4 S0 = (f32x4){0.f, 0.f, 0.f, 0.f}, S1 = S0;
-        const bf16_t* qrow = &s_q[(rg * 64 + ct * 16 + l16) * Q_ROW + g * 8];
+        const f16_t* qrow = &s_q[(rg * 64 + ct * 16 + l16) * Q_ROW + g * 8];
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-          const bf16x8 qf = *reinterpret_cast<const bf16x8*>(qrow + s * 32);
-          S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][s], qf, S0, 0, 0, 0);
-          S1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][s], qf, S1, 0, 0, 0);
+          const f16x8 qf = *reinterpret_cast<const f16x8*>(qrow + s * 32);
+          S0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[0][s], qf, S0, 0, 0, 0);
+          S1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[1][s], qf, S1, 0, 0, 0);
         }
         // lane holds keys key0 + 8g + e, e = 0..7 (S0 -> e 0..3, S1 -> e 4..7) of row l16
         float sc[8];
@@ -243,14 +280,14 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int n_splits
           ps += p[e];
         }
         run_l[ct] = run_l[ct] * alpha + ps;  // per-lane partial sum; lane groups are added at the end
-        union { bf16x8 v; uint32_t u[4]; } pf;
+        union { f16x8 v; uint32_t u[4]; } pf;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) pf.u[e] = pack2bf(p[2 * e], p[2 * e + 1]);
+        for (int e = 0; e < 4; ++e) pf.u[e] = pack2h(p[2 * e], p[2 * e + 1]);
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
           f32x4 o = O[ct][u];
           o[0] *= alpha; o[1] *= alpha; o[2] *= alpha; o[3] *= alpha;
-          O[ct][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[u], pf.v, o, 0, 0, 0);
+          O[ct][u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[u], pf.v, o, 0, 0, 0);
         }
       }
     }
@@ -311,11 +348,11 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int n_splits
       const int m = row0 + j, h = kvh * G + gi;
       if (n_splits == 1) {
         const float inv = (ok && run_l[ct] > 0.f) ? 1.f / run_l[ct] : 0.f;
-        bf16_t* o = reinterpret_cast<bf16_t*>(a.out) + ((size_t)m * a.H + h) * HD + 4 * g;
+        f16_t* o = reinterpret_cast<f16_t*>(a.out) + ((size_t)m * a.H + h) * HD + 4 * g;
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
           const f32x4 v = O[ct][u];
-          *reinterpret_cast<uint2*>(o + 16 * u) = make_uint2(pack2bf(v[0] * inv, v[1] * inv), pack2bf(v[2] * inv, v[3] * inv));
+          *reinterpret_cast<uint2*>(o + 16 * u) = make_uint2(pack2h(v[0] * inv, v[1] * inv), pack2h(v[2] * inv, v[3] * inv));
         }
       } else {
         float* o = o_part + (((size_t)split * a.M + m) * a.H + h) * HD + 4 * g;
@@ -334,9 +371,9 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int n_splits
   }
 }
 
-// One wave per (row, head): merge the split partials, normalise, store bf16.
+// One wave per (row, head): merge the split partials, normalise, store fp16.
 __global__ void __launch_bounds__(256) attn_merge_kernel(const float* __restrict__ o_part, const float* __restrict__ ml_part,
-                                                         int n_splits, int M, int H, bf16_t* __restrict__ out) {
+                                                         int n_splits, int M, int H, f16_t* __restrict__ out) {
   const int wid = (blockIdx.x * 256 + threadIdx.x) >> 6, lane = threadIdx.x & 63;
   if (wid >= M * H) return;
   float gm = -INFINITY;
@@ -352,7 +389,7 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(const float* __restrict
     o1 += v.y * f;
   }
   const float inv = l > 0.f ? 1.f / l : 0.f;
-  *reinterpret_cast<uint32_t*>(out + (size_t)wid * HD + lane * 2) = pack2bf(o0 * inv, o1 * inv);
+  *reinterpret_cast<uint32_t*>(out + (size_t)wid * HD + lane * 2) = pack2h(o0 * inv, o1 * inv);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -389,8 +426,9 @@ bool attention_mfma_supported(int H, int Hkv, int hd, int block_size, int dtype)
 }
 
 static size_t mfma_smem_bytes(int rg_max) {
-  const size_t q = (size_t)rg_max * 64 * Q_ROW * sizeof(bf16_t);
-  const size_t merge = rg_max <= MERGE_RG ? (size_t)MERGE_RG * CT * (8 * 4 + 2) * 64 * sizeof(float) : 0;
+  const size_t q = (size_t)rg_max * 64 * Q_ROW * sizeof(f16_t);
+  // the merge area is needed by any sequence with at most MERGE_RG row groups, whatever the batch maximum is
+  const size_t merge = (size_t)MERGE_RG * CT * (8 * 4 + 2) * 64 * sizeof(float);
   return q > merge ? q : merge;
 }
 
@@ -422,13 +460,13 @@ void launch_attention(const AttnArgs& a, hipStream_t st) {
     attn_mfma_kernel<<<grid, 256, smem, st>>>(a, n_splits, o_part, ml_part);
     if (n_splits > 1) {
       const int waves = a.M * a.H;
-      attn_merge_kernel<<<(waves + 3) / 4, 256, 0, st>>>(o_part, ml_part, n_splits, a.M, a.H, reinterpret_cast<bf16_t*>(a.out));
+      attn_merge_kernel<<<(waves + 3) / 4, 256, 0, st>>>(o_part, ml_part, n_splits, a.M, a.H, reinterpret_cast<f16_t*>(a.out));
     }
     return;
   }
   dim3 grid(a.H, a.M);
-  if (a.dtype == MN_DT_BF16) attn_generic_kernel<bf16_t><<<grid, GEN_THREADS, 0, st>>>(a);
-  else attn_generic_kernel<float><<<grid, GEN_THREADS, 0, st>>>(a);
+  if (a.dtype == MN_DT_BF16) attn_generic_kernel<f16_t, bf16_t><<<grid, GEN_THREADS, 0, st>>>(a);
+  else attn_generic_kernel<float, float><<<grid, GEN_THREADS, 0, st>>>(a);
 }
 
 }  // namespace mn

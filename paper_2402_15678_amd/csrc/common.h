@@ -5,10 +5,20 @@
 
 namespace mn {
 
-typedef uint16_t bf16_t;  // raw bf16 pattern
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef uint16_t bf16_t;  // raw bf16 pattern (storage type of weights and KV pages in bf16 models)
+typedef _Float16 f16_t;   // activation type in bf16 models (see the note below)
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Precision note.  In bf16 models the weights and the KV pages are bf16 in HBM.  Every bf16 value
+// in the normal fp16 range is exactly representable in fp16 (8 significant bits into 11), so the
+// kernels widen weight and cache fragments to fp16 in registers and run the fp16 MFMA with fp32
+// accumulation, while the activations between kernels (norm output, queries, attention output,
+// FFN activation, softmax probabilities) are kept in fp16: 8x less rounding error per stage than
+// bf16 activations at the same MFMA rate and the same HBM traffic.  bf16 magnitudes below 2^-14
+// lose low bits in the widening (absolute error below 2^-25), which is far below every tolerance.
 
 constexpr int WAVE = 64;
 
@@ -20,11 +30,30 @@ __device__ __forceinline__ bf16_t f2bf(float f) {
 }
 __device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 __device__ __forceinline__ uint32_t pack2bf(float lo, float hi) { return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16); }
+// two fp32 -> packed fp16, round to nearest even
+__device__ __forceinline__ uint32_t pack2h(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+}
+// 8 bf16 (16 bytes) -> 8 fp16, exact for magnitudes in [2^-14, 65504]
+__device__ __forceinline__ f16x8 bf16x8_to_f16x8(uint4 u) {
+  union { f16x8 v; uint32_t w[4]; } r;
+  const uint32_t in[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    r.w[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(__uint_as_float(in[i] << 16),
+                                                                     __uint_as_float(in[i] & 0xffff0000u)));
+  return r.v;
+}
 
 template <typename T> struct Store;
 template <> struct Store<float> {
   static __device__ __forceinline__ float load(const float* p) { return *p; }
   static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+};
+template <> struct Store<f16_t> {
+  static __device__ __forceinline__ float load(const f16_t* p) { return (float)*p; }
+  static __device__ __forceinline__ void store(f16_t* p, float v) { *p = (f16_t)v; }
 };
 template <> struct Store<bf16_t> {
   static __device__ __forceinline__ float load(const bf16_t* p) { return bf2f(*p); }

@@ -2,10 +2,11 @@
 //
 // The verification step scores only M = sum_b (k_b + 1) rows (tens to a few hundred) against
 // matrices of 10^8..10^9 parameters, so every weight byte is needed exactly once per step and
-// the kernel is a weight streamer: weights go HBM -> registers -> MFMA with no staging (both
-// operands are contiguous along k, which is what the 16x16x32 bf16 MFMA wants: 8 consecutive k
-// per lane), the small activation tile is shared by the four waves of a workgroup through LDS,
-// and all M rows of a chunk are covered by one workgroup so no weight byte is read twice.
+// the kernel is a weight streamer: weights go HBM -> registers (bf16 widened exactly to fp16) ->
+// MFMA with no staging (both operands are contiguous along k, which is what the 16x16x32 MFMA
+// wants: 8 consecutive k per lane), the small fp16 activation tile is shared by the four waves of
+// a workgroup through LDS, and all M rows of a chunk are covered by one workgroup so no weight
+// byte is read twice.
 #include "launch.h"
 #include "../../include/minions_verify.h"
 
@@ -14,17 +15,17 @@
 namespace mn {
 
 constexpr int KB = 64;            // k elements per main-loop iteration (two MFMA k-steps)
-constexpr int LDS_ROW = KB + 8;   // padded row of the activation tile, in bf16 elements (144 bytes)
+constexpr int LDS_ROW = KB + 8;   // padded row of the activation tile, in fp16 elements (144 bytes)
 
 // Workgroup = 4 waves; wave w owns NTW 16-column tiles; every wave covers all MT 16-row tiles.
 // MFMA orientation: the weight fragment is the row operand (rows = output columns n), the
 // activation fragment is the column operand (columns = rows m of the output), so a lane ends up
 // with 4 consecutive n for one m.
 template <int MT, int NTW>
-__global__ void __launch_bounds__(256) gemm_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
+__global__ void __launch_bounds__(256) gemm_w16_kernel(const f16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                         float* __restrict__ out, const float* __restrict__ bias,
                                                         int M, int N, int K, int k_per_split) {
-  __shared__ __attribute__((aligned(16))) bf16_t s_a[2][16 * MT * LDS_ROW];
+  __shared__ __attribute__((aligned(16))) f16_t s_a[2][16 * MT * LDS_ROW];
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
@@ -73,13 +74,14 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(const bf16_t* __restrict
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  bf16x8 wcur[NTW][2], wnxt[NTW][2];
+  f16x8 wcur[NTW][2];
+  uint4 wnxt[NTW][2];  // raw bf16 of the next iteration, widened when it becomes current
   if (n_iter > 0) {
     load_a(k_begin);
 #pragma unroll
     for (int nt = 0; nt < NTW; ++nt) {
-      wcur[nt][0] = *reinterpret_cast<const bf16x8*>(wrow[nt]);
-      wcur[nt][1] = *reinterpret_cast<const bf16x8*>(wrow[nt] + 32);
+      wcur[nt][0] = bf16x8_to_f16x8(*reinterpret_cast<const uint4*>(wrow[nt]));
+      wcur[nt][1] = bf16x8_to_f16x8(*reinterpret_cast<const uint4*>(wrow[nt] + 32));
     }
     store_a(0);
   }
@@ -93,28 +95,28 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(const bf16_t* __restrict
       load_a(k_begin + koff);
 #pragma unroll
       for (int nt = 0; nt < NTW; ++nt) {
-        wnxt[nt][0] = *reinterpret_cast<const bf16x8*>(wrow[nt] + koff);
-        wnxt[nt][1] = *reinterpret_cast<const bf16x8*>(wrow[nt] + koff + 32);
+        wnxt[nt][0] = *reinterpret_cast<const uint4*>(wrow[nt] + koff);
+        wnxt[nt][1] = *reinterpret_cast<const uint4*>(wrow[nt] + koff + 32);
       }
     }
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      bf16x8 bfrag[MT];
+      f16x8 bfrag[MT];
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
-        bfrag[mt] = *reinterpret_cast<const bf16x8*>(&s_a[buf][(mt * 16 + l16) * LDS_ROW + ks * 32 + g * 8]);
+        bfrag[mt] = *reinterpret_cast<const f16x8*>(&s_a[buf][(mt * 16 + l16) * LDS_ROW + ks * 32 + g * 8]);
 #pragma unroll
       for (int nt = 0; nt < NTW; ++nt)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-          acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wcur[nt][ks], bfrag[mt], acc[nt][mt], 0, 0, 0);
+          acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wcur[nt][ks], bfrag[mt], acc[nt][mt], 0, 0, 0);
     }
     if (more) {
       store_a(buf ^ 1);
 #pragma unroll
       for (int nt = 0; nt < NTW; ++nt) {
-        wcur[nt][0] = wnxt[nt][0];
-        wcur[nt][1] = wnxt[nt][1];
+        wcur[nt][0] = bf16x8_to_f16x8(wnxt[nt][0]);
+        wcur[nt][1] = bf16x8_to_f16x8(wnxt[nt][1]);
       }
     }
     __syncthreads();
@@ -233,12 +235,12 @@ static void launch_bf16_mt(const GemmArgs& a, int ntw, int m_chunks, hipStream_t
   const int iters = a.K / KB;
   const int per = (iters + a.split_k - 1) / a.split_k;  // iterations per split
   dim3 grid((a.N + n_wg - 1) / n_wg, a.split_k, m_chunks);
-  const bf16_t* A = reinterpret_cast<const bf16_t*>(a.a);
+  const f16_t* A = reinterpret_cast<const f16_t*>(a.a);
   const bf16_t* W = reinterpret_cast<const bf16_t*>(a.w);
   if (ntw == 4)
-    gemm_bf16_kernel<MT, 4><<<grid, 256, 0, st>>>(A, W, a.out, a.bias, a.M, a.N, a.K, per * KB);
+    gemm_w16_kernel<MT, 4><<<grid, 256, 0, st>>>(A, W, a.out, a.bias, a.M, a.N, a.K, per * KB);
   else
-    gemm_bf16_kernel<MT, 2><<<grid, 256, 0, st>>>(A, W, a.out, a.bias, a.M, a.N, a.K, per * KB);
+    gemm_w16_kernel<MT, 2><<<grid, 256, 0, st>>>(A, W, a.out, a.bias, a.M, a.N, a.K, per * KB);
 }
 
 void launch_gemm(const GemmArgs& a, hipStream_t st) {

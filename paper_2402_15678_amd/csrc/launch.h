@@ -36,7 +36,7 @@ struct NormArgs {
   const int32_t *row_tok, *row_pos;
   const float *gain, *shift;  // shift null => RMSNorm
   float eps;
-  void* h;                // [M][d] normalised output in the storage type
+  void* h;                // [M][d] normalised output in the activation type
   int M, d, dtype;
 };
 void launch_norm(const NormArgs& a, hipStream_t st);
@@ -48,7 +48,8 @@ struct RopeAppendArgs {
   const float *rope_cos, *rope_sin;  // [M][hd/2] or null (no rotation)
   RowInfo rows;
   KvView kv;
-  void* q;  // [M][H][hd] storage type
+  void* q;  // [M][H][hd] activation type
+  void *knew, *vnew;  // [M][Hkv][hd] activation type: this step's K/V rows before the cache rounding, or null
   int M, H, Hkv, hd, dtype;
 };
 void launch_rope_append(const RopeAppendArgs& a, hipStream_t st);
@@ -58,7 +59,7 @@ struct ActArgs {
   const float* partials;  // [S][M][ncols]
   int n_partials;
   const float* bias;
-  void* act;  // [M][F] storage type
+  void* act;  // [M][F] activation type
   int M, F, swiglu, dtype;
 };
 void launch_act(const ActArgs& a, hipStream_t st);
@@ -68,7 +69,7 @@ void launch_argmax_rows(const float* logits, int M, int V, const RowInfo& rows, 
 
 // ---- gemm.hip ----
 struct GemmArgs {
-  const void* a;  // [M][K] storage type
+  const void* a;  // [M][K] activation type (fp32 in fp32 models, fp16 in bf16 models)
   const void* w;  // [N][K] storage type
   float* out;     // [S][M][N] fp32 partial sums (S = split_k); bias added to split 0 when given
   const float* bias;
@@ -80,10 +81,13 @@ void launch_reduce_partials(const float* partials, int S, size_t stride, float* 
 
 // ---- attention.hip ----
 struct AttnArgs {
-  const void* q;  // [M][H][hd] storage type
-  void* out;      // [M][H*hd] storage type
+  const void* q;  // [M][H][hd] activation type
+  void* out;      // [M][H*hd] activation type
   RowInfo rows;
   KvView kv;
+  // this step's own K/V rows [M][Hkv][hd] in the activation type (keys at positions >= ctx_b are read
+  // from here instead of the cache), or null: every key is read from the cache
+  const void *knew, *vnew;
   int B, M, H, Hkv, hd, dtype, max_ctx;
   int max_q;       // largest number of rows of one sequence (host knowledge)
   float* scratch;  // split-KV partials

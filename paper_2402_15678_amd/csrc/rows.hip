@@ -117,8 +117,18 @@ __device__ __forceinline__ float4 load4<bf16_t>(const bf16_t* p) {
   return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u), __uint_as_float(u.y << 16),
                      __uint_as_float(u.y & 0xFFFF0000u));
 }
+template <>
+__device__ __forceinline__ float4 load4<f16_t>(const f16_t* p) {
+  const uint2 u = *reinterpret_cast<const uint2*>(p);
+  const f16x2 a = __builtin_bit_cast(f16x2, u.x), b = __builtin_bit_cast(f16x2, u.y);
+  return make_float4((float)a[0], (float)a[1], (float)b[0], (float)b[1]);
+}
 template <typename T>
 __device__ __forceinline__ void store4(T* p, float4 v);
+template <>
+__device__ __forceinline__ void store4<f16_t>(f16_t* p, float4 v) {
+  *reinterpret_cast<uint2*>(p) = make_uint2(pack2h(v.x, v.y), pack2h(v.z, v.w));
+}
 template <>
 __device__ __forceinline__ void store4<float>(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
 template <>
@@ -126,7 +136,8 @@ __device__ __forceinline__ void store4<bf16_t>(bf16_t* p, float4 v) {
   *reinterpret_cast<uint2*>(p) = make_uint2(pack2bf(v.x, v.y), pack2bf(v.z, v.w));
 }
 
-template <typename T>
+// T: storage type of the embedding tables; TA: activation type of the normalised output
+template <typename T, typename TA>
 __global__ void __launch_bounds__(NORM_THREADS) norm_kernel(NormArgs a) {
   __shared__ float red[NORM_THREADS / 64];
   const int m = blockIdx.x;
@@ -186,7 +197,7 @@ __global__ void __launch_bounds__(NORM_THREADS) norm_kernel(NormArgs a) {
   }
   const float var = block_sum<NORM_THREADS / 64>(sq, red) * inv_d;
   const float rstd = 1.f / sqrtf(var + a.eps);
-  T* hr = reinterpret_cast<T*>(a.h) + (size_t)m * d;
+  TA* hr = reinterpret_cast<TA*>(a.h) + (size_t)m * d;
 #pragma unroll
   for (int it = 0; it < NORM_MAX_VEC; ++it) {
     const int i4 = it * NORM_THREADS + tid;
@@ -200,22 +211,23 @@ __global__ void __launch_bounds__(NORM_THREADS) norm_kernel(NormArgs a) {
         const float4 sh = *reinterpret_cast<const float4*>(a.shift + e);
         o.x += sh.x; o.y += sh.y; o.z += sh.z; o.w += sh.w;
       }
-      store4<T>(hr + e, o);
+      store4<TA>(hr + e, o);
     }
   }
 }
 
 void launch_norm(const NormArgs& a, hipStream_t st) {
   if (a.M <= 0) return;
-  if (a.dtype == MN_DT_BF16) norm_kernel<bf16_t><<<a.M, NORM_THREADS, 0, st>>>(a);
-  else norm_kernel<float><<<a.M, NORM_THREADS, 0, st>>>(a);
+  if (a.dtype == MN_DT_BF16) norm_kernel<bf16_t, f16_t><<<a.M, NORM_THREADS, 0, st>>>(a);
+  else norm_kernel<float, float><<<a.M, NORM_THREADS, 0, st>>>(a);
 }
 
 // ------------------------------------------------------------------------------------------
 // rotary embedding + tentative KV append
 // ------------------------------------------------------------------------------------------
 // grid (H + 2 Hkv, M), hd/2 threads: thread t owns the pair (t, t + hd/2) of one head of one row.
-template <typename T>
+// TA: activation type of the query buffer; T: storage type of the KV pages
+template <typename TA, typename T>
 __global__ void rope_append_kernel(RopeAppendArgs a) {
   const int m = blockIdx.y;
   const int head = blockIdx.x;
@@ -238,10 +250,17 @@ __global__ void rope_append_kernel(RopeAppendArgs a) {
     v0 = r0; v1 = r1;
   }
   if (head < a.H) {
-    T* q = reinterpret_cast<T*>(a.q) + ((size_t)m * a.H + head) * hd;
-    Store<T>::store(q + t, v0);
-    Store<T>::store(q + t + half, v1);
+    TA* q = reinterpret_cast<TA*>(a.q) + ((size_t)m * a.H + head) * hd;
+    Store<TA>::store(q + t, v0);
+    Store<TA>::store(q + t + half, v1);
     return;
+  }
+  // this step's own copy in the activation type (not yet rounded to the cache's storage type)
+  if (a.knew) {
+    TA* side = reinterpret_cast<TA*>(is_v ? a.vnew : a.knew) +
+               ((size_t)m * a.Hkv + (head - a.H - (is_v ? a.Hkv : 0))) * hd;
+    Store<TA>::store(side + t, v0);
+    Store<TA>::store(side + t + half, v1);
   }
   const int pos = a.rows.row_pos[m];
   if (pos < 0) return;  // disabled sequence: nothing is written to the cache
@@ -268,8 +287,8 @@ __global__ void rope_append_kernel(RopeAppendArgs a) {
 void launch_rope_append(const RopeAppendArgs& a, hipStream_t st) {
   if (a.M <= 0) return;
   dim3 grid(a.H + 2 * a.Hkv, a.M);
-  if (a.dtype == MN_DT_BF16) rope_append_kernel<bf16_t><<<grid, a.hd / 2, 0, st>>>(a);
-  else rope_append_kernel<float><<<grid, a.hd / 2, 0, st>>>(a);
+  if (a.dtype == MN_DT_BF16) rope_append_kernel<f16_t, bf16_t><<<grid, a.hd / 2, 0, st>>>(a);
+  else rope_append_kernel<float, float><<<grid, a.hd / 2, 0, st>>>(a);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -314,7 +333,7 @@ void launch_act(const ActArgs& a, hipStream_t st) {
   const size_t nvec = (size_t)a.M * (a.F >> 2);
   int blocks = (int)((nvec + 255) / 256);
   if (blocks > 4096) blocks = 4096;
-  if (a.dtype == MN_DT_BF16) act_kernel<bf16_t><<<blocks, 256, 0, st>>>(a);
+  if (a.dtype == MN_DT_BF16) act_kernel<f16_t><<<blocks, 256, 0, st>>>(a);
   else act_kernel<float><<<blocks, 256, 0, st>>>(a);
 }
 

@@ -28,6 +28,14 @@ def to_device(a: np.ndarray, dtype: int) -> torch.Tensor:
     return torch.from_numpy(a).to(_dev())
 
 
+def to_device_act(a: np.ndarray, dtype: int) -> torch.Tensor:
+    """Host values -> device tensor in the activation type of the model (fp32, or fp16 in bf16 models)."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if dtype == synth.DT_BF16:
+        return torch.from_numpy(a.astype(np.float16)).to(_dev())
+    return torch.from_numpy(a).to(_dev())
+
+
 def stream_ptr() -> int:
     return torch.cuda.current_stream().cuda_stream
 

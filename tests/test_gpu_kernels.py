@@ -37,7 +37,8 @@ def test_vote_bit_exact(hb, B, n, k_max, V, mode):
     ssm = torch.full((B,), -9, dtype=torch.int32, device="cuda:0")
     st = torch.zeros(1, dtype=torch.int32, device="cuda:0")
     d_dev = _dev(drafts.reshape(-1) if drafts.size else np.zeros(1))
-    binding.mn_mv_vote(None, d_dev.data_ptr(), _dev(spec).data_ptr(), _dev(w, torch.float32).data_ptr(), B, n, k_max,
+    spec_d, w_d = _dev(spec), _dev(w, torch.float32)          # named: the buffers must outlive the call
+    binding.mn_mv_vote(None, d_dev.data_ptr(), spec_d.data_ptr(), w_d.data_ptr(), B, n, k_max,
                        mode, voted.data_ptr(), ssm.data_ptr(), st.data_ptr(), harness.stream_ptr())
     torch.cuda.synchronize()
     assert st.item() == 0
@@ -52,12 +53,15 @@ def test_vote_paper_example_and_bad_spec_len(hb):
     voted = torch.zeros((1, 2), dtype=torch.int32, device="cuda:0")
     ssm = torch.zeros((1,), dtype=torch.int32, device="cuda:0")
     st = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    two, three = _dev([2]), _dev([3])
     for w, want, ws in [([3, 2, 4], [1, 3], 0), ([2, 3, 4], [1, 4], 1), ([1, 1, 3], [2, 5], 2)]:
-        binding.mn_mv_vote(None, drafts.data_ptr(), _dev([2]).data_ptr(), _dev(w, torch.float32).data_ptr(), 1, 3, 2, 0,
+        w_d = _dev(w, torch.float32)
+        binding.mn_mv_vote(None, drafts.data_ptr(), two.data_ptr(), w_d.data_ptr(), 1, 3, 2, 0,
                            voted.data_ptr(), ssm.data_ptr(), st.data_ptr(), harness.stream_ptr())
         torch.cuda.synchronize()
         assert voted.cpu().tolist() == [want] and ssm.item() == ws
-    binding.mn_mv_vote(None, drafts.data_ptr(), _dev([3]).data_ptr(), _dev([1, 1, 1], torch.float32).data_ptr(), 1, 3, 2, 0,
+    w_d = _dev([1, 1, 1], torch.float32)
+    binding.mn_mv_vote(None, drafts.data_ptr(), three.data_ptr(), w_d.data_ptr(), 1, 3, 2, 0,
                        voted.data_ptr(), ssm.data_ptr(), st.data_ptr(), harness.stream_ptr())
     torch.cuda.synchronize()
     assert st.item() == binding.MN_DEV_DRAFTS and voted.cpu().tolist() == [[-1, -1]] and ssm.item() == -1
@@ -87,7 +91,8 @@ def test_accept_commit_bit_exact(hb, B, k_max):
     o = {k: torch.full(s, -9, dtype=torch.int32, device="cuda:0") for k, s in
          [("acc", (B,)), ("out", (B, k_max + 1)), ("n_out", (B,)), ("nxt", (B,)), ("blocks", (B,))]}
     st = torch.zeros(1, dtype=torch.int32, device="cuda:0")
-    binding.mn_accept_and_commit(None, _dev(voted).data_ptr(), _dev(greedy).data_ptr(), _dev(spec).data_ptr(), B, k_max, kv,
+    voted_d, greedy_d, spec_d = _dev(voted), _dev(greedy), _dev(spec)
+    binding.mn_accept_and_commit(None, voted_d.data_ptr(), greedy_d.data_ptr(), spec_d.data_ptr(), B, k_max, kv,
                                  o["acc"].data_ptr(), o["out"].data_ptr(), o["n_out"].data_ptr(), o["nxt"].data_ptr(),
                                  o["blocks"].data_ptr(), st.data_ptr(), harness.stream_ptr())
     torch.cuda.synchronize()
@@ -101,17 +106,17 @@ def test_accept_commit_bit_exact(hb, B, k_max):
 @pytest.mark.parametrize("M,N,K,split", [(5, 256, 256, 1), (40, 5120, 5120, 0), (144, 8192, 8192, 0), (144, 1000, 1024, 4),
                                          (17, 50272, 512, 1), (144, 10240, 8192, 2), (200, 3072, 2048, 0),
                                          (608, 2048, 8192, 0), (1, 64, 64, 1), (144, 8192, 28672, 0)])
-def test_gemm_bf16_matches_fp64(hb, M, N, K, split):
+def test_proj_gemm_matches_fp64(hb, M, N, K, split):
     harness, binding = hb
     g = synth.stream(79, M, N, K)
-    a = synth.storage_round(g.standard_normal((M, K), dtype=np.float32), synth.DT_BF16)
+    a = g.standard_normal((M, K), dtype=np.float32).astype(np.float16).astype(np.float32)   # fp16 activations
     w = synth.storage_round(g.standard_normal((N, K), dtype=np.float32) * 0.05, synth.DT_BF16)
     bias = g.standard_normal(N).astype(np.float32)
-    a_d, w_d = harness.to_device(a, synth.DT_BF16), harness.to_device(w, synth.DT_BF16)
+    a_d, w_d = harness.to_device_act(a, synth.DT_BF16), harness.to_device(w, synth.DT_BF16)
     b_d = torch.from_numpy(bias).cuda()
     out = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda:0")
     ws = torch.empty((16 * M * N * 4 + 256,), dtype=torch.uint8, device="cuda:0")
-    binding.mn_gemm_bf16(None, a_d.data_ptr(), w_d.data_ptr(), b_d.data_ptr(), out.data_ptr(), M, N, K, split,
+    binding.mn_proj_gemm(None, a_d.data_ptr(), w_d.data_ptr(), b_d.data_ptr(), out.data_ptr(), M, N, K, split,
                          ws.data_ptr(), ws.numel(), harness.stream_ptr())
     torch.cuda.synchronize()
     got = out.cpu().numpy().astype(np.float64)
@@ -143,19 +148,22 @@ def test_attention_matches_oracle(hb, name, desc, ctx_lens, spec_lens):
     kvh.ctx_lens = np.asarray(ctx_lens, np.int32)
     M = int(sum(k + 1 for k in spec_lens))
     g = synth.stream(91, 9)
-    q = synth.storage_round(g.standard_normal((M, desc.n_heads, desc.head_dim), dtype=np.float32), desc.dtype)
+    q = g.standard_normal((M, desc.n_heads, desc.head_dim), dtype=np.float32)
+    if desc.dtype == synth.DT_BF16:
+        q = q.astype(np.float16).astype(np.float32)                                   # fp16 activations
     tiny = synth.ModelDesc(desc.arch, desc.dtype, 1, 64, desc.n_heads, desc.n_kv_heads, desc.head_dim, 64, 8, 4096)
     model = harness.DeviceModel.from_host(tiny, synth.make_weights(tiny, 1))
     kvd = harness.DeviceKV.from_host(desc, kvh)
     kvd.ctx_lens.copy_(torch.from_numpy(kvh.ctx_lens))
-    q_d = harness.to_device(q, desc.dtype)
-    st_t = torch.bfloat16 if desc.dtype == synth.DT_BF16 else torch.float32
+    q_d = harness.to_device_act(q, desc.dtype)
+    st_t = torch.float16 if desc.dtype == synth.DT_BF16 else torch.float32
     out = torch.full((M, desc.n_heads * desc.head_dim), float("nan"), dtype=st_t, device="cuda:0")
     max_ctx = max(total)
     wsb = binding.mn_workspace_bytes(model.ctx, B, M, max_ctx)
     ws = torch.empty((wsb,), dtype=torch.uint8, device="cuda:0")
     st = torch.zeros(1, dtype=torch.int32, device="cuda:0")
-    binding.mn_attention(model.ctx, q_d.data_ptr(), _dev(spec_lens).data_ptr(), binding.host_i32(spec_lens), B, max_ctx,
+    spec_d = _dev(spec_lens)
+    binding.mn_attention(model.ctx, q_d.data_ptr(), spec_d.data_ptr(), binding.host_i32(spec_lens), B, max_ctx,
                          kvd.c, 0, out.data_ptr(), ws.data_ptr(), wsb, st.data_ptr(), harness.stream_ptr())
     torch.cuda.synchronize()
     assert st.item() == 0
@@ -169,6 +177,7 @@ def test_attention_matches_oracle(hb, name, desc, ctx_lens, spec_lens):
                                     int(ctx_lens[b]))
         worst = max(worst, np.abs(got[row:row + T] - want).max())
         row += T
-    # outputs are O(1) averages of N(0,1) values; bf16 output rounding alone is 2^-9 relative
-    tol = 2e-2 if desc.dtype == synth.DT_BF16 else 1e-5
+    # outputs are softmax averages of N(0,1) values (|o| up to ~1): fp16 rounding of the probabilities and
+    # of the output is 2^-11 relative each; fp32 path: accumulation order only
+    tol = 2e-3 if desc.dtype == synth.DT_BF16 else 1e-5
     assert worst < tol, worst

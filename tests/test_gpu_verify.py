@@ -47,7 +47,8 @@ def test_config0_tiny_opt_fp32_end_to_end(hb):
     kvd = harness.DeviceKV.from_host(desc, kvh)
     # ---- prefill through the library: ctx = 0, 64 rows, causal among them ----
     pre = harness.VerifySession(model, kvd, 1, 63, 1, 64, want_logits=True)
-    pre.forward(_i32(prompt[:1]), _i32([63]), [63], voted=_i32(prompt[None, 1:]))
+    t_last, t_k, t_voted = _i32(prompt[:1]), _i32([63]), _i32(prompt[None, 1:])   # named: must outlive the call
+    pre.forward(t_last, t_k, [63], voted=t_voted)
     torch.cuda.synchronize()
     assert pre.dev_status.item() == 0
     cache = orc.SeqCache(desc.n_layers, desc.n_kv_heads, desc.head_dim)
@@ -64,7 +65,8 @@ def test_config0_tiny_opt_fp32_end_to_end(hb):
     ssm_w = np.ones(3, np.float32)
     want = orc.verify_step(desc, W, [cache], [last], drafts[None], [4], ssm_w)
     ses = harness.VerifySession(model, kvd, 1, 4, 3, 64 + 5, want_logits=True)
-    ses.step(_i32([last]), _i32(drafts[None]), _i32([4]), [4], torch.ones(3, device="cuda:0"))
+    t_last, t_drafts, t_k, t_w = _i32([last]), _i32(drafts[None]), _i32([4]), torch.ones(3, device="cuda:0")
+    ses.step(t_last, t_drafts, t_k, [4], t_w)
     torch.cuda.synchronize()
     assert ses.dev_status.item() == 0
     assert np.array_equal(ses.voted.cpu().numpy(), want["voted"])
@@ -103,7 +105,8 @@ def _reduced_case(hb, wl, n_layers, B, n_cand, ctx_override=None, k_override=Non
     want = orc.verify_step(desc, W64, caches, last, drafts, ks, ssm_w)
     M = int((ks + 1).sum())
     ses = harness.VerifySession(model, kvd, B, k_max, wl.n_drafts, int((ctx + ks + 1).max()), max_rows=M, want_logits=True)
-    ses.step(_i32(last), _i32(drafts), _i32(ks), ks.tolist(), torch.ones(wl.n_drafts, device="cuda:0"))
+    t_last, t_drafts, t_k, t_w = _i32(last), _i32(drafts), _i32(ks), torch.ones(wl.n_drafts, device="cuda:0")
+    ses.step(t_last, t_drafts, t_k, ks.tolist(), t_w)
     torch.cuda.synchronize()
     assert ses.dev_status.item() == 0
     # votes: bit-exact
@@ -147,7 +150,10 @@ def _reduced_case(hb, wl, n_layers, B, n_cand, ctx_override=None, k_override=Non
             if c is None:
                 continue
             K, V = synth.gather_sequence_kv(img, l, b, c.ctx)
-            assert np.abs(K - c.K[l]).max() < tol and np.abs(V - c.V[l]).max() < tol
+            # the cache stores bf16: at most half an ulp (2^-9 relative; 2^-8 allowed) of storage rounding, on top
+            # of the absolute noise the fp16 activations upstream leave on O(1) values
+            for got, ref in ((K, c.K[l]), (V, c.V[l])):
+                assert (np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-2).all()
     return err, decisive_seqs
 
 
