@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of the verification step (vote -> verify forward -> accept + commit) on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input, everything resident in HBM.
+Default workload: the Llama-2-70B-shaped configuration, batch 16, context 1024, k = 8 (M = 144 scored
+positions), bf16 weights and KV pages, random-init weights, synthetic KV pages and drafts.
+
+Prints one JSON line: throughput in verified positions/s, the roofline of the dominant kernel (the
+weight-streaming projection GEMM; its device time comes from HIP events the library records around
+every launch of that kernel on the launch stream), and the CPU oracle timed on the host cores on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
+MFMA_PEAK_TFLOPS = 2500.0    # dense bf16/fp16 MFMA
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=2, help="index into the workload list (default: 70B b16 k8)")
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the real depth); for experiments")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-steps", type=int, default=3, help="extra steps run with the timing taps on")
+    return ap.parse_args()
+
+
+def cpu_baseline(wl, desc, M, ks, ctx, n_drafts):
+    """The oracle as it stands, on the host cores: one full-shape layer at the real M and context, the LM
+    head, the vote and the acceptance are timed; the layer time is multiplied by the layer count
+    (the full depth would need the 137 GB of weights on the host)."""
+    import numpy as np
+    from oracle import minions_oracle as orc
+    from paper_2402_15678_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    d1 = desc.with_layers(1)
+    W = synth.make_weights(d1, wl.seed)
+    kvh = synth.make_paged_kv(d1, ctx, ks, wl.seed)
+    B = len(ctx)
+    caches = []
+    for b in range(B):
+        K, V = synth.gather_sequence_kv(kvh, 0, b, int(ctx[b]))
+        caches.append(orc.SeqCache(1, d1.n_kv_heads, d1.head_dim, [K], [V]))
+    g = synth.stream(wl.seed, 900)
+    k_max = int(max(ks))
+    drafts = g.integers(0, desc.vocab, size=(B, n_drafts, max(1, k_max))).astype(np.int32)
+    last = g.integers(0, desc.vocab, size=B).astype(np.int32)
+    ssm_w = np.ones(n_drafts, np.float32)
+    t0 = time.perf_counter()
+    voted, _ = orc.vote_batch(drafts, ks, ssm_w)
+    t_vote = time.perf_counter() - t0
+    toks = [[int(last[b])] + [int(t) for t in voted[b, :ks[b]]] for b in range(B)]
+    # one layer + head through the oracle's own step; the head is timed on its own and subtracted
+    t0 = time.perf_counter()
+    logits = orc.decoder_step(d1, W, toks, caches)
+    t_layer_head = time.perf_counter() - t0
+    x = np.zeros((M, desc.d_model))
+    t0 = time.perf_counter()
+    h = orc._norm(d1, x + 1.0, W["final_norm_g"], W.get("final_norm_b"))
+    orc._linear(h, W["lm_head"])
+    t_head = time.perf_counter() - t0
+    greedy = np.full((B, k_max + 1), -1, np.int32)
+    t0 = time.perf_counter()
+    for b in range(B):
+        greedy[b, :len(toks[b])] = orc.greedy_tokens(logits[b])
+    orc.accept_batch(voted, greedy, ks, ctx, wl.block_size)
+    t_accept = time.perf_counter() - t0
+    t_layer = max(t_layer_head - t_head, 1e-9)
+    total = t_vote + desc.n_layers * t_layer + t_head + t_accept
+    return {"value": M / total, "unit": "positions/s", "cores": int(cores), "kind": "oracle",
+            "sample": "1 of %d layers at the full shape (M=%d rows, real contexts) + LM head + vote + accept; "
+                      "layer time x %d (extrapolated): layer %.2fs, head %.2fs" % (desc.n_layers, M, desc.n_layers,
+                                                                                 t_layer, t_head)}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); --gpus %d is not supported. "
+              "Run with --gpus 1." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2402_15678_amd import binding, harness, synth
+
+    wl = synth.WORKLOADS[args.workload]
+    desc = wl.desc if args.layers <= 0 else wl.desc.with_layers(args.layers)
+    dev = torch.device("cuda:0")
+    t_setup = time.perf_counter()
+    model = harness.DeviceModel.random_on_device(desc, wl.seed)
+    ctx = synth.draw_ctx_lens(wl)
+    ks = synth.draw_spec_lens(wl)
+    B, k_max, n = wl.batch, int(ks.max()), wl.n_drafts
+    M = int((ks + 1).sum())
+    kvd = harness.DeviceKV.random_on_device(desc, ctx, ks, wl.seed, wl.block_size)
+    max_ctx = int((ctx + ks + 1).max())
+    ses = harness.VerifySession(model, kvd, B, k_max, n, max_ctx, max_rows=M)
+    ctx0 = kvd.ctx_lens.clone()
+    g = synth.stream(wl.seed, 600)
+    last = torch.tensor(g.integers(0, desc.vocab, size=B).astype(np.int32), device=dev)
+
+    # greedy continuation by k_max sequential single-token steps of the library itself, then roll back
+    one = harness.VerifySession(model, kvd, B, 0, 1, max_ctx, max_rows=B)
+    zeros = torch.zeros((B,), dtype=torch.int32, device=dev)
+    cur = last.clone()
+    cont = []
+    dummy_voted = torch.zeros((B, 1), dtype=torch.int32, device=dev)
+    for _ in range(k_max):
+        one.forward(cur, zeros, [0] * B, voted=dummy_voted)
+        one.accept(zeros, voted=dummy_voted)
+        cur = one.next_last_tok.clone()
+        cont.append(cur.cpu().numpy())
+    kvd.ctx_lens.copy_(ctx0)
+    cont = np.stack(cont, axis=1) if cont else np.zeros((B, 0), np.int32)   # [B][k_max]
+    per = [synth.drafts_corrupted(cont[b, :ks[b]], n, wl.p_corrupt, desc.vocab, g) for b in range(B)]
+    drafts = torch.tensor(synth.pack_drafts(per, max(1, k_max)), device=dev)
+    spec = torch.tensor(ks, dtype=torch.int32, device=dev)
+    ssm_w = torch.ones((n,), dtype=torch.float32, device=dev)
+    h_spec = ks.tolist()
+    torch.cuda.synchronize()
+    t_setup = time.perf_counter() - t_setup
+
+    def step():
+        kvd.ctx_lens.copy_(ctx0)          # 4*B-byte device copy: the commit of the previous step is undone
+        ses.step(last, drafts, spec, h_spec, ssm_w)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert ses.dev_status.item() == 0
+    ms_per_step = dt / args.steps * 1e3
+    acc = ses.accepted_len.cpu().numpy()
+
+    # the same steps again with the timing taps on: per-family device time from HIP events on the launch stream
+    prof = None
+    if args.profile_steps > 0:
+        binding.mn_profile_enable(model.ctx, True)
+        t0 = time.perf_counter()
+        for _ in range(args.profile_steps):
+            step()
+        torch.cuda.synchronize()
+        dt_prof = time.perf_counter() - t0
+        prof = binding.mn_profile_collect(model.ctx)
+        binding.mn_profile_enable(model.ctx, False)
+
+    gemm_bytes_step = 2.0 * desc.gemm_params()          # every matrix parameter (2 bytes) is needed once per step
+    roofline = None
+    families = None
+    if prof:
+        ps = args.profile_steps
+        gemm_ms, gemm_n = prof["gemm"]
+        per_launch_ms = gemm_ms / max(1, gemm_n)
+        achieved = gemm_bytes_step * ps / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else 0.0
+        flops = 2.0 * M * desc.gemm_params() * ps
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "gemm_w16_kernel",
+                    "launches_per_step": gemm_n // ps, "avg_launch_us": per_launch_ms * 1e3,
+                    "mfma_tflops": flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0,
+                    "mfma_frac": flops / (gemm_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS if gemm_ms > 0 else 0.0}
+        families = {k: {"ms_per_step": v[0] / ps, "launches_per_step": v[1] // ps} for k, v in prof.items()}
+        families["_instrumented_ms_per_step"] = dt_prof / ps * 1e3
+        # attention: KV bytes streamed per step
+        kv_bytes = float(((ctx + ks + 1).astype(np.int64)).sum()) * 2 * desc.n_kv_heads * desc.head_dim * 2 * desc.n_layers
+        att_ms = prof["attention"][0] / ps
+        families["attention"]["kv_GBps"] = kv_bytes / (att_ms * 1e-3) / 1e9 if att_ms > 0 else 0.0
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(wl, desc, M, ks, ctx, n)
+
+    out = {
+        "metric": "verified_positions_per_sec", "value": M / (ms_per_step * 1e-3), "unit": "positions/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "storage_dtype": "bf16", "accumulate_dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "arch": "llama" if desc.arch == synth.ARCH_LLAMA else "opt",
+                   "n_layers": desc.n_layers, "d_model": desc.d_model, "batch": B, "k_max": k_max, "rows": M,
+                   "ctx_min": int(ctx.min()), "ctx_max": int(ctx.max()), "n_drafts": n, "block_size": wl.block_size,
+                   "seed": wl.seed},
+        "accepted_tokens_per_sec": float((acc + 1).sum()) / (ms_per_step * 1e-3),
+        "acceptance_rate": float(acc.sum()) / max(1, int(ks.sum())),
+        "setup_s": t_setup,
+        "roofline": roofline, "kernel_families": families, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

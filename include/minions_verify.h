@@ -209,6 +209,24 @@ mn_status mn_attention(mn_ctx *ctx, const void *q, const int32_t *spec_len, cons
                        int max_ctx, const mn_kv *kv, int layer, void *out, void *workspace, size_t workspace_bytes,
                        int32_t *dev_status, void *stream);
 
+/* ---- timing taps (for benchmarks; off by default) --------------------------------------------- */
+
+/* Kernel families of the step, as indexed in mn_profile_collect's arrays. */
+enum {
+  MN_PROF_PREPARE = 0, MN_PROF_NORM = 1, MN_PROF_GEMM = 2, MN_PROF_ROPE_APPEND = 3, MN_PROF_ATTENTION = 4,
+  MN_PROF_ACT = 5, MN_PROF_ARGMAX = 6, MN_PROF_VOTE = 7, MN_PROF_ACCEPT = 8, MN_PROF_KINDS = 9
+};
+
+/* With on != 0 every later call on ctx brackets each kernel-family launch with a pair of HIP events
+ * on the call's stream (host-side objects; no device memory is allocated).  The taps cost a few
+ * microseconds of stream time per launch, so throughput is measured with them off. */
+mn_status mn_profile_enable(mn_ctx *ctx, int on);
+
+/* After the caller has synchronised the stream: ms[kind] = summed device time of the launches of
+ * that family since the last collect, counts[kind] = number of launches.  Both arrays hold
+ * MN_PROF_KINDS entries.  Resets the taps. */
+mn_status mn_profile_collect(mn_ctx *ctx, double *ms, int *counts);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,9 @@ MN_DEV_BLOCK_TABLE, MN_DEV_SPEC_LEN, MN_DEV_TOKEN, MN_DEV_DRAFTS = 1, 2, 4, 8
 MN_MAX_DRAFTS, MN_MAX_BATCH, MN_MAX_SPLIT_K = 64, 4096, 16
 
 EXPORTS = ("mn_create", "mn_destroy", "mn_last_error", "mn_status_str", "mn_workspace_bytes", "mn_mv_vote",
-           "mn_verify_forward", "mn_accept_and_commit", "mn_proj_gemm", "mn_attention")
+           "mn_verify_forward", "mn_accept_and_commit", "mn_proj_gemm", "mn_attention", "mn_profile_enable",
+           "mn_profile_collect")
+PROF_KINDS = ("prepare", "norm", "gemm", "rope_append", "attention", "act", "argmax", "vote", "accept")
 
 
 class ModelDesc(C.Structure):
@@ -71,6 +73,10 @@ def _load() -> C.CDLL:
     lib.mn_proj_gemm.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, sz, vp]
     lib.mn_attention.restype = i32
     lib.mn_attention.argtypes = [vp, vp, vp, C.POINTER(C.c_int32), i32, i32, C.POINTER(KV), i32, vp, vp, sz, vp, vp]
+    lib.mn_profile_enable.restype = i32
+    lib.mn_profile_enable.argtypes = [vp, i32]
+    lib.mn_profile_collect.restype = i32
+    lib.mn_profile_collect.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int)]
     return lib
 
 
@@ -140,3 +146,15 @@ def mn_attention(ctx, q, spec_len, h_spec_len, B, max_ctx, kv: KV, layer, out, w
                  dev_status=None, stream=None) -> None:
     _check(lib.mn_attention(ctx, q, spec_len, h_spec_len, B, max_ctx, C.byref(kv), layer, out, workspace,
                             workspace_bytes, dev_status, stream), ctx)
+
+
+def mn_profile_enable(ctx, on: bool) -> None:
+    _check(lib.mn_profile_enable(ctx, 1 if on else 0), ctx)
+
+
+def mn_profile_collect(ctx):
+    """{family: (summed ms, launches)} since the last collect; synchronise the stream first."""
+    ms = (C.c_double * len(PROF_KINDS))()
+    cnt = (C.c_int * len(PROF_KINDS))()
+    _check(lib.mn_profile_collect(ctx, ms, cnt), ctx)
+    return {k: (ms[i], cnt[i]) for i, k in enumerate(PROF_KINDS)}

@@ -12,8 +12,39 @@
 
 using namespace mn;
 
+// Timing taps: pairs of events around kernel-family launches, summed per family on collect.
+struct Prof {
+  bool on = false;
+  std::vector<hipEvent_t> pool;   // created on demand, reused after every collect
+  std::vector<int> kind;          // kind[i] belongs to the pair (pool[2i], pool[2i+1])
+  size_t used = 0;                // events handed out since the last collect
+  hipEvent_t take() {
+    if (used == pool.size()) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) return nullptr;
+      pool.push_back(e);
+    }
+    return pool[used++];
+  }
+  ~Prof() { for (hipEvent_t e : pool) (void)hipEventDestroy(e); }
+};
+
+struct Tap {  // RAII bracket around one launch
+  Prof* p; hipStream_t st; hipEvent_t end = nullptr;
+  Tap(Prof* prof, int kind, hipStream_t s) : p(prof && prof->on ? prof : nullptr), st(s) {
+    if (!p) return;
+    hipEvent_t b = p->take();
+    end = p->take();
+    if (!b || !end) { p = nullptr; return; }
+    p->kind.push_back(kind);
+    (void)hipEventRecord(b, st);
+  }
+  ~Tap() { if (p) (void)hipEventRecord(end, st); }
+};
+
 struct mn_ctx {
   mn_model_desc d;
+  Prof prof;
   const void *tok_emb, *pos_emb, *final_norm_g, *final_norm_b, *lm_head;
   std::vector<const void*> ln1_g, ln1_b, wqkv, bqkv, wo, bo, ln2_g, ln2_b, w1, b1, w2, b2;
   std::string err;
@@ -175,7 +206,10 @@ extern "C" mn_status mn_mv_vote(mn_ctx* ctx, const int32_t* drafts, const int32_
   if (B == 0) return MN_OK;
   if (!spec_len || !ssm_w || !voted_ssm) return fail(ctx, MN_ENULL, "mn_mv_vote: spec_len/ssm_w/voted_ssm is NULL");
   if (k_max > 0 && (!drafts || !voted)) return fail(ctx, MN_ENULL, "mn_mv_vote: drafts/voted is NULL");
-  launch_vote(drafts, spec_len, ssm_w, B, n, k_max, mode, voted, voted_ssm, dev_status, (hipStream_t)stream);
+  {
+    Tap t(ctx ? &ctx->prof : nullptr, MN_PROF_VOTE, (hipStream_t)stream);
+    launch_vote(drafts, spec_len, ssm_w, B, n, k_max, mode, voted, voted_ssm, dev_status, (hipStream_t)stream);
+  }
   return hip_check(ctx, "mn_mv_vote");
 }
 
@@ -192,8 +226,11 @@ extern "C" mn_status mn_accept_and_commit(mn_ctx* ctx, const int32_t* voted, con
   if (!greedy || !spec_len || !accepted_len || !out_tokens || !n_out || !next_last_tok || !blocks_in_use)
     return fail(ctx, MN_ENULL, "mn_accept_and_commit: a required pointer is NULL");
   if (k_max > 0 && !voted) return fail(ctx, MN_ENULL, "mn_accept_and_commit: voted is NULL");
-  launch_accept_commit(voted, greedy, spec_len, B, k_max, kv->ctx_lens, kv->block_size, kv->max_blocks_per_seq,
-                       accepted_len, out_tokens, n_out, next_last_tok, blocks_in_use, dev_status, (hipStream_t)stream);
+  {
+    Tap t(ctx ? &ctx->prof : nullptr, MN_PROF_ACCEPT, (hipStream_t)stream);
+    launch_accept_commit(voted, greedy, spec_len, B, k_max, kv->ctx_lens, kv->block_size, kv->max_blocks_per_seq,
+                         accepted_len, out_tokens, n_out, next_last_tok, blocks_in_use, dev_status, (hipStream_t)stream);
+  }
   return hip_check(ctx, "mn_accept_and_commit");
 }
 
@@ -262,6 +299,7 @@ static void run_prepare(mn_ctx* c, const Ws& w, const int32_t* last_tok, const i
   p.seq_row0 = w.at<int32_t>(w.L.seq_row0); p.seq_ctx = w.at<int32_t>(w.L.seq_ctx); p.seq_ok = w.at<int32_t>(w.L.seq_ok);
   p.rope_cos = w.at<float>(w.L.rope_cos); p.rope_sin = w.at<float>(w.L.rope_sin);
   p.dev_status = dev_status;
+  Tap t(&c->prof, MN_PROF_PREPARE, st);
   launch_prepare(p, st);
 }
 
@@ -314,12 +352,14 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
     n.pos_emb = embed ? c->pos_emb : nullptr;
     n.row_tok = rows.row_tok; n.row_pos = rows.row_pos;
     n.gain = gain; n.shift = shift; n.eps = d.norm_eps; n.h = h; n.M = M; n.d = d.d_model; n.dtype = d.dtype;
+    Tap t(&c->prof, MN_PROF_NORM, st);
     launch_norm(n, st);
     pend = nullptr; pend_n = 0; pend_bias = nullptr;
   };
   auto gemm = [&](const void* a, const void* wt, float* out, int N, int K, int split) {
     GemmArgs g{};
     g.a = a; g.w = wt; g.out = out; g.bias = nullptr; g.M = M; g.N = N; g.K = K; g.split_k = split; g.dtype = d.dtype;
+    Tap t(&c->prof, MN_PROF_GEMM, st);
     launch_gemm(g, st);
   };
 
@@ -338,14 +378,20 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
     r.knew = d.dtype == MN_DT_BF16 ? w.at<void>(w.L.knew) : nullptr;
     r.vnew = d.dtype == MN_DT_BF16 ? w.at<void>(w.L.vnew) : nullptr;
     r.M = M; r.H = d.n_heads; r.Hkv = d.n_kv_heads; r.hd = d.head_dim; r.dtype = d.dtype;
-    launch_rope_append(r, st);
+    {
+      Tap t(&c->prof, MN_PROF_ROPE_APPEND, st);
+      launch_rope_append(r, st);
+    }
     AttnArgs at{};
     at.q = r.q; at.out = w.at<void>(w.L.attn); at.rows = rows; at.kv = r.kv;
     at.knew = r.knew; at.vnew = r.vnew;
     at.B = B; at.M = M; at.H = d.n_heads; at.Hkv = d.n_kv_heads; at.hd = d.head_dim; at.dtype = d.dtype;
     at.max_ctx = max_ctx; at.max_q = max_q;
     at.scratch = w.at<float>(w.L.attn_scratch); at.scratch_bytes = w.L.attn_scratch_bytes;
-    launch_attention(at, st);
+    {
+      Tap t(&c->prof, MN_PROF_ATTENTION, st);
+      launch_attention(at, st);
+    }
     s = gemm_pick_split(M, d.d_model, hdim, d.dtype);
     gemm(at.out, c->wo[l], part, d.d_model, hdim, s);
     pend = part; pend_n = s; pend_bias = (const float*)c->bo[l];
@@ -355,7 +401,10 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
     ActArgs ac{};
     ac.partials = part; ac.n_partials = s; ac.bias = (const float*)c->b1[l]; ac.act = w.at<void>(w.L.act);
     ac.M = M; ac.F = d.d_ffn; ac.swiglu = llama ? 1 : 0; ac.dtype = d.dtype;
-    launch_act(ac, st);
+    {
+      Tap t(&c->prof, MN_PROF_ACT, st);
+      launch_act(ac, st);
+    }
     s = gemm_pick_split(M, d.d_model, d.d_ffn, d.dtype);
     gemm(ac.act, c->w2[l], part, d.d_model, d.d_ffn, s);
     pend = part; pend_n = s; pend_bias = (const float*)c->b2[l];
@@ -363,7 +412,10 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
   norm((const float*)c->final_norm_g, (const float*)c->final_norm_b, d.n_layers == 0);
   float* lg = logits ? logits : w.at<float>(w.L.logits);
   gemm(h, c->lm_head, lg, d.vocab, d.d_model, 1);
-  launch_argmax_rows(lg, M, d.vocab, rows, k_max, greedy, B, st);
+  {
+    Tap t(&c->prof, MN_PROF_ARGMAX, st);
+    launch_argmax_rows(lg, M, d.vocab, rows, k_max, greedy, B, st);
+  }
   return hip_check(c, who);
 }
 
@@ -380,6 +432,7 @@ extern "C" mn_status mn_proj_gemm(mn_ctx* c, const void* a, const void* w, const
   hipStream_t st = (hipStream_t)stream;
   GemmArgs g{};
   g.a = a; g.w = w; g.bias = bias; g.M = M; g.N = N; g.K = K; g.split_k = s; g.dtype = MN_DT_BF16;
+  Tap t(c ? &c->prof : nullptr, MN_PROF_GEMM, st);
   if (s == 1) {
     g.out = out;
     launch_gemm(g, st);
@@ -426,6 +479,34 @@ extern "C" mn_status mn_attention(mn_ctx* c, const void* q, const int32_t* spec_
   at.B = B; at.M = M; at.H = d.n_heads; at.Hkv = d.n_kv_heads; at.hd = d.head_dim; at.dtype = d.dtype;
   at.max_ctx = max_ctx; at.max_q = max_q;
   at.scratch = w.at<float>(w.L.attn_scratch); at.scratch_bytes = w.L.attn_scratch_bytes;
-  launch_attention(at, st);
+  {
+    Tap t(&c->prof, MN_PROF_ATTENTION, st);
+    launch_attention(at, st);
+  }
   return hip_check(c, who);
+}
+
+// ---- timing taps ------------------------------------------------------------------------------------
+extern "C" mn_status mn_profile_enable(mn_ctx* c, int on) {
+  if (!c) return MN_ENULL;
+  c->prof.on = on != 0;
+  return MN_OK;
+}
+
+extern "C" mn_status mn_profile_collect(mn_ctx* c, double* ms, int* counts) {
+  if (!c) return MN_ENULL;
+  if (!ms || !counts) return fail(c, MN_ENULL, "mn_profile_collect: ms/counts is NULL");
+  for (int k = 0; k < MN_PROF_KINDS; ++k) { ms[k] = 0.0; counts[k] = 0; }
+  Prof& p = c->prof;
+  mn_status rc = MN_OK;
+  for (size_t i = 0; i < p.kind.size(); ++i) {
+    float t = 0.f;
+    const hipError_t e = hipEventElapsedTime(&t, p.pool[2 * i], p.pool[2 * i + 1]);
+    if (e != hipSuccess) { rc = fail(c, MN_EHIP, "mn_profile_collect: %s (synchronise the stream first)", hipGetErrorString(e)); break; }
+    ms[p.kind[i]] += t;
+    counts[p.kind[i]] += 1;
+  }
+  p.kind.clear();
+  p.used = 0;
+  return rc;
 }
