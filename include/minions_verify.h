@@ -86,6 +86,10 @@ typedef struct {
  *   bqkv [(H + 2 Hkv) hd] (OPT)   wo [d][H hd]    bo [d] (OPT)
  *   w1: OPT [F][d], Llama [2F][d] with rows [0,F) = gate and [F,2F) = up;  b1 [F] (OPT)
  *   w2 [d][F]                     b2 [d] (OPT)
+ * Matrix layout.  fp32 models: row-major as written above.  bf16 models: the five matrices
+ * (wqkv, wo, w1, w2, lm_head) must be in the library's packed streaming layout, produced from the
+ * row-major matrix by mn_pack_weight (w1 of a Llama-style model with interleave_half = F); the
+ * embedding tables stay row-major.
  */
 typedef struct {
   const void *tok_emb, *pos_emb, *final_norm_g, *final_norm_b, *lm_head;
@@ -129,6 +133,22 @@ const char *mn_status_str(mn_status s);
  * positions, B sequences and contexts up to max_ctx tokens (including the scored ones).
  * The workspace must be 256-byte aligned.  Returns 0 on invalid arguments. */
 size_t mn_workspace_bytes(const mn_ctx *ctx, int B, int max_rows, int max_ctx);
+
+/* ---- weight packing (bf16 models) ---------------------------------------------------------------
+ * HBM streams near its peak only over long contiguous runs, so the projection kernel reads its
+ * weights pre-tiled: blocks of 128 output columns x 128 inputs, 32 KB each, consecutive along k for
+ * one column block, every 1 KB inside in the order the MFMA lanes consume it.  Columns are padded
+ * with zeros to a multiple of 128. */
+
+/* Bytes of the packed form of an [N][K] bf16 matrix (K a multiple of 128).  0 on invalid arguments. */
+size_t mn_packed_weight_bytes(int N, int K);
+
+/* src dev [N][K] bf16 row-major -> dst dev packed (mn_packed_weight_bytes(N, K) bytes, 256-byte
+ * aligned, not overlapping src).  interleave_half = 0 keeps the row order.  interleave_half = F > 0
+ * (N must be 2F, F a multiple of 16) is for the gate||up matrix of a SwiGLU FFN: packed column tile
+ * 2t holds gate rows [16t, 16t+16) and tile 2t+1 up rows F + [16t, 16t+16), which lets the
+ * projection kernel apply silu(gate) * up in its epilogue. */
+mn_status mn_pack_weight(const void *src, void *dst, int N, int K, int interleave_half, void *stream);
 
 /* ---- the verification step --------------------------------------------------------------- */
 
@@ -190,11 +210,12 @@ mn_status mn_accept_and_commit(mn_ctx *ctx, const int32_t *voted, const int32_t 
 /* ---- component entry points (the kernels mn_verify_forward is made of, at their own shapes) -- */
 
 /* The projection GEMM of a bf16 model: out[m][n] = sum_k a[m][k] * w[n][k] (+ bias[n]).
- * a dev [M][K] fp16 (the activation type of bf16 models), w dev [N][K] bf16 (widened exactly to
- * fp16 in registers), fp16 MFMA with fp32 accumulation, bias dev [N] fp32 or NULL, out dev [M][N]
+ * a dev [M][K] fp16 (the activation type of bf16 models), w dev: the [N][K] bf16 matrix in packed
+ * layout (mn_pack_weight with interleave_half = 0; widened exactly to fp16 in registers),
+ * fp16 MFMA with fp32 accumulation, bias dev [N] fp32 or NULL, out dev [M][N]
  * fp32.  split_k in [0, MN_MAX_SPLIT_K]: 0 lets the library choose; with split_k > 1 `workspace`
  * (dev, >= split_k*M*N*4 bytes, 256-byte aligned) holds the partial sums, which are added in a
- * fixed order.  K must be a multiple of 64; M >= 0, N >= 1 arbitrary. */
+ * fixed order.  K must be a multiple of 128; M >= 0, N >= 1 arbitrary. */
 mn_status mn_proj_gemm(mn_ctx *ctx, const void *a, const void *w, const float *bias, float *out, int M, int N, int K,
                        int split_k, void *workspace, size_t workspace_bytes, void *stream);
 

@@ -22,7 +22,7 @@ MN_MAX_DRAFTS, MN_MAX_BATCH, MN_MAX_SPLIT_K = 64, 4096, 16
 
 EXPORTS = ("mn_create", "mn_destroy", "mn_last_error", "mn_status_str", "mn_workspace_bytes", "mn_mv_vote",
            "mn_verify_forward", "mn_accept_and_commit", "mn_proj_gemm", "mn_attention", "mn_profile_enable",
-           "mn_profile_collect")
+           "mn_profile_collect", "mn_packed_weight_bytes", "mn_pack_weight")
 PROF_KINDS = ("prepare", "norm", "gemm", "rope_append", "attention", "act", "argmax", "vote", "accept")
 
 
@@ -73,6 +73,10 @@ def _load() -> C.CDLL:
     lib.mn_proj_gemm.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, sz, vp]
     lib.mn_attention.restype = i32
     lib.mn_attention.argtypes = [vp, vp, vp, C.POINTER(C.c_int32), i32, i32, C.POINTER(KV), i32, vp, vp, sz, vp, vp]
+    lib.mn_packed_weight_bytes.restype = sz
+    lib.mn_packed_weight_bytes.argtypes = [i32, i32]
+    lib.mn_pack_weight.restype = i32
+    lib.mn_pack_weight.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.mn_profile_enable.restype = i32
     lib.mn_profile_enable.argtypes = [vp, i32]
     lib.mn_profile_collect.restype = i32
@@ -158,3 +162,11 @@ def mn_profile_collect(ctx):
     cnt = (C.c_int * len(PROF_KINDS))()
     _check(lib.mn_profile_collect(ctx, ms, cnt), ctx)
     return {k: (ms[i], cnt[i]) for i, k in enumerate(PROF_KINDS)}
+
+
+def mn_packed_weight_bytes(N: int, K: int) -> int:
+    return int(lib.mn_packed_weight_bytes(N, K))
+
+
+def mn_pack_weight(src, dst, N, K, interleave_half=0, stream=None) -> None:
+    _check(lib.mn_pack_weight(src, dst, N, K, interleave_half, stream), None)

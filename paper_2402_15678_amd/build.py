@@ -33,6 +33,7 @@ def _run(cmd):
 def build(verbose: bool = False) -> str:
     """Compile every source and link the shared library; always recompiles."""
     hipcc = _hipcc()
+    extra = os.environ.get("MN_EXTRA_HIPCC_FLAGS", "").split()
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     objs = []
@@ -41,7 +42,7 @@ def build(verbose: bool = False) -> str:
         for src in SOURCES:
             obj = os.path.join(objdir, src.replace(".hip", ".o"))
             objs.append(obj)
-            jobs.append(ex.submit(_run, [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]))
+            jobs.append(ex.submit(_run, [hipcc, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]))
         for src, j in zip(SOURCES, jobs):
             out = j.result()
             if verbose and out.strip():

@@ -113,6 +113,8 @@ extern "C" mn_status mn_create(mn_ctx** out, const mn_model_desc* d, const mn_we
     return fail(nullptr, MN_EUNSUPPORTED, "mn_create: d_model %d (must be a multiple of 64, at most 8192)", d->d_model);
   if ((d->n_heads * d->head_dim) % 64 || d->d_ffn % 64)
     return fail(nullptr, MN_EUNSUPPORTED, "mn_create: n_heads*head_dim and d_ffn must be multiples of 64");
+  if (d->dtype == MN_DT_BF16 && (d->d_model % 128 || (d->n_heads * d->head_dim) % 128 || d->d_ffn % 128))
+    return fail(nullptr, MN_EUNSUPPORTED, "mn_create: bf16 models need d_model, n_heads*head_dim and d_ffn to be multiples of 128");
   if (!(d->norm_eps >= 0.f)) return fail(nullptr, MN_EINVAL, "mn_create: norm_eps");
   if (d->arch == MN_ARCH_LLAMA && !(d->rope_base > 0.f)) return fail(nullptr, MN_EINVAL, "mn_create: rope_base");
   if (!w->tok_emb || !w->lm_head || !w->final_norm_g) return fail(nullptr, MN_ENULL, "mn_create: tok_emb/lm_head/final_norm_g");
@@ -396,17 +398,24 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
     gemm(at.out, c->wo[l], part, d.d_model, hdim, s);
     pend = part; pend_n = s; pend_bias = (const float*)c->bo[l];
     norm((const float*)c->ln2_g[l], (const float*)c->ln2_b[l], false);
-    s = gemm_pick_split(M, w1r, d.d_model, d.dtype);
-    gemm(h, c->w1[l], part, w1r, d.d_model, s);
-    ActArgs ac{};
-    ac.partials = part; ac.n_partials = s; ac.bias = (const float*)c->b1[l]; ac.act = w.at<void>(w.L.act);
-    ac.M = M; ac.F = d.d_ffn; ac.swiglu = llama ? 1 : 0; ac.dtype = d.dtype;
-    {
+    void* act = w.at<void>(w.L.act);
+    if (llama && d.dtype == MN_DT_BF16) {
+      // gate||up projection with silu(gate) * up applied in the kernel's epilogue
+      GemmArgs g{};
+      g.a = h; g.w = c->w1[l]; g.swiglu_act = act; g.M = M; g.N = w1r; g.K = d.d_model; g.split_k = 1; g.dtype = d.dtype;
+      Tap t(&c->prof, MN_PROF_GEMM, st);
+      launch_gemm(g, st);
+    } else {
+      s = gemm_pick_split(M, w1r, d.d_model, d.dtype);
+      gemm(h, c->w1[l], part, w1r, d.d_model, s);
+      ActArgs ac{};
+      ac.partials = part; ac.n_partials = s; ac.bias = (const float*)c->b1[l]; ac.act = act;
+      ac.M = M; ac.F = d.d_ffn; ac.swiglu = llama ? 1 : 0; ac.dtype = d.dtype;
       Tap t(&c->prof, MN_PROF_ACT, st);
       launch_act(ac, st);
     }
     s = gemm_pick_split(M, d.d_model, d.d_ffn, d.dtype);
-    gemm(ac.act, c->w2[l], part, d.d_model, d.d_ffn, s);
+    gemm(act, c->w2[l], part, d.d_model, d.d_ffn, s);
     pend = part; pend_n = s; pend_bias = (const float*)c->b2[l];
   }
   norm((const float*)c->final_norm_g, (const float*)c->final_norm_b, d.n_layers == 0);
@@ -419,16 +428,32 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
   return hip_check(c, who);
 }
 
+// ---- weight packing ---------------------------------------------------------------------------------
+extern "C" size_t mn_packed_weight_bytes(int N, int K) {
+  if (N < 1 || K < 128 || K % 128) return 0;
+  return packed_weight_elems(N, K) * 2;
+}
+
+extern "C" mn_status mn_pack_weight(const void* src, void* dst, int N, int K, int interleave_half, void* stream) {
+  if (N < 1 || K < 128 || K % 128) return fail(nullptr, MN_ESHAPE, "mn_pack_weight: N=%d K=%d (K must be a positive multiple of 128)", N, K);
+  if (interleave_half < 0 || (interleave_half > 0 && (N != 2 * interleave_half || interleave_half % 16)))
+    return fail(nullptr, MN_ESHAPE, "mn_pack_weight: interleave_half=%d needs N == 2*half and half %% 16 == 0", interleave_half);
+  if (!src || !dst) return fail(nullptr, MN_ENULL, "mn_pack_weight: src/dst is NULL");
+  if ((uintptr_t)dst & 255) return fail(nullptr, MN_EINVAL, "mn_pack_weight: dst not 256-byte aligned");
+  launch_pack_weight(src, dst, N, K, interleave_half, (hipStream_t)stream);
+  return hip_check(nullptr, "mn_pack_weight");
+}
+
 // ---- component entry points -----------------------------------------------------------------------
 extern "C" mn_status mn_proj_gemm(mn_ctx* c, const void* a, const void* w, const float* bias, float* out, int M, int N,
                                   int K, int split_k, void* workspace, size_t workspace_bytes, void* stream) {
   const char* who = "mn_proj_gemm";
-  if (M < 0 || N < 1 || K < 64 || K % 64) return fail(c, MN_ESHAPE, "%s: M=%d N=%d K=%d (K must be a positive multiple of 64)", who, M, N, K);
+  if (M < 0 || N < 1 || K < 128 || K % 128) return fail(c, MN_ESHAPE, "%s: M=%d N=%d K=%d (K must be a positive multiple of 128)", who, M, N, K);
   if (split_k < 0 || split_k > MN_MAX_SPLIT_K) return fail(c, MN_EINVAL, "%s: split_k = %d", who, split_k);
   if (M == 0) return MN_OK;
   if (!a || !w || !out) return fail(c, MN_ENULL, "%s: a/w/out is NULL", who);
   int s = split_k ? split_k : gemm_pick_split(M, N, K, MN_DT_BF16);
-  if (s > K / 64) s = K / 64;
+  if (s > K / 128) s = K / 128;
   hipStream_t st = (hipStream_t)stream;
   GemmArgs g{};
   g.a = a; g.w = w; g.bias = bias; g.M = M; g.N = N; g.K = K; g.split_k = s; g.dtype = MN_DT_BF16;

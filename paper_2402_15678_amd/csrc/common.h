@@ -9,6 +9,7 @@ typedef uint16_t bf16_t;  // raw bf16 pattern (storage type of weights and KV pa
 typedef _Float16 f16_t;   // activation type in bf16 models (see the note below)
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -36,15 +37,17 @@ __device__ __forceinline__ uint32_t pack2h(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
 }
 // 8 bf16 (16 bytes) -> 8 fp16, exact for magnitudes in [2^-14, 65504]
-__device__ __forceinline__ f16x8 bf16x8_to_f16x8(uint4 u) {
+__device__ __forceinline__ f16x8 bf16x8_to_f16x8(u32x4 u) {
   union { f16x8 v; uint32_t w[4]; } r;
-  const uint32_t in[4] = {u.x, u.y, u.z, u.w};
+  const uint32_t in[4] = {u[0], u[1], u[2], u[3]};
 #pragma unroll
   for (int i = 0; i < 4; ++i)
     r.w[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(__uint_as_float(in[i] << 16),
                                                                      __uint_as_float(in[i] & 0xffff0000u)));
   return r.v;
 }
+
+__device__ __forceinline__ f16x8 bf16x8_to_f16x8(uint4 u) { return bf16x8_to_f16x8((u32x4){u.x, u.y, u.z, u.w}); }
 
 template <typename T> struct Store;
 template <> struct Store<float> {

@@ -70,12 +70,15 @@ void launch_argmax_rows(const float* logits, int M, int V, const RowInfo& rows, 
 // ---- gemm.hip ----
 struct GemmArgs {
   const void* a;  // [M][K] activation type (fp32 in fp32 models, fp16 in bf16 models)
-  const void* w;  // [N][K] storage type
+  const void* w;  // fp32 models: [N][K] row-major; bf16 models: the packed layout of gemm.hip
   float* out;     // [S][M][N] fp32 partial sums (S = split_k); bias added to split 0 when given
+  void* swiglu_act;  // non-null: fused SwiGLU epilogue, fp16 [M][N/2] (bf16 models, split_k == 1, interleaved packing)
   const float* bias;
   int M, N, K, split_k, dtype;
 };
 int gemm_pick_split(int M, int N, int K, int dtype);
+size_t packed_weight_elems(int N, int K);
+void launch_pack_weight(const void* src, void* dst, int N, int K, int half, hipStream_t st);
 void launch_gemm(const GemmArgs& a, hipStream_t st);
 void launch_reduce_partials(const float* partials, int S, size_t stride, float* out, size_t n, hipStream_t st);
 

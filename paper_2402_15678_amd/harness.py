@@ -40,6 +40,33 @@ def stream_ptr() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
+def pack_matrix(w: torch.Tensor, interleave_half: int = 0) -> torch.Tensor:
+    """Row-major bf16 [N][K] on the device -> the library's packed streaming layout (a new tensor)."""
+    N, K = w.shape
+    nbytes = B.mn_packed_weight_bytes(N, K)
+    if nbytes == 0:
+        raise ValueError("cannot pack a %dx%d matrix" % (N, K))
+    out = torch.empty((nbytes // 2,), dtype=torch.bfloat16, device=w.device)
+    B.mn_pack_weight(w.data_ptr(), out.data_ptr(), N, K, interleave_half, stream_ptr())
+    return out
+
+
+PACKED_KEYS = ("wqkv", "wo", "w1", "w2", "lm_head")
+
+
+def pack_model_tensors(desc: synth.ModelDesc, t: Dict[str, object]) -> None:
+    """In bf16 models replace the five projection matrices by their packed form, in place."""
+    if desc.dtype != synth.DT_BF16:
+        return
+    half = desc.d_ffn if desc.arch == synth.ARCH_LLAMA else 0
+    t["lm_head"] = pack_matrix(t["lm_head"])
+    for Lw in t["layers"]:
+        for k in ("wqkv", "wo", "w2"):
+            Lw[k] = pack_matrix(Lw[k])
+        Lw["w1"] = pack_matrix(Lw["w1"], half)
+    torch.cuda.synchronize()
+
+
 class DeviceModel:
     """Weights on the device + the library context."""
 
@@ -81,6 +108,7 @@ class DeviceModel:
         conv = lambda k, a: to_device(a, desc.dtype if k in mats else synth.DT_F32)
         t: Dict[str, object] = {k: conv(k, v) for k, v in W.items() if k != "layers"}
         t["layers"] = [{k: conv(k, v) for k, v in Lw.items()} for Lw in W["layers"]]
+        pack_model_tensors(desc, t)
         return cls(desc, t)
 
     @classmethod
@@ -107,9 +135,13 @@ class DeviceModel:
             t["pos_emb"] = mat(desc.max_pos, d)
             t["final_norm_b"] = vec(d)
         layers = []
+        bf = desc.dtype == synth.DT_BF16
+        half = desc.d_ffn if desc.arch == synth.ARCH_LLAMA else 0
+        pk = (lambda w, h=0: pack_matrix(w, h)) if bf else (lambda w, h=0: w)
+        t["lm_head"] = pk(t["lm_head"])
         for _ in range(desc.n_layers):
-            Lw = {"wqkv": mat(desc.n_qkv, d), "wo": mat(d, desc.n_heads * hd), "w1": mat(desc.w1_rows, d),
-                  "w2": mat(d, desc.d_ffn), "ln1_g": vec(d, 1.0), "ln2_g": vec(d, 1.0)}
+            Lw = {"wqkv": pk(mat(desc.n_qkv, d)), "wo": pk(mat(d, desc.n_heads * hd)), "w1": pk(mat(desc.w1_rows, d), half),
+                  "w2": pk(mat(d, desc.d_ffn)), "ln1_g": vec(d, 1.0), "ln2_g": vec(d, 1.0)}
             if opt:
                 Lw.update({"ln1_b": vec(d), "ln2_b": vec(d), "bqkv": vec(desc.n_qkv), "bo": vec(d),
                            "b1": vec(desc.d_ffn), "b2": vec(d)})

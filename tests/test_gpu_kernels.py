@@ -105,14 +105,14 @@ def test_accept_commit_bit_exact(hb, B, k_max):
 # ---------------------------------------------------------------------------- GEMM
 @pytest.mark.parametrize("M,N,K,split", [(5, 256, 256, 1), (40, 5120, 5120, 0), (144, 8192, 8192, 0), (144, 1000, 1024, 4),
                                          (17, 50272, 512, 1), (144, 10240, 8192, 2), (200, 3072, 2048, 0),
-                                         (608, 2048, 8192, 0), (1, 64, 64, 1), (144, 8192, 28672, 0)])
+                                         (608, 2048, 8192, 0), (1, 64, 128, 1), (144, 8192, 28672, 0), (144, 640, 8192, 16)])
 def test_proj_gemm_matches_fp64(hb, M, N, K, split):
     harness, binding = hb
     g = synth.stream(79, M, N, K)
     a = g.standard_normal((M, K), dtype=np.float32).astype(np.float16).astype(np.float32)   # fp16 activations
     w = synth.storage_round(g.standard_normal((N, K), dtype=np.float32) * 0.05, synth.DT_BF16)
     bias = g.standard_normal(N).astype(np.float32)
-    a_d, w_d = harness.to_device_act(a, synth.DT_BF16), harness.to_device(w, synth.DT_BF16)
+    a_d, w_d = harness.to_device_act(a, synth.DT_BF16), harness.pack_matrix(harness.to_device(w, synth.DT_BF16))
     b_d = torch.from_numpy(bias).cuda()
     out = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda:0")
     ws = torch.empty((16 * M * N * 4 + 256,), dtype=torch.uint8, device="cuda:0")
@@ -151,7 +151,7 @@ def test_attention_matches_oracle(hb, name, desc, ctx_lens, spec_lens):
     q = g.standard_normal((M, desc.n_heads, desc.head_dim), dtype=np.float32)
     if desc.dtype == synth.DT_BF16:
         q = q.astype(np.float16).astype(np.float32)                                   # fp16 activations
-    tiny = synth.ModelDesc(desc.arch, desc.dtype, 1, 64, desc.n_heads, desc.n_kv_heads, desc.head_dim, 64, 8, 4096)
+    tiny = synth.ModelDesc(desc.arch, desc.dtype, 1, 128, desc.n_heads, desc.n_kv_heads, desc.head_dim, 128, 8, 4096)
     model = harness.DeviceModel.from_host(tiny, synth.make_weights(tiny, 1))
     kvd = harness.DeviceKV.from_host(desc, kvh)
     kvd.ctx_lens.copy_(torch.from_numpy(kvh.ctx_lens))
