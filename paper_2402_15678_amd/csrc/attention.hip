@@ -398,7 +398,7 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(const float* __restrict
 static int attn_target_wgs() {
   static int t = [] {
     const char* e = getenv("MN_ATTN_TARGET_WGS");
-    return e ? atoi(e) : 1024;
+    return e ? atoi(e) : 256;  // one workgroup per CU: more splits cost more in partial sums than they gain
   }();
   return t;
 }

@@ -104,8 +104,8 @@ void launch_prepare(const PrepArgs& a, hipStream_t st) {
 // ------------------------------------------------------------------------------------------
 // norm: x += sum of partials + bias (or x = embedding), then LayerNorm / RMSNorm -> h
 // ------------------------------------------------------------------------------------------
-constexpr int NORM_THREADS = 256;
-constexpr int NORM_MAX_VEC = 8;  // float4 per thread: d <= 256*8*4 = 8192
+constexpr int NORM_THREADS = 1024;  // 16 waves per row: the row's partial sums are many independent streams
+constexpr int NORM_MAX_VEC = 2;     // float4 per thread: d <= 1024*2*4 = 8192
 
 template <typename T>
 __device__ __forceinline__ float4 load4(const T* p);

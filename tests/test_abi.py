@@ -1,0 +1,108 @@
+"""No GPU needed: the C-ABI library loads, exports every symbol the header declares, and reports
+host-visible argument errors before anything would be launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "minions_verify.h")
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2402_15678_amd import binding
+    return binding
+
+
+def _declared():
+    src = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(mn_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported(binding):
+    names = _declared()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(binding.lib, n), n
+    assert set(names) == set(binding.EXPORTS)
+
+
+def _desc(binding, **kw):
+    d = dict(arch=1, dtype=1, n_layers=1, d_model=256, n_heads=2, n_kv_heads=1, head_dim=128, d_ffn=256, vocab=64,
+             max_pos=128, norm_eps=1e-5, rope_base=10000.0)
+    d.update(kw)
+    return binding.ModelDesc(*[d[k] for k, _ in binding.ModelDesc._fields_])
+
+
+def _weights(binding, n_layers=1):
+    w = binding.Weights()
+    fake = 0x1000  # never dereferenced by mn_create
+    w.tok_emb = w.pos_emb = w.final_norm_g = w.final_norm_b = w.lm_head = fake
+    arr = binding.ptr_array([fake] * n_layers)
+    for k in ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2"):
+        setattr(w, k, C.cast(arr, C.POINTER(C.c_void_p)))
+    return w, arr
+
+
+def test_create_validates_the_description(binding):
+    w, keep = _weights(binding)
+    ctx = binding.mn_create(_desc(binding), w)
+    assert ctx
+    assert binding.mn_workspace_bytes(ctx, 4, 20, 100) > 0
+    assert binding.mn_workspace_bytes(ctx, -1, 20, 100) == 0
+    binding.mn_destroy(ctx)
+    bad = [dict(arch=7), dict(dtype=3), dict(head_dim=48), dict(d_model=100), dict(n_heads=3, n_kv_heads=2),
+           dict(arch=0, n_heads=2, n_kv_heads=1), dict(vocab=0), dict(d_model=192), dict(norm_eps=-1.0)]
+    for kw in bad:
+        with pytest.raises(binding.MinionsError):
+            binding.mn_create(_desc(binding, **kw), w)
+    with pytest.raises(binding.MinionsError) as e:
+        binding.mn_create(_desc(binding), binding.Weights())
+    assert e.value.status == binding.MN_ENULL
+
+
+def test_step_calls_reject_bad_arguments_before_launch(binding):
+    w, keep = _weights(binding)
+    ctx = binding.mn_create(_desc(binding), w)
+    p = 0x1000
+    with pytest.raises(binding.MinionsError) as e:
+        binding.mn_mv_vote(ctx, p, p, p, 4, 0, 3, 0, p, p)
+    assert e.value.status == binding.MN_EINVAL and "n = 0" in str(e.value)
+    with pytest.raises(binding.MinionsError):
+        binding.mn_mv_vote(ctx, p, p, p, 4, 65, 3, 0, p, p)
+    with pytest.raises(binding.MinionsError):
+        binding.mn_mv_vote(ctx, p, p, p, 4, 3, 3, 2, p, p)
+    with pytest.raises(binding.MinionsError) as e:
+        binding.mn_mv_vote(ctx, None, p, p, 4, 3, 3, 0, p, p)
+    assert e.value.status == binding.MN_ENULL
+    binding.mn_mv_vote(ctx, None, None, None, 0, 3, 3, 0, None, None)          # B = 0: no-op, no launch
+    kv = binding.KV(None, None, 16, 8, 4, None, None)
+    with pytest.raises(binding.MinionsError) as e:
+        binding.mn_verify_forward(ctx, p, p, p, binding.host_i32([1]), 1, 1, 10, kv, p, None, p, 1 << 20)
+    assert e.value.status == binding.MN_ENULL                                   # kv members
+    arr = binding.ptr_array([p])
+    kv = binding.KV(C.cast(arr, C.POINTER(C.c_void_p)), C.cast(arr, C.POINTER(C.c_void_p)), 16, 8, 4, p, p)
+    with pytest.raises(binding.MinionsError) as e:
+        binding.mn_verify_forward(ctx, p, p, p, binding.host_i32([1]), 1, 1, 100, kv, p, None, p, 1 << 20)
+    assert e.value.status == binding.MN_ECAPACITY                               # 100 tokens > 4 blocks of 16
+    with pytest.raises(binding.MinionsError) as e:
+        binding.mn_verify_forward(ctx, p, p, p, binding.host_i32([5]), 1, 1, 10, kv, p, None, p, 1 << 20)
+    assert e.value.status == binding.MN_EINVAL                                  # h_spec_len > k_max
+    with pytest.raises(binding.MinionsError) as e:
+        binding.mn_verify_forward(ctx, p, p, p, binding.host_i32([1]), 1, 1, 10, kv, p, None, 0x1000, 16)
+    assert e.value.status == binding.MN_EWORKSPACE                              # too small
+    with pytest.raises(binding.MinionsError) as e:
+        binding.mn_verify_forward(ctx, p, p, p, binding.host_i32([1]), 1, 1, 10, kv, p, None, 0x1010, 1 << 30)
+    assert e.value.status == binding.MN_EWORKSPACE                              # misaligned
+    with pytest.raises(binding.MinionsError):
+        binding.mn_accept_and_commit(ctx, p, p, p, 2, 3, binding.KV(None, None, 16, 8, 4, None, None), p, p, p, p, p)
+    with pytest.raises(binding.MinionsError) as e:
+        binding.mn_proj_gemm(ctx, p, p, None, p, 4, 8, 100)
+    assert e.value.status == binding.MN_ESHAPE
+    assert binding.mn_packed_weight_bytes(130, 256) == 256 * 256 * 2            # columns padded to 128
+    assert binding.mn_packed_weight_bytes(130, 100) == 0
+    with pytest.raises(binding.MinionsError):
+        binding.mn_pack_weight(p, 0x2000, 64, 256, 48)                          # N != 2 * half
+    binding.mn_destroy(ctx)
