@@ -118,254 +118,307 @@ __global__ void __launch_bounds__(GEN_THREADS) attn_generic_kernel(AttnArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
-// MFMA kernel (bf16, head_dim 128, block 16)
+// MFMA kernel (bf16 pages, fp16 queries, head_dim 128, block 16)
 // ------------------------------------------------------------------------------------------
+// Workgroup (4 waves) = one (KV split, KV head, sequence).  The R = G*q_b query rows that share the
+// KV head are cut into 16-row column tiles; wave w owns tiles w, w+4, (w+8).  Key tiles of 32 keys
+// (two blocks) travel HBM -> registers (raw bf16, a ring of PF tiles in flight per workgroup) ->
+// widened once to fp16 -> LDS in MFMA fragment order -> every wave's MFMAs, so each K/V byte is
+// loaded and converted once per KV head.  Q sits in LDS for the whole kernel.
+//
+// Both products have the query row as the MFMA column index (S^T = K Q^T, O^T = V^T P^T): softmax
+// statistics are per-lane scalars.  Inside a tile the K rows are permuted (S^T row 4g'+r of half t
+// is key 8g' + 4t + r) so that the lane group g of the first product's output holds keys
+// 8g..8g+7, exactly the operand order of the second product and 16 contiguous bytes of a V page.
 constexpr int HD = 128;
 constexpr int BS = 16;
-constexpr int KT = 32;                 // keys per tile (two blocks)
-constexpr int CT = 4;                  // 16-row column tiles per wave (64 query rows)
-constexpr int Q_ROW = HD + 8;          // padded LDS row of Q, fp16 elements
-constexpr int MAX_RG = 4;              // row groups of 64 rows per workgroup
-constexpr int MERGE_RG = 2;              // row groups that can need a wave merge (KW > 1 only when RG <= 2)
+constexpr int KT = 32;                         // keys per tile (two blocks)
+constexpr int TILE_BYTES = 2 * KT * HD * 2;    // K + V of one tile in fp16: 16 KB
+constexpr int PF = 2;                          // key tiles in flight in registers per workgroup
+constexpr int MAX_CT = 3;                      // column tiles per wave at most (R <= 192)
 constexpr float LOG2E = 1.4426950408889634f;
 
+// Q in LDS: 256-byte rows with the sixteen 16-byte chunks of row r rotated by 2r (bank pattern of a
+// 288-byte stride: conflict-free for 16 rows x one chunk per quarter wave).
+__device__ __forceinline__ int q_slot(int row, int chunk) { return row * HD + (((chunk + 2 * row) & 15) << 3); }
+
+struct TileAddr {  // what a thread needs to fetch its four 16-byte pieces of a key tile
+  const bf16_t* k[2];
+  const bf16_t* v[2];
+};
+
 // Partials: o_part [split][M][H][HD] fp32 (unnormalised), ml_part [split][M][H][2] = (max in log2 units, sum)
-__global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int n_splits, float* __restrict__ o_part,
-                                                        float* __restrict__ ml_part) {
+template <int CTW>
+__global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_splits, float* __restrict__ o_part,
+                                                           float* __restrict__ ml_part) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  f16_t* s_q = reinterpret_cast<f16_t*>(smem);  // [RG*64][Q_ROW]; later reused for the wave merge
+  f16_t* s_kv = reinterpret_cast<f16_t*>(smem);                       // [2][16 fragments][64 lanes][8]
+  f16_t* s_q = reinterpret_cast<f16_t*>(smem + 2 * TILE_BYTES);       // [NT16*16][HD], rotated chunks
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
   const int G = a.H / a.Hkv;
   const int row0 = a.rows.seq_row0[b];
   const int qb = a.rows.seq_row0[b + 1] - row0;
+  if (qb <= 0) return;
   const int ok = a.rows.seq_ok[b];
   const int ctx = a.rows.seq_ctx[b];
-  const int R = G * qb;  // query rows sharing this KV head; row r = j*G + gi
-  if (qb <= 0) return;
-  const int RG = (R + 63) >> 6;            // row groups in use (1..4)
-  const int KW = (RG == 1) ? 4 : (RG == 2 ? 2 : 1);  // waves that interleave over key tiles
-  const int rg = wave / KW, kw = wave % KW;
-  const bool active = ok && rg < RG;
+  const int R = G * qb;                   // query rows sharing this KV head; row r = j*G + gi
+  const int NT16 = (R + 15) >> 4;         // column tiles in use (<= 4*CTW, checked by the launcher)
   const int nkeys = ok ? ctx + qb : 0;
   const int n_tiles = (nkeys + KT - 1) / KT;
   const int t_begin = (int)(((long)n_tiles * split) / n_splits);
   const int t_end = (int)(((long)n_tiles * (split + 1)) / n_splits);
+  // tiles that hold only cached keys (all visible to every row, both blocks mapped) are streamed
+  // through the prefetch ring; the last tiles, which hold this step's own keys, go one by one
+  const int t_full_end = min(t_end, ctx / KT);
 
   // ---- Q -> LDS (zero rows past R) ----
   const f16_t* Q = reinterpret_cast<const f16_t*>(a.q);
-  for (int c = tid; c < RG * 64 * (HD / 8); c += 256) {
-    const int r = c / (HD / 8), ch = c % (HD / 8);
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+  for (int c = tid; c < NT16 * 16 * (HD / 8); c += 256) {
+    const int r = c >> 4, ch = c & 15;
+    u32x4 v = {0u, 0u, 0u, 0u};
     if (r < R) {
       const int j = r / G, gi = r % G;
-      v = *reinterpret_cast<const uint4*>(Q + ((size_t)(row0 + j) * a.H + kvh * G + gi) * HD + ch * 8);
+      v = *reinterpret_cast<const u32x4*>(Q + ((size_t)(row0 + j) * a.H + kvh * G + gi) * HD + ch * 8);
     }
-    *reinterpret_cast<uint4*>(&s_q[r * Q_ROW + ch * 8]) = v;
+    *reinterpret_cast<u32x4*>(&s_q[q_slot(r, ch)]) = v;
   }
-  __syncthreads();
 
   const float sscale = rsqrtf((float)HD) * LOG2E;
-  f32x4 O[CT][8];
-  float run_m[CT], run_l[CT];
-  int lim[CT];
+  f32x4 O[CTW][8];
+  float run_m[CTW], run_l[CTW];
+  int lim[CTW];
+  bool mine[CTW];
 #pragma unroll
-  for (int ct = 0; ct < CT; ++ct) {
+  for (int ct = 0; ct < CTW; ++ct) {
     run_m[ct] = -INFINITY;
     run_l[ct] = 0.f;
-    const int r = rg * 64 + ct * 16 + l16;
+    const int tile = wave + 4 * ct;
+    mine[ct] = ok && tile < NT16;
+    const int r = tile * 16 + l16;
     lim[ct] = ctx + min(r / G, qb - 1);  // last visible key of this lane's query row
 #pragma unroll
     for (int u = 0; u < 8; ++u) O[ct][u] = (f32x4){0.f, 0.f, 0.f, 0.f};
   }
-  const int n_ct = active ? min(CT, (R - rg * 64 + 15) >> 4) : 0;
 
   const bf16_t* Kp = reinterpret_cast<const bf16_t*>(a.kv.k);
   const bf16_t* Vp = reinterpret_cast<const bf16_t*>(a.kv.v);
   const f16_t* Kn = reinterpret_cast<const f16_t*>(a.knew);
   const f16_t* Vn = reinterpret_cast<const f16_t*>(a.vnew);
   const int32_t* bt = a.kv.block_tables + (size_t)b * a.kv.max_blocks_per_seq;
-  // lane constants of the K operand: S^T row i = l16 = 4g'+r  <->  key 8g' + 4t + r of the tile
-  const int kg_ = l16 >> 2, kr_ = l16 & 3;
+  const size_t head_off = (size_t)kvh * (HD * BS);
+  const size_t blk_stride = (size_t)a.Hkv * (HD * BS);
+  // Loader role of this thread: K pieces (t = 0, 1; head-dim step s = wave) and V pieces (u = wave, wave + 4).
+  // K piece: S^T row l16 = 4g'+r of half t <-> key 8g' + 4t + r of the tile; head-dim chunk 4*wave + g.
+  const int kkey0 = 8 * (l16 >> 2) + (l16 & 3);      // key inside the tile for t = 0 (t = 1: + 4)
+  const int kchunk = 4 * wave + g;
 
-  if (active) {
-    for (int T = t_begin + kw; T < t_end; T += KW) {
+  auto tile_addr = [&](int T) {
+    TileAddr ta;
+    const int pb0 = bt[2 * T], pb1 = bt[2 * T + 1];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int kk = kkey0 + 4 * t;
+      ta.k[t] = Kp + (size_t)(kk < BS ? pb0 : pb1) * blk_stride + head_off + ((size_t)kchunk * BS + (kk & (BS - 1))) * 8;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      ta.v[i] = Vp + (size_t)(g < 2 ? pb0 : pb1) * blk_stride + head_off + (size_t)(16 * (wave + 4 * i) + l16) * BS + 8 * (g & 1);
+    return ta;
+  };
+  // LDS fragment slots this thread fills: K fragment (t*4 + wave), V fragment 8 + wave + 4i
+  auto frag_ptr = [&](int buf, int f, int ln) { return s_kv + (size_t)buf * (TILE_BYTES / 2) + ((size_t)f * 64 + ln) * 8; };
+
+  // ---- one key tile on this wave's column tiles; `tail` tiles apply the causal mask ----
+  auto compute = [&](int buf, int key0, bool tail) {
+    f32x4 S0[CTW], S1[CTW];
+#pragma unroll
+    for (int ct = 0; ct < CTW; ++ct) S0[ct] = S1[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const f16x8 k0 = *reinterpret_cast<const f16x8*>(frag_ptr(buf, s, lane));
+      const f16x8 k1 = *reinterpret_cast<const f16x8*>(frag_ptr(buf, 4 + s, lane));
+#pragma unroll
+      for (int ct = 0; ct < CTW; ++ct) {
+        if (!mine[ct]) continue;
+        const f16x8 qf = *reinterpret_cast<const f16x8*>(&s_q[q_slot((wave + 4 * ct) * 16 + l16, 4 * s + g)]);
+        S0[ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(k0, qf, S0[ct], 0, 0, 0);
+        S1[ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(k1, qf, S1[ct], 0, 0, 0);
+      }
+    }
+    f16x8 P[CTW];
+    float alpha[CTW];
+#pragma unroll
+    for (int ct = 0; ct < CTW; ++ct) {
+      alpha[ct] = 1.f;
+      if (!mine[ct]) continue;
+      // lane holds keys key0 + 8g + e, e = 0..7 (S0 -> e 0..3, S1 -> e 4..7) of query row l16
+      float sc[8];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        sc[e] = S0[ct][e] * sscale;
+        sc[4 + e] = S1[ct][e] * sscale;
+      }
+      if (tail) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (key0 + 8 * g + e > lim[ct]) sc[e] = -INFINITY;
+      }
+      float tm = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+      tm = fmaxf(tm, __shfl_xor(tm, 16, 64));
+      tm = fmaxf(tm, __shfl_xor(tm, 32, 64));
+      const float new_m = fmaxf(run_m[ct], tm);
+      const float m_safe = (new_m == -INFINITY) ? 0.f : new_m;
+      alpha[ct] = __builtin_amdgcn_exp2f(run_m[ct] - m_safe);
+      run_m[ct] = new_m;
+      float ps = 0.f;
+      float p[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        p[e] = __builtin_amdgcn_exp2f(sc[e] - m_safe);
+        ps += p[e];
+      }
+      run_l[ct] = run_l[ct] * alpha[ct] + ps;  // per-lane partial sum; lane groups are added at the end
+      union { f16x8 v; uint32_t u[4]; } pf;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) pf.u[e] = pack2h(p[2 * e], p[2 * e + 1]);
+      P[ct] = pf.v;
+      // rescale the accumulator only when some row's maximum moved (rare once the scan is warm)
+      if (__any(alpha[ct] != 1.f)) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          O[ct][u][0] *= alpha[ct]; O[ct][u][1] *= alpha[ct]; O[ct][u][2] *= alpha[ct]; O[ct][u][3] *= alpha[ct];
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const f16x8 vf = *reinterpret_cast<const f16x8*>(frag_ptr(buf, 8 + u, lane));
+#pragma unroll
+      for (int ct = 0; ct < CTW; ++ct) {
+        if (!mine[ct]) continue;
+        O[ct][u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf, P[ct], O[ct][u], 0, 0, 0);
+      }
+    }
+  };
+
+  // ---- main loop over the cached-key tiles ----
+  const int n_full = max(0, t_full_end - t_begin);
+  if (ok && n_full > 0) {
+    const int T_last = t_begin + n_full - 1;
+    u32x4 ring[PF][4];  // raw bf16 pieces of the next PF tiles
+#define MN_ATT_LOAD(SLOT, T)                                                                     \
+  {                                                                                              \
+    const TileAddr ta_ = tile_addr(min((T), T_last));                                            \
+    ring[SLOT][0] = *reinterpret_cast<const u32x4*>(ta_.k[0]);                                   \
+    ring[SLOT][1] = *reinterpret_cast<const u32x4*>(ta_.k[1]);                                   \
+    ring[SLOT][2] = *reinterpret_cast<const u32x4*>(ta_.v[0]);                                   \
+    ring[SLOT][3] = *reinterpret_cast<const u32x4*>(ta_.v[1]);                                   \
+  }
+#define MN_ATT_FILL(SLOT, BUF)                                                                   \
+  {                                                                                              \
+    *reinterpret_cast<f16x8*>(frag_ptr((BUF), wave, lane)) = bf16x8_to_f16x8(ring[SLOT][0]);     \
+    *reinterpret_cast<f16x8*>(frag_ptr((BUF), 4 + wave, lane)) = bf16x8_to_f16x8(ring[SLOT][1]); \
+    *reinterpret_cast<f16x8*>(frag_ptr((BUF), 8 + wave, lane)) = bf16x8_to_f16x8(ring[SLOT][2]); \
+    *reinterpret_cast<f16x8*>(frag_ptr((BUF), 12 + wave, lane)) = bf16x8_to_f16x8(ring[SLOT][3]); \
+  }
+    // prologue: tile 0 -> LDS buffer 0, tiles 1..PF in flight
+    MN_ATT_LOAD(0, t_begin)
+    MN_ATT_FILL(0, 0)
+    MN_ATT_LOAD(0, t_begin + 1)
+    MN_ATT_LOAD(1, t_begin + 2)
+    __syncthreads();
+// iteration i: LDS[i&1] holds tile i; ring slot SLOT holds tile i+1 (landed); the other slot tile i+2.
+// Fill the other LDS buffer with tile i+1, refill the slot with tile i+3, compute tile i.
+#define MN_ATT_ITER(SLOT, I)                                                                     \
+  {                                                                                              \
+    const int i_ = (I);                                                                          \
+    MN_ATT_FILL(SLOT, (i_ + 1) & 1)                                                              \
+    MN_ATT_LOAD(SLOT, t_begin + i_ + 3)                                                          \
+    asm volatile("" ::: "memory");                                                               \
+    compute(i_ & 1, (t_begin + i_) * KT, false);                                                 \
+    __syncthreads();                                                                             \
+  }
+    int i = 0;
+    for (; i + 1 < n_full; i += 2) {
+      MN_ATT_ITER(0, i)
+      MN_ATT_ITER(1, i + 1)
+    }
+    if (i < n_full) MN_ATT_ITER(0, i)
+#undef MN_ATT_ITER
+#undef MN_ATT_FILL
+#undef MN_ATT_LOAD
+  }
+
+  // ---- tail tiles: they hold this step's own keys (read from the fp16 side buffers when given) ----
+  if (ok) {
+    __syncthreads();
+    for (int T = max(t_begin, t_full_end); T < t_end; ++T) {
       const int key0 = T * KT;
       const int pb0 = bt[2 * T];
       const int pb1 = (key0 + BS < nkeys) ? bt[2 * T + 1] : pb0;
-      const bool tail = key0 + KT > ctx;  // the tile holds keys of this step (masking, side-buffer reads)
-      // ---- K fragments: [t][s] ----
-      f16x8 kf[2][4];
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        const int kk = 8 * kg_ + 4 * t + kr_;  // key inside the tile
-        const int pb = (kk < BS) ? pb0 : pb1;
-        const int key = key0 + kk;
-        if (tail && Kn && key >= ctx && key < nkeys) {
-          // a key of this step: read the unrounded row from the side buffer
-          const f16_t* base = Kn + ((size_t)(row0 + key - ctx) * a.Hkv + kvh) * HD + g * 8;
-#pragma unroll
-          for (int s = 0; s < 4; ++s) kf[t][s] = *reinterpret_cast<const f16x8*>(base + 32 * s);
+        const int kk = kkey0 + 4 * t, key = key0 + kk;
+        f16x8 kf;
+        if (Kn && key >= ctx && key < nkeys) {
+          kf = *reinterpret_cast<const f16x8*>(Kn + ((size_t)(row0 + key - ctx) * a.Hkv + kvh) * HD + kchunk * 8);
         } else {
-          const bf16_t* base = Kp + ((size_t)pb * a.Hkv + kvh) * (size_t)(HD * BS) + (kk & (BS - 1)) * 8;
-#pragma unroll
-          for (int s = 0; s < 4; ++s)
-            kf[t][s] = bf16x8_to_f16x8(*reinterpret_cast<const uint4*>(base + (size_t)(4 * s + g) * (BS * 8)));
+          kf = bf16x8_to_f16x8(*reinterpret_cast<const u32x4*>(Kp + (size_t)(kk < BS ? pb0 : pb1) * blk_stride + head_off +
+                                                               ((size_t)kchunk * BS + (kk & (BS - 1))) * 8));
         }
-      }
-      // ---- V fragments: [u], keys 8g..8g+7 of the tile ----
-      f16x8 vf[8];
-      {
-        const int pb = (g < 2) ? pb0 : pb1;
-        const bf16_t* base = Vp + ((size_t)pb * a.Hkv + kvh) * (size_t)(HD * BS) + (8 * (g & 1));
-#pragma unroll
-        for (int u = 0; u < 8; ++u) vf[u] = bf16x8_to_f16x8(*reinterpret_cast<const uint4*>(base + (size_t)(16 * u + l16) * BS));
-        if (key0 + KT > nkeys) {
-          // stale slots past the sequence end may hold anything: zero them so 0 * garbage stays 0
-#pragma unroll
-          for (int u = 0; u < 8; ++u)
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-              if (key0 + 8 * g + e >= nkeys) vf[u][e] = (f16_t)0.f;
-        }
-        if (tail && Vn) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const int key = key0 + 8 * g + e;
-            if (key >= ctx && key < nkeys) {
-              const f16_t* src = Vn + ((size_t)(row0 + key - ctx) * a.Hkv + kvh) * HD + l16;
-#pragma unroll
-              for (int u = 0; u < 8; ++u) vf[u][e] = src[16 * u];
-            }
-          }
-        }
+        *reinterpret_cast<f16x8*>(frag_ptr(0, t * 4 + wave, lane)) = kf;
       }
 #pragma unroll
-      for (int ct = 0; ct < CT; ++ct) {
-        if (ct >= n_ct) continue;
-        // ---- S^T = K Q^T for 32 keys x 16 rows ----
-        f32x4 S0 = (f32x4){0.f, 0.f, 0.f, 0.f}, S1 = S0;
-        const f16_t* qrow = &s_q[(rg * 64 + ct * 16 + l16) * Q_ROW + g * 8];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const f16x8 qf = *reinterpret_cast<const f16x8*>(qrow + s * 32);
-          S0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[0][s], qf, S0, 0, 0, 0);
-          S1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[1][s], qf, S1, 0, 0, 0);
-        }
-        // lane holds keys key0 + 8g + e, e = 0..7 (S0 -> e 0..3, S1 -> e 4..7) of row l16
-        float sc[8];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          sc[e] = S0[e] * sscale;
-          sc[4 + e] = S1[e] * sscale;
-        }
-        if (tail) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e)
-            if (key0 + 8 * g + e > lim[ct]) sc[e] = -INFINITY;
-        }
-        float tm = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
-        tm = fmaxf(tm, __shfl_xor(tm, 16, 64));
-        tm = fmaxf(tm, __shfl_xor(tm, 32, 64));
-        const float new_m = fmaxf(run_m[ct], tm);
-        const float m_safe = (new_m == -INFINITY) ? 0.f : new_m;
-        const float alpha = __builtin_amdgcn_exp2f(run_m[ct] - m_safe);
-        run_m[ct] = new_m;
-        float ps = 0.f;
-        float p[8];
+      for (int i = 0; i < 2; ++i) {
+        const int hd = 16 * (wave + 4 * i) + l16;
+        f16x8 vf = bf16x8_to_f16x8(*reinterpret_cast<const u32x4*>(Vp + (size_t)(g < 2 ? pb0 : pb1) * blk_stride + head_off +
+                                                                   (size_t)hd * BS + 8 * (g & 1)));
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          p[e] = __builtin_amdgcn_exp2f(sc[e] - m_safe);
-          ps += p[e];
+          const int key = key0 + 8 * g + e;
+          if (key >= nkeys) vf[e] = (f16_t)0.f;  // stale slots may hold anything: 0 * garbage must stay 0
+          else if (Vn && key >= ctx) vf[e] = Vn[((size_t)(row0 + key - ctx) * a.Hkv + kvh) * HD + hd];
         }
-        run_l[ct] = run_l[ct] * alpha + ps;  // per-lane partial sum; lane groups are added at the end
-        union { f16x8 v; uint32_t u[4]; } pf;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) pf.u[e] = pack2h(p[2 * e], p[2 * e + 1]);
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          f32x4 o = O[ct][u];
-          o[0] *= alpha; o[1] *= alpha; o[2] *= alpha; o[3] *= alpha;
-          O[ct][u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[u], pf.v, o, 0, 0, 0);
-        }
+        *reinterpret_cast<f16x8*>(frag_ptr(0, 8 + wave + 4 * i, lane)) = vf;
       }
+      __syncthreads();
+      compute(0, key0, true);
+      __syncthreads();
     }
   }
-  // per-row sums over the four lane groups
+
+  // ---- output: lane holds O^T[hd = 16u + 4g + i][row = tile*16 + l16] ----
 #pragma unroll
-  for (int ct = 0; ct < CT; ++ct) {
+  for (int ct = 0; ct < CTW; ++ct) {
+    const int tile = wave + 4 * ct;
+    const int r = tile * 16 + l16;
+    if (tile >= NT16 || r >= R) continue;
     float l = run_l[ct];
     l += __shfl_xor(l, 16, 64);
     l += __shfl_xor(l, 32, 64);
-    run_l[ct] = l;
-  }
-
-  // ---- merge the KW waves of a row group through LDS (wave kw=0 accumulates) ----
-  __syncthreads();  // everyone is done with s_q
-  float* s_o = reinterpret_cast<float*>(smem);                 // [MERGE_RG][CT][8][4][64]
-  float* s_ml = s_o + MERGE_RG * CT * 8 * 4 * 64;              // [MERGE_RG][CT][2][64]
-  for (int step = 1; step < KW; ++step) {
-    if (active && kw == step) {
+    const int j = r / G, gi = r % G;
+    const int m = row0 + j, h = kvh * G + gi;
+    if (n_splits == 1) {
+      const float inv = (ok && l > 0.f) ? 1.f / l : 0.f;
+      f16_t* o = reinterpret_cast<f16_t*>(a.out) + ((size_t)m * a.H + h) * HD + 4 * g;
 #pragma unroll
-      for (int ct = 0; ct < CT; ++ct) {
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) s_o[(((rg * CT + ct) * 8 + u) * 4 + i) * 64 + lane] = O[ct][u][i];
-        s_ml[((rg * CT + ct) * 2 + 0) * 64 + lane] = run_m[ct];
-        s_ml[((rg * CT + ct) * 2 + 1) * 64 + lane] = run_l[ct];
+      for (int u = 0; u < 8; ++u) {
+        const f32x4 v = O[ct][u];
+        *reinterpret_cast<uint2*>(o + 16 * u) = make_uint2(pack2h(v[0] * inv, v[1] * inv), pack2h(v[2] * inv, v[3] * inv));
       }
-    }
-    __syncthreads();
-    if (active && kw == 0) {
+    } else {
+      float* o = o_part + (((size_t)split * a.M + m) * a.H + h) * HD + 4 * g;
 #pragma unroll
-      for (int ct = 0; ct < CT; ++ct) {
-        const float om = s_ml[((rg * CT + ct) * 2 + 0) * 64 + lane];
-        const float ol = s_ml[((rg * CT + ct) * 2 + 1) * 64 + lane];
-        const float nm = fmaxf(run_m[ct], om);
-        const float ms = (nm == -INFINITY) ? 0.f : nm;
-        const float fa = __builtin_amdgcn_exp2f(run_m[ct] - ms), fb = __builtin_amdgcn_exp2f(om - ms);
-        run_m[ct] = nm;
-        run_l[ct] = run_l[ct] * fa + ol * fb;
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            O[ct][u][i] = O[ct][u][i] * fa + s_o[(((rg * CT + ct) * 8 + u) * 4 + i) * 64 + lane] * fb;
+      for (int u = 0; u < 8; ++u) {
+        const f32x4 v = O[ct][u];
+        *reinterpret_cast<float4*>(o + 16 * u) = make_float4(v[0], v[1], v[2], v[3]);
       }
-    }
-    __syncthreads();
-  }
-
-  // ---- output: lane holds O^T[hd = 16u + 4g + i][row = rg*64 + ct*16 + l16] ----
-  if (rg < RG && kw == 0) {
-#pragma unroll
-    for (int ct = 0; ct < CT; ++ct) {
-      const int r = rg * 64 + ct * 16 + l16;
-      if (r >= R) continue;
-      const int j = r / G, gi = r % G;
-      const int m = row0 + j, h = kvh * G + gi;
-      if (n_splits == 1) {
-        const float inv = (ok && run_l[ct] > 0.f) ? 1.f / run_l[ct] : 0.f;
-        f16_t* o = reinterpret_cast<f16_t*>(a.out) + ((size_t)m * a.H + h) * HD + 4 * g;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const f32x4 v = O[ct][u];
-          *reinterpret_cast<uint2*>(o + 16 * u) = make_uint2(pack2h(v[0] * inv, v[1] * inv), pack2h(v[2] * inv, v[3] * inv));
-        }
-      } else {
-        float* o = o_part + (((size_t)split * a.M + m) * a.H + h) * HD + 4 * g;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const f32x4 v = O[ct][u];
-          *reinterpret_cast<float4*>(o + 16 * u) = make_float4(v[0], v[1], v[2], v[3]);
-        }
-        if (g == 0) {
-          float* ml = ml_part + (((size_t)split * a.M + m) * a.H + h) * 2;
-          ml[0] = run_m[ct];
-          ml[1] = run_l[ct];
-        }
+      if (g == 0) {
+        float* ml = ml_part + (((size_t)split * a.M + m) * a.H + h) * 2;
+        ml[0] = run_m[ct];
+        ml[1] = l;
       }
     }
   }
@@ -398,7 +451,7 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(const float* __restrict
 static int attn_target_wgs() {
   static int t = [] {
     const char* e = getenv("MN_ATTN_TARGET_WGS");
-    return e ? atoi(e) : 256;  // one workgroup per CU: more splits cost more in partial sums than they gain
+    return e ? atoi(e) : 512;  // two workgroups per CU
   }();
   return t;
 }
@@ -410,7 +463,7 @@ static int pick_splits(int B, int Hkv, int max_ctx) {
   }();
   const int tiles = (max_ctx + KT - 1) / KT;
   int s = forced > 0 ? forced : (attn_target_wgs() + B * Hkv - 1) / (B * Hkv);
-  const int cap = (tiles + 3) / 4;  // at least four key tiles per split
+  const int cap = (tiles + 7) / 8;  // at least eight key tiles per split
   if (s > cap) s = cap;
   if (s > 16) s = 16;
   if (s < 1) s = 1;
@@ -425,12 +478,7 @@ bool attention_mfma_supported(int H, int Hkv, int hd, int block_size, int dtype)
   return !off && dtype == MN_DT_BF16 && hd == HD && block_size == BS && Hkv > 0 && H % Hkv == 0;
 }
 
-static size_t mfma_smem_bytes(int rg_max) {
-  const size_t q = (size_t)rg_max * 64 * Q_ROW * sizeof(f16_t);
-  // the merge area is needed by any sequence with at most MERGE_RG row groups, whatever the batch maximum is
-  const size_t merge = (size_t)MERGE_RG * CT * (8 * 4 + 2) * 64 * sizeof(float);
-  return q > merge ? q : merge;
-}
+static size_t mfma_smem_bytes(int nt16_max) { return (size_t)2 * TILE_BYTES + (size_t)nt16_max * 16 * HD * sizeof(f16_t); }
 
 size_t attention_scratch_bytes(int M, int H, int hd, int max_ctx, int dtype) {
   if (dtype != MN_DT_BF16 || hd != HD) return 256;
@@ -440,24 +488,28 @@ size_t attention_scratch_bytes(int M, int H, int hd, int max_ctx, int dtype) {
 void launch_attention(const AttnArgs& a, hipStream_t st) {
   if (a.M <= 0 || a.B <= 0) return;
   const int G = a.Hkv > 0 ? a.H / a.Hkv : 1;
-  // the MFMA kernel stacks at most MAX_RG*64 query rows per KV head
-  const bool mfma = attention_mfma_supported(a.H, a.Hkv, a.hd, a.kv.block_size, a.dtype) &&
-                    (long)G * a.max_q <= MAX_RG * 64 && a.scratch != nullptr &&
+  // the MFMA kernel stacks at most 4 * MAX_CT column tiles of 16 query rows per KV head
+  const int nt16_max = (G * a.max_q + 15) / 16;
+  const bool mfma = attention_mfma_supported(a.H, a.Hkv, a.hd, a.kv.block_size, a.dtype) && nt16_max <= 4 * MAX_CT &&
+                    a.scratch != nullptr &&
                     a.scratch_bytes >= attention_scratch_bytes(a.M, a.H, a.hd, a.max_ctx, a.dtype);
   if (mfma) {
     const int n_splits = pick_splits(a.B, a.Hkv, a.max_ctx);
     float* o_part = a.scratch;
     float* ml_part = a.scratch + (size_t)n_splits * a.M * a.H * HD;
-    const int rg_max = (G * a.max_q + 63) / 64;
-    const size_t smem = mfma_smem_bytes(rg_max);
+    const size_t smem = mfma_smem_bytes(nt16_max);
     static bool attr_set = false;
     if (!attr_set) {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)mfma_smem_bytes(MAX_RG));
+      const int most = (int)mfma_smem_bytes(4 * MAX_CT);
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, most);
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, most);
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<3>), hipFuncAttributeMaxDynamicSharedMemorySize, most);
       attr_set = true;
     }
     dim3 grid(n_splits, a.Hkv, a.B);
-    attn_mfma_kernel<<<grid, 256, smem, st>>>(a, n_splits, o_part, ml_part);
+    if (nt16_max <= 4) attn_mfma_kernel<1><<<grid, 256, smem, st>>>(a, n_splits, o_part, ml_part);
+    else if (nt16_max <= 8) attn_mfma_kernel<2><<<grid, 256, smem, st>>>(a, n_splits, o_part, ml_part);
+    else attn_mfma_kernel<3><<<grid, 256, smem, st>>>(a, n_splits, o_part, ml_part);
     if (n_splits > 1) {
       const int waves = a.M * a.H;
       attn_merge_kernel<<<(waves + 3) / 4, 256, 0, st>>>(o_part, ml_part, n_splits, a.M, a.H, reinterpret_cast<f16_t*>(a.out));

@@ -132,6 +132,16 @@ __global__ void __launch_bounds__(256, 2) gemm_w16_kernel(const f16_t* __restric
     }
     __syncthreads();
 
+#ifndef MN_ABLATE
+#define MN_ABLATE 0
+#endif
+#if MN_ABLATE & 1  // experiment: no LDS reads / MFMAs, keep the weight stream alive
+#define MN_ABLATE_GROUPS 0
+#define MN_ABLATE_SKIP_COMPUTE(W) { acc[0][0][0] += (float)W[0][0] + (float)W[1][0]; }
+#else
+#define MN_ABLATE_GROUPS 2
+#define MN_ABLATE_SKIP_COMPUTE(W)
+#endif
 // One iteration on ring slot RING.  Issue order matters because loads return in order: the next
 // activation tile (L2 hits, needed at the end of this iteration) goes first, then, k-step by k-step, the
 // weight refills for iteration it+2 (HBM, needed two iterations from now), so waiting for the tile
@@ -142,7 +152,7 @@ __global__ void __launch_bounds__(256, 2) gemm_w16_kernel(const f16_t* __restric
     const int buf_ = it_ & 1;                                                                               \
     const int nxt_ = min(it_ + 1, last);                                                                    \
     u32x4 sa_[MT];                                                                                          \
-    MN_LOAD_A(sa_, 0, MT, nxt_)                                                                             \
+    if (!(MN_ABLATE & 2)) { MN_LOAD_A(sa_, 0, MT, nxt_) }                                                   \
     /* a compiler-level memory fence: without it the loads above are sunk to the stores at the bottom */    \
     asm volatile("" ::: "memory");                                                                          \
     const f16_t* tile_ = s_a + buf_ * TILE;                                                                 \
@@ -152,7 +162,8 @@ __global__ void __launch_bounds__(256, 2) gemm_w16_kernel(const f16_t* __restric
         wcur_[nt] = bf16x8_to_f16x8(RING[nt][ks]);                                                          \
         RING[nt][ks] = *MN_W_PTR(it_ + 2, nt, ks);                                                          \
       }                                                                                                     \
-      _Pragma("unroll") for (int grp = 0; grp < 2; ++grp) {                                                 \
+      MN_ABLATE_SKIP_COMPUTE(wcur_)                                                                         \
+      _Pragma("unroll") for (int grp = 0; grp < MN_ABLATE_GROUPS; ++grp) {                                  \
         constexpr int G0 = (MT + 1) / 2;                                                                    \
         const int lo_ = grp ? G0 : 0, cnt_ = grp ? MT - G0 : G0;                                            \
         f16x8 bfrag_[G0];                                                                                   \
@@ -166,8 +177,8 @@ __global__ void __launch_bounds__(256, 2) gemm_w16_kernel(const f16_t* __restric
         __builtin_amdgcn_sched_barrier(0);                                                                  \
       }                                                                                                     \
     }                                                                                                       \
-    MN_STORE_A(sa_, 0, MT, buf_ ^ 1)                                                                        \
-    __syncthreads();                                                                                        \
+    if (!(MN_ABLATE & 2)) { MN_STORE_A(sa_, 0, MT, buf_ ^ 1) }                                              \
+    if (!(MN_ABLATE & 4)) __syncthreads();                                                                  \
   }
 
     // pairs of iterations with no branch inside the loop (a conditional second half would give the
@@ -327,10 +338,11 @@ int gemm_pick_split(int M, int N, int K, int dtype) {
   const int forced = tune().split;
   const int nblocks = (N + NWG - 1) / NWG;
   const int iters = K / KB;
-  // as many splits as keep the whole grid resident at once (two workgroups per CU), each split
-  // at least four iterations long
+  // as many splits as keep the whole grid resident at once (two workgroups per CU), each split at
+  // least 16 iterations long (measured: shorter splits lose more to ramp-up and partial sums than
+  // the extra workgroups win)
   int s = forced >= 1 ? forced : tune().target / nblocks;
-  if (s > iters / 4) s = iters / 4;
+  if (forced < 1 && s > iters / 16) s = iters / 16;
   if (s > MN_MAX_SPLIT_K) s = MN_MAX_SPLIT_K;
   if (s < 1) s = 1;
   // drop splits that would get no iteration

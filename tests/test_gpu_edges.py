@@ -1,0 +1,157 @@
+"""GPU edge cases through the C ABI: degenerate batches, device-detected errors (the sequence becomes a
+no-op and nothing of it reaches the cache), run-to-run bit reproducibility, plain decode (k = 0),
+and the one-pass == sequential-decodes invariant on the device."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import minions_oracle as orc
+from paper_2402_15678_amd import synth
+from tests import util
+
+pytestmark = pytest.mark.gpu
+
+DESC = synth.ModelDesc(synth.ARCH_LLAMA, synth.DT_BF16, 2, 256, 8, 2, 128, 512, 1000, 512)
+
+
+@pytest.fixture(scope="module")
+def env():
+    from paper_2402_15678_amd import binding, harness
+    W = synth.make_weights(DESC, 77)
+    model = harness.DeviceModel.from_host(DESC, W)
+    return harness, binding, W, model
+
+
+def _i32(a):
+    return torch.tensor(np.asarray(a, np.int32), dtype=torch.int32, device="cuda:0")
+
+
+def _setup(harness, model, ctx, ks, seed=3, want_logits=True):
+    kvh = synth.make_paged_kv(DESC, ctx, ks, seed)
+    kvd = harness.DeviceKV.from_host(DESC, kvh)
+    B = len(ctx)
+    ses = harness.VerifySession(model, kvd, B, int(max(ks)), 3, int((np.asarray(ctx) + np.asarray(ks) + 1).max()),
+                                max_rows=int((np.asarray(ks) + 1).sum()), want_logits=want_logits)
+    return kvh, kvd, ses
+
+
+def test_empty_batch_is_a_noop(env):
+    harness, binding, W, model = env
+    kv = binding.KV(None, None, 16, 1, 1, None, None)
+    binding.mn_mv_vote(model.ctx, None, None, None, 0, 3, 4, 0, None, None)
+    binding.mn_verify_forward(model.ctx, None, None, None, binding.host_i32([]), 0, 4, 0, kv, None, None, None, 0)
+    binding.mn_accept_and_commit(model.ctx, None, None, None, 0, 4, kv, None, None, None, None, None)
+    torch.cuda.synchronize()
+
+
+def test_plain_decode_k0_and_mixed_lengths(env):
+    harness, binding, W, model = env
+    ctx, ks = np.array([17, 40, 16, 1], np.int32), np.array([0, 3, 0, 5], np.int32)
+    kvh, kvd, ses = _setup(harness, model, ctx, ks)
+    g = synth.stream(5, 1)
+    last = g.integers(0, DESC.vocab, size=4).astype(np.int32)
+    drafts = g.integers(0, DESC.vocab, size=(4, 3, 5)).astype(np.int32)
+    caches = util.oracle_caches(DESC, kvh)
+    want = orc.verify_step(DESC, W, caches, last, drafts, ks, np.ones(3, np.float32))
+    t = [_i32(last), _i32(drafts), _i32(ks), torch.ones(3, device="cuda:0")]
+    ses.step(t[0], t[1], t[2], ks.tolist(), t[3])
+    torch.cuda.synchronize()
+    assert ses.dev_status.item() == 0
+    assert np.array_equal(ses.voted.cpu().numpy(), want["voted"])
+    assert np.abs(ses.logits.cpu().numpy() - np.concatenate(want["logits"])).max() < 3e-2
+    margins = [orc.top1_margin(l) for l in want["logits"]]
+    for b in range(4):
+        if margins[b].min() >= 6e-2:
+            assert np.array_equal(ses.greedy[b].cpu().numpy(), want["greedy"][b])
+            assert ses.accepted_len[b].item() == want["accepted_len"][b]
+            assert kvd.ctx_lens[b].item() == want["ctx_lens"][b]
+            assert ses.n_out[b].item() == want["n_out"][b]
+
+
+def test_bit_reproducible_run_to_run(env):
+    harness, binding, W, model = env
+    ctx, ks = np.array([100, 33, 257], np.int32), np.array([4, 7, 2], np.int32)
+    g = synth.stream(6, 1)
+    last, drafts = _i32(g.integers(0, DESC.vocab, size=3)), _i32(g.integers(0, DESC.vocab, size=(3, 3, 7)))
+    spec, w = _i32(ks), torch.ones(3, device="cuda:0")
+    outs = []
+    for _ in range(2):
+        kvh, kvd, ses = _setup(harness, model, ctx, ks)
+        ses.step(last, drafts, spec, ks.tolist(), w)
+        torch.cuda.synchronize()
+        outs.append((ses.logits.clone(), ses.greedy.clone(), kvd.k_pages[1].clone(), kvd.ctx_lens.clone()))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)                                              # no float atomics: identical bits
+
+
+def test_one_pass_equals_sequential_decodes_on_the_device(env):
+    harness, binding, W, model = env
+    ctx, k = np.array([50, 16, 129], np.int32), 5
+    ks = np.full(3, k, np.int32)
+    g = synth.stream(7, 1)
+    last = g.integers(0, DESC.vocab, size=3).astype(np.int32)
+    toks = g.integers(0, DESC.vocab, size=(3, k)).astype(np.int32)
+    kvh, kvd, ses = _setup(harness, model, ctx, ks)
+    t_last, t_voted, t_spec = _i32(last), _i32(toks), _i32(ks)
+    ses.forward(t_last, t_spec, ks.tolist(), voted=t_voted)
+    torch.cuda.synchronize()
+    one = ses.logits.cpu().numpy().reshape(3, k + 1, -1)
+    # the same tokens one at a time, committing each (ctx_lens advances by one per step)
+    kvh2, kvd2, seq = _setup(harness, model, ctx, np.zeros(3, np.int32) + k)  # blocks for all k+1 positions
+    single = harness.VerifySession(model, kvd2, 3, 0, 1, int(ctx.max()) + k + 1, max_rows=3, want_logits=True)
+    zeros = _i32(np.zeros(3)); dummy = _i32(np.zeros((3, 1)))
+    for j in range(k + 1):
+        cur = _i32(last if j == 0 else toks[:, j - 1])
+        single.forward(cur, zeros, [0, 0, 0], voted=dummy)
+        torch.cuda.synchronize()
+        step_logits = single.logits.cpu().numpy()
+        # fp16 activations both ways; the sequential path re-reads its own K/V rounded to bf16 from the cache
+        assert np.abs(step_logits - one[:, j]).max() < 3e-2, j
+        kvd2.ctx_lens.add_(1)
+
+
+def test_device_detected_errors_disable_only_the_bad_sequence(env):
+    harness, binding, W, model = env
+    ctx, ks = np.array([30, 45, 60], np.int32), np.array([3, 3, 3], np.int32)
+    g = synth.stream(8, 1)
+    last = g.integers(0, DESC.vocab, size=3).astype(np.int32)
+    voted = g.integers(0, DESC.vocab, size=(3, 3)).astype(np.int32)
+    # reference run
+    kvh, kvd, ses = _setup(harness, model, ctx, ks)
+    t = [_i32(last), _i32(voted), _i32(ks)]
+    ses.forward(t[0], t[2], ks.tolist(), voted=t[1])
+    torch.cuda.synchronize()
+    ref_greedy, ref_k = ses.greedy.cpu().numpy().copy(), kvd.k_pages[0].clone()
+    # (a) sequence 1 gets a block id out of range
+    kvh2, kvd2, ses2 = _setup(harness, model, ctx, ks)
+    before = kvd2.k_pages[0].clone()
+    bt = kvd2.block_tables.clone(); bt[1, 0] = 10 ** 6
+    kvd2.block_tables.copy_(bt)
+    ses2.forward(t[0], t[2], ks.tolist(), voted=t[1])
+    ses2.accept(t[2], voted=t[1])
+    torch.cuda.synchronize()
+    assert ses2.dev_status.item() & binding.MN_DEV_BLOCK_TABLE
+    got = ses2.greedy.cpu().numpy()
+    assert (got[1] == -1).all() and np.array_equal(got[[0, 2]], ref_greedy[[0, 2]])
+    assert ses2.n_out.cpu().tolist()[1] == 0 and ses2.next_last_tok.cpu().tolist()[1] == -1
+    assert kvd2.ctx_lens.cpu().tolist()[1] == 45                               # untouched
+    # nothing of sequence 1 reached the cache: pages differ from `before` only where sequences 0 and 2 wrote
+    changed = (kvd2.k_pages[0] != before).flatten(1).any(dim=1).nonzero().flatten().cpu().tolist()
+    own_blocks = set(kvh2.block_tables[1][kvh2.block_tables[1] >= 0].tolist())
+    assert not (set(changed) & own_blocks)
+    # (b) a token id outside the vocabulary
+    kvh3, kvd3, ses3 = _setup(harness, model, ctx, ks)
+    bad = voted.copy(); bad[2, 1] = DESC.vocab + 5
+    tb = _i32(bad)
+    ses3.forward(t[0], t[2], ks.tolist(), voted=tb)
+    torch.cuda.synchronize()
+    assert ses3.dev_status.item() & binding.MN_DEV_TOKEN
+    assert (ses3.greedy[2].cpu().numpy() == -1).all() and np.array_equal(ses3.greedy[:2].cpu().numpy(), ref_greedy[:2])
+    # (c) device spec_len disagrees with the host copy: the whole batch is disabled, nothing is written
+    kvh4, kvd4, ses4 = _setup(harness, model, ctx, ks)
+    before4 = kvd4.k_pages[0].clone()
+    wrong = _i32([3, 2, 3])
+    ses4.forward(t[0], wrong, ks.tolist(), voted=t[1])
+    torch.cuda.synchronize()
+    assert ses4.dev_status.item() & binding.MN_DEV_SPEC_LEN
+    assert (ses4.greedy.cpu().numpy() == -1).all() and torch.equal(kvd4.k_pages[0], before4)

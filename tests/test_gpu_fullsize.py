@@ -1,0 +1,123 @@
+"""Full-size GPU checks in the launch configuration bench.py times.  The oracle cannot run 80 layers, so
+the full-depth step is checked through properties that hold at any size (all-greedy drafts are fully
+accepted, a corruption at position i cuts acceptance at i, bit reproducibility); the attention-only
+configuration (32 x 8192 keys) is checked on sampled sequences against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import minions_oracle as orc
+from paper_2402_15678_amd import synth
+
+pytestmark = pytest.mark.gpu
+TOL = 3e-2
+
+
+def _i32(a):
+    return torch.tensor(np.asarray(a, np.int32), dtype=torch.int32, device="cuda:0")
+
+
+def test_llama70b_full_depth_b16_k8_properties():
+    from paper_2402_15678_amd import harness
+    wl = synth.WORKLOADS[2]
+    desc = wl.desc
+    free, _ = torch.cuda.mem_get_info()
+    if free < 170e9:
+        pytest.skip("needs ~150 GB of free HBM")
+    model = harness.DeviceModel.random_on_device(desc, wl.seed)
+    ctx, ks = synth.draw_ctx_lens(wl), synth.draw_spec_lens(wl)
+    B, k = wl.batch, int(ks.max())
+    kvd = harness.DeviceKV.random_on_device(desc, ctx, ks, wl.seed, wl.block_size)
+    max_ctx = int((ctx + ks + 1).max())
+    ctx0 = kvd.ctx_lens.clone()
+    g = synth.stream(wl.seed, 600)
+    last = _i32(g.integers(0, desc.vocab, size=B))
+    # the library's own greedy continuation, one token at a time
+    one = harness.VerifySession(model, kvd, B, 0, 1, max_ctx, max_rows=B)
+    zeros, dummy = _i32(np.zeros(B)), _i32(np.zeros((B, 1)))
+    cur, cont = last.clone(), []
+    for _ in range(k + 1):
+        one.forward(cur, zeros, [0] * B, voted=dummy)
+        one.accept(zeros, voted=dummy)
+        cur = one.next_last_tok.clone()
+        cont.append(cur.cpu().numpy())
+    cont = np.stack(cont, axis=1)                                   # [B][k+1]: token after the pending one, ...
+    kvd.ctx_lens.copy_(ctx0)
+    ses = harness.VerifySession(model, kvd, B, k, 3, max_ctx, max_rows=B * (k + 1), want_logits=True)
+    spec, w = _i32(ks), torch.ones(3, device="cuda:0")
+
+    def run(drafts):
+        kvd.ctx_lens.copy_(ctx0)
+        d = _i32(drafts)
+        ses.step(last, d, spec, ks.tolist(), w)
+        torch.cuda.synchronize()
+        assert ses.dev_status.item() == 0
+        return (ses.accepted_len.cpu().numpy().copy(), ses.out_tokens.cpu().numpy().copy(),
+                ses.logits.clone(), kvd.ctx_lens.cpu().numpy().copy())
+
+    good = np.repeat(cont[:, None, :k], 3, axis=1)                  # all three drafts = greedy continuation
+    acc, out, logits, new_ctx = run(good)
+    lg = logits.cpu().numpy().reshape(B, k + 1, -1)
+    full = 0
+    for b in range(B):
+        a = int(acc[b])
+        assert np.array_equal(out[b, :a], cont[b, :a])
+        assert new_ctx[b] == ctx[b] + a + 1
+        if a == k:
+            full += 1
+            assert out[b, k] == cont[b, k]
+        else:
+            # one-pass and sequential decoding may only part at a near tie of the one-pass logits
+            part = np.partition(lg[b, a], -2)
+            assert part[-1] - part[-2] < 2 * TOL, (b, a, part[-1] - part[-2])
+    assert full >= B // 2, full                                   # 80 layers of fp16 noise: near ties do flip
+    # bit reproducibility of the whole step
+    acc2, out2, logits2, _ = run(good)
+    assert torch.equal(logits, logits2) and np.array_equal(acc, acc2) and np.array_equal(out, out2)
+    # corruption of every draft at position i_b: acceptance stops exactly there and the true token is emitted
+    cut = g.integers(0, k, size=B)
+    bad = good.copy()
+    for b in range(B):
+        bad[b, :, cut[b]] = (good[b, 0, cut[b]] + 1 + g.integers(0, desc.vocab - 1)) % desc.vocab
+    acc3, out3, _, ctx3 = run(bad)
+    for b in range(B):
+        if acc[b] == k:                                             # sequences whose clean run was decisive
+            assert acc3[b] == cut[b], (b, acc3[b], cut[b])
+            assert np.array_equal(out3[b, :cut[b] + 1], cont[b, :cut[b] + 1])
+            assert ctx3[b] == ctx[b] + cut[b] + 1
+
+
+def test_attention_only_config_full_size_sampled_against_oracle():
+    from paper_2402_15678_amd import binding, harness
+    wl = synth.WORKLOADS[4]
+    desc = wl.desc
+    B = wl.batch
+    ctx, ks = synth.draw_ctx_lens(wl), synth.draw_spec_lens(wl)
+    total = ctx + ks + 1                                            # 8192 keys, the last 16 are the queries' own
+    kvh = synth.make_paged_kv(desc, total, [-1] * B, wl.seed)
+    kvd = harness.DeviceKV.from_host(desc, kvh)
+    kvd.ctx_lens.copy_(torch.from_numpy(ctx))
+    M = int((ks + 1).sum())
+    q = synth.stream(wl.seed, 9).standard_normal((M, desc.n_heads, desc.head_dim), dtype=np.float32)
+    q = q.astype(np.float16).astype(np.float32)
+    tiny = synth.ModelDesc(desc.arch, desc.dtype, 1, 128, desc.n_heads, desc.n_kv_heads, desc.head_dim, 128, 8, 8192)
+    model = harness.DeviceModel.from_host(tiny, synth.make_weights(tiny, 1))
+    q_d = harness.to_device_act(q, desc.dtype)
+    out = torch.full((M, desc.n_heads * desc.head_dim), float("nan"), dtype=torch.float16, device="cuda:0")
+    max_ctx = int(total.max())
+    wsb = binding.mn_workspace_bytes(model.ctx, B, M, max_ctx)
+    ws = torch.empty((wsb,), dtype=torch.uint8, device="cuda:0")
+    st = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    spec = _i32(ks)
+    binding.mn_attention(model.ctx, q_d.data_ptr(), spec.data_ptr(), binding.host_i32(ks.tolist()), B, max_ctx, kvd.c, 0,
+                         out.data_ptr(), ws.data_ptr(), wsb, st.data_ptr(), harness.stream_ptr())
+    torch.cuda.synchronize()
+    assert st.item() == 0
+    got = out.float().cpu().numpy().reshape(M, desc.n_heads, desc.head_dim)
+    assert np.isfinite(got).all()
+    rows = np.concatenate([[0], np.cumsum(ks + 1)])
+    for b in (0, 13, 31):                                           # sampled sequences, every head and query row
+        K, V = synth.gather_sequence_kv(kvh, 0, b, int(total[b]))
+        want = orc.attention_cached(desc, q[rows[b]:rows[b + 1]].astype(np.float64), K.astype(np.float64),
+                                    V.astype(np.float64), int(ctx[b]))
+        assert np.abs(got[rows[b]:rows[b + 1]] - want).max() < 2e-3
