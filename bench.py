@@ -35,7 +35,22 @@ def parse_args():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the real depth); for experiments")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=3, help="extra steps run with the timing taps on")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device copy (a kernel of known traffic, for scaling rocprofv3 byte counters)")
     return ap.parse_args()
+
+
+def measured_traffic(workload_name):
+    """HBM bytes per GEMM launch from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE scaled by a
+    copy kernel of known size), or None when there is no summary for this workload."""
+    path = os.path.join(ROOT, "profiles", "gemm_w16_kernel_%s.hbm_traffic.txt" % workload_name)
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(wl, desc, M, ks, ctx, n_drafts):
@@ -165,6 +180,13 @@ def main():
         prof = binding.mn_profile_collect(model.ctx)
         binding.mn_profile_enable(model.ctx, False)
 
+    if args.calibrate_copy:
+        src = torch.empty((1 << 30,), dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     gemm_bytes_step = 2.0 * desc.gemm_params()          # every matrix parameter (2 bytes) is needed once per step
     roofline = None
     families = None
@@ -175,7 +197,9 @@ def main():
         achieved = gemm_bytes_step * ps / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else 0.0
         flops = 2.0 * M * desc.gemm_params() * ps
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "gemm_w16_kernel",
+                    "frac": achieved / HBM_PEAK_GBS,
+                    "traffic": measured_traffic(wl.name) if args.layers <= 0 else None,
+                    "algorithmic_bytes_per_launch": gemm_bytes_step / max(1, gemm_n // ps), "kernel": "gemm_w16_kernel",
                     "launches_per_step": gemm_n // ps, "avg_launch_us": per_launch_ms * 1e3,
                     "mfma_tflops": flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0,
                     "mfma_frac": flops / (gemm_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS if gemm_ms > 0 else 0.0}
