@@ -176,9 +176,9 @@ static Layout make_layout(const mn_model_desc& d, int B, int M, int max_ctx) {
   const int nqkv = (d.n_heads + 2 * d.n_kv_heads) * d.head_dim;
   const int w1r = d.d_ffn * (d.arch == MN_ARCH_LLAMA ? 2 : 1);
   size_t pmax = 0;
-  const int Ns[4] = {nqkv, d.d_model, w1r, d.d_model};
-  const int Ks[4] = {d.d_model, d.n_heads * d.head_dim, d.d_model, d.d_ffn};
-  for (int i = 0; i < 4; ++i) {
+  const int Ns[5] = {nqkv, d.d_model, w1r, d.d_model, d.vocab};
+  const int Ks[5] = {d.d_model, d.n_heads * d.head_dim, d.d_model, d.d_ffn, d.d_model};
+  for (int i = 0; i < 5; ++i) {
     const size_t s = (size_t)gemm_pick_split(M, Ns[i], Ks[i], d.dtype);
     const size_t b = s * Mr * Ns[i] * 4;
     if (b > pmax) pmax = b;
@@ -420,7 +420,16 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
   }
   norm((const float*)c->final_norm_g, (const float*)c->final_norm_b, d.n_layers == 0);
   float* lg = logits ? logits : w.at<float>(w.L.logits);
-  gemm(h, c->lm_head, lg, d.vocab, d.d_model, 1);
+  {
+    const int s = gemm_pick_split(M, d.vocab, d.d_model, d.dtype);
+    if (s == 1) {
+      gemm(h, c->lm_head, lg, d.vocab, d.d_model, 1);
+    } else {
+      gemm(h, c->lm_head, part, d.vocab, d.d_model, s);
+      Tap t(&c->prof, MN_PROF_ARGMAX, st);
+      launch_reduce_partials(part, s, (size_t)M * d.vocab, lg, (size_t)M * d.vocab, st);
+    }
+  }
   {
     Tap t(&c->prof, MN_PROF_ARGMAX, st);
     launch_argmax_rows(lg, M, d.vocab, rows, k_max, greedy, B, st);

@@ -38,8 +38,6 @@ constexpr int WBLOCK = NWG * KB;  // elements of one packed 128 x 128 weight blo
 // the LDS cycles.
 __device__ __forceinline__ int lds_slot(int row, int chunk) { return row * LDS_ROW + (((chunk + 2 * row) & 15) << 3); }
 
-template <int MT>
-constexpr size_t gemm_smem_bytes() { return (size_t)2 * 16 * MT * LDS_ROW * sizeof(f16_t); }
 
 // Workgroup = 4 waves; wave w owns NTW 16-column tiles; every wave covers all MT 16-row tiles.
 // MFMA orientation: the weight fragment is the row operand (rows = output columns n), the
@@ -57,17 +55,25 @@ constexpr size_t gemm_smem_bytes() { return (size_t)2 * 16 * MT * LDS_ROW * size
 // columns; it stores silu(gate) * up as fp16 [M][F] and nothing else.
 enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1 };
 
-template <int MT, int NTW, int EPI>
-__global__ void __launch_bounds__(256, 2) gemm_w16_kernel(const f16_t* __restrict__ A, const bf16_t* __restrict__ W,
+template <int MT, int NTW, int EPI, int NW>
+__global__ void __launch_bounds__(NW * 64, 2) gemm_w16_kernel(const f16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                            void* __restrict__ out_, const float* __restrict__ bias,
                                                            int M, int N, int K, int k_per_split) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem[];
-  f16_t* s_a = reinterpret_cast<f16_t*>(gemm_smem);  // [2][16*MT][LDS_ROW]
-  constexpr int TILE = 16 * MT * LDS_ROW;
+  // two activation-tile buffers as separate objects: the compiler then knows that a DMA into one
+  // does not touch the reads of the other
+  __shared__ __attribute__((aligned(1024))) f16_t s_a0[16 * MT * LDS_ROW];
+  __shared__ __attribute__((aligned(1024))) f16_t s_a1[16 * MT * LDS_ROW];
+  // NW = 4: one 128-column block per workgroup, two workgroups per CU.  NW = 8: two adjacent blocks per
+  // workgroup (waves 0-3 / 4-7), one workgroup per CU: the activation tile is then fetched once per 256
+  // columns, which halves the L2 -> LDS traffic and the load-unit time it costs.
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
-  const int n_wg = blockIdx.x * (64 * NTW);
+  const int w4 = wave & 3;                                      // wave inside its 128-column block
+  const int nblk_all = (N + NWG - 1) / NWG;
+  const int nblk = blockIdx.x * (NW / 4) + (wave >> 2);         // this wave's column block
+  const int nblk_rd = min(nblk, nblk_all - 1);                  // past the end: re-read the last block, store nothing
+  const int n_wg = nblk * NWG;
   const int split = blockIdx.y;
   const int m0 = blockIdx.z * (16 * MT);
   const int k_begin = split * k_per_split;
@@ -75,30 +81,41 @@ __global__ void __launch_bounds__(256, 2) gemm_w16_kernel(const f16_t* __restric
   const int n_iter = (k_end - k_begin) / KB;
 
   // this wave's stream inside the workgroup's contiguous run of 32 KB blocks
-  const bf16_t* wbase = W + ((size_t)blockIdx.x * (K / KB) + k_begin / KB) * (size_t)WBLOCK + wave * (NTW * KS * 512) + lane * 8;
+  const bf16_t* wbase = W + ((size_t)nblk_rd * (K / KB) + k_begin / KB) * (size_t)WBLOCK + w4 * (NTW * KS * 512) + lane * 8;
 
-  // Activation tile staging: 16*MT rows x 16 chunks of 16 bytes = MT chunks per thread.  Every load in the main loop is unconditional, with
-  // clamped addresses (rows past M re-read row M-1 and feed output rows that are never stored;
-  // iterations past the end re-read the last block), so the compiler can count outstanding loads and
-  // wait for exactly the ones it needs instead of draining the queue.
-  constexpr int CPR = KB / 8;  // chunks per row
-  static_assert(16 * MT * CPR == MT * 256, "one chunk per thread per row tile");
-  const int a_r0 = tid / CPR, a_ch = tid % CPR;  // chunk i of this thread: row a_r0 + 16 i, 16-byte chunk a_ch
-  const f16_t* a_base = A + k_begin + a_ch * 8;
-  const int a_dst0 = lds_slot(a_r0, a_ch);  // rows 16 apart share the rotation: (2 * 16) mod 16 == 0
+  // Activation tile: 16*MT rows x 256 bytes = 4*MT chunks of 1 KB (four rows each).  Wave w brings in
+  // chunks w, w + NW, ... with direct global->LDS loads (no staging registers, no ds_write): a wave
+  // load drops lane i's 16 bytes at chunk base + 16 i, so lane i fetches the piece that belongs there
+  // under the rotated layout: row = 4c + i/16, k-chunk = (i%16 - 2 row) mod 16.  Rows past M re-read row
+  // M-1 (they feed output rows that are never stored); every load in the loop is unconditional.
+  constexpr int A_PER_WAVE = (4 * MT + NW - 1) / NW;
+  const f16_t* a_lane[A_PER_WAVE];
+#pragma unroll
+  for (int i = 0; i < A_PER_WAVE; ++i) {
+    const int row = 4 * (i * NW + wave) + (lane >> 4);
+    const int kc = ((lane & 15) - 2 * row) & 15;
+    a_lane[i] = A + (size_t)min(m0 + row, M - 1) * K + k_begin + kc * 8;
+  }
   const int last = n_iter - 1;
   const bf16_t* wlane = wbase;
 
-#define MN_LOAD_A(STAGE, LO, CNT, IT)                                                              \
-  _Pragma("unroll") for (int i_ = 0; i_ < (CNT); ++i_) {                                           \
-    const int row_ = min(m0 + a_r0 + 16 * ((LO) + i_), M - 1);                                     \
-    STAGE[i_] = *reinterpret_cast<const u32x4*>(a_base + (size_t)row_ * K + (IT) * KB);            \
-  }
-#define MN_STORE_A(STAGE, LO, CNT, BUF)                                                            \
-  _Pragma("unroll") for (int i_ = 0; i_ < (CNT); ++i_)                                             \
-    *reinterpret_cast<u32x4*>(&s_a[(BUF) * TILE + a_dst0 + ((LO) + i_) * 16 * LDS_ROW]) = STAGE[i_];
+#define MN_DMA_A(DST, IT)                                                                            \
+  _Pragma("unroll") for (int i_ = 0; i_ < A_PER_WAVE; ++i_)                                          \
+    if ((4 * MT) % NW == 0 || i_ * NW + wave < 4 * MT) /* wave-uniform */                            \
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a_lane[i_] + (IT) * KB),     \
+                                       (__attribute__((address_space(3))) void*)((DST) + (i_ * NW + wave) * 512), 16, 0, 0);
 #define MN_W_PTR(IT, NT, KS_) \
   reinterpret_cast<const u32x4*>(wlane + (size_t)min((IT), last) * WBLOCK + ((NT) * KS + (KS_)) * 512)
+// Wait until at most N (8 or 16) of this wave's memory loads are outstanding (loads complete in order).
+// The wait is the compiler's own s_waitcnt builtin, so its wait-count bookkeeping sees it, fenced on
+// both sides so that no load moves across it.  Encoding (gfx9 family): vmcnt = bits [3:0] and [15:14],
+// expcnt [6:4] = 7 and lgkmcnt [11:8] = 15 mean "do not wait".
+#define MN_WAIT_VM(N)                                                                   \
+  {                                                                                     \
+    asm volatile("" ::: "memory");                                                      \
+    __builtin_amdgcn_s_waitcnt((((N) & 15) | (((N) >> 4) << 14)) | (7 << 4) | (15 << 8)); \
+    asm volatile("" ::: "memory");                                                      \
+  }
 
   f32x4 acc[NTW][MT];
 #pragma unroll
@@ -108,99 +125,82 @@ __global__ void __launch_bounds__(256, 2) gemm_w16_kernel(const f16_t* __restric
 
   if (n_iter > 0) {  // (uniform per workgroup)
     u32x4 ring0[NTW][KS], ring1[NTW][KS];  // raw bf16 fragments of the next two iterations
-    {
-      u32x4 st0[MT];
-      MN_LOAD_A(st0, 0, MT, 0)
+    MN_DMA_A(s_a0, 0)
+    asm volatile("" ::: "memory");
 #pragma unroll
-      for (int nt = 0; nt < NTW; ++nt)
+    for (int nt = 0; nt < NTW; ++nt)
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          ring0[nt][ks] = *MN_W_PTR(0, nt, ks);
-          ring1[nt][ks] = *MN_W_PTR(1, nt, ks);
-        }
-      MN_STORE_A(st0, 0, MT, 0)
-      // Land the first two ring slots before the loop (an empty asm that reads them).  The compiler sizes
-      // its in-loop waits by the shortest distance between a load and its use over all paths; without
-      // this the short prologue path would halve the prefetch depth of every iteration.
-#pragma unroll
-      for (int nt = 0; nt < NTW; ++nt)
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          asm volatile("" : "+v"(ring0[nt][ks]));
-          asm volatile("" : "+v"(ring1[nt][ks]));
-        }
-    }
-    __syncthreads();
+      for (int ks = 0; ks < KS; ++ks) {
+        ring0[nt][ks] = *MN_W_PTR(0, nt, ks);
+        ring1[nt][ks] = *MN_W_PTR(1, nt, ks);
+      }
+    // everything lands before the loop (the two ring slots arrive together with the tile anyway): the
+    // compiler sizes its in-loop waits by the worst path into the loop, and this path is then empty
+    MN_WAIT_VM(0);
+    __builtin_amdgcn_s_barrier();
 
-#ifndef MN_ABLATE
-#define MN_ABLATE 0
+#ifndef MN_SCHED_MODE
+#define MN_SCHED_MODE 0  // 0: scheduling fence after every row-tile group; 1: after every k-step; 2: none
 #endif
-#if MN_ABLATE & 1  // experiment: no LDS reads / MFMAs, keep the weight stream alive
-#define MN_ABLATE_GROUPS 0
-#define MN_ABLATE_SKIP_COMPUTE(W) { acc[0][0][0] += (float)W[0][0] + (float)W[1][0]; }
-#else
-#define MN_ABLATE_GROUPS 2
-#define MN_ABLATE_SKIP_COMPUTE(W)
-#endif
-// One iteration on ring slot RING.  Issue order matters because loads return in order: the next
-// activation tile (L2 hits, needed at the end of this iteration) goes first, then, k-step by k-step, the
-// weight refills for iteration it+2 (HBM, needed two iterations from now), so waiting for the tile
-// never waits for a refill.  The row tiles of a k-step run in two groups to keep the live set small.
-#define MN_GEMM_ITER(RING, IT)                                                                              \
+// One iteration on ring slot RING, reading tile CUR and bringing the next tile into NXT.  Issue order
+// matters because loads complete in order: the tile loads go first (L2 hits, needed at the end of this
+// iteration), then, k-step by k-step, the NTW*KS = 8 weight refills for iteration it+2 (HBM, needed two
+// iterations from now).  The compiler-level fence keeps the two groups apart, so "at most 8 outstanding"
+// at the bottom means exactly "the tile has landed" without waiting for any refill.
+#define MN_GEMM_ITER(RING, CUR, NXT, IT)                                                                    \
   {                                                                                                         \
     const int it_ = (IT);                                                                                   \
-    const int buf_ = it_ & 1;                                                                               \
     const int nxt_ = min(it_ + 1, last);                                                                    \
-    u32x4 sa_[MT];                                                                                          \
-    if (!(MN_ABLATE & 2)) { MN_LOAD_A(sa_, 0, MT, nxt_) }                                                   \
-    /* a compiler-level memory fence: without it the loads above are sunk to the stores at the bottom */    \
+    /* pin this iteration's ring slot below the previous barrier: the compiler otherwise hoists the      */ \
+    /* widening above it, where the tile loads are still pending and every wait becomes a full drain     */ \
+    _Pragma("unroll") for (int nt = 0; nt < NTW; ++nt)                                                      \
+      _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(RING[nt][ks]));              \
+    MN_DMA_A(NXT, nxt_)                                                                                     \
     asm volatile("" ::: "memory");                                                                          \
-    const f16_t* tile_ = s_a + buf_ * TILE;                                                                 \
     _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                                     \
       f16x8 wcur_[NTW];                                                                                     \
       _Pragma("unroll") for (int nt = 0; nt < NTW; ++nt) {                                                  \
         wcur_[nt] = bf16x8_to_f16x8(RING[nt][ks]);                                                          \
         RING[nt][ks] = *MN_W_PTR(it_ + 2, nt, ks);                                                          \
       }                                                                                                     \
-      MN_ABLATE_SKIP_COMPUTE(wcur_)                                                                         \
-      _Pragma("unroll") for (int grp = 0; grp < MN_ABLATE_GROUPS; ++grp) {                                  \
+      _Pragma("unroll") for (int grp = 0; grp < 2; ++grp) {                                                 \
         constexpr int G0 = (MT + 1) / 2;                                                                    \
         const int lo_ = grp ? G0 : 0, cnt_ = grp ? MT - G0 : G0;                                            \
         f16x8 bfrag_[G0];                                                                                   \
         _Pragma("unroll") for (int i = 0; i < G0; ++i)                                                      \
           if (i < cnt_)                                                                                     \
-            bfrag_[i] = *reinterpret_cast<const f16x8*>(&tile_[(lo_ + i) * 16 * LDS_ROW + lds_slot(l16, ks * 4 + g)]); \
+            bfrag_[i] = *reinterpret_cast<const f16x8*>(&CUR[(lo_ + i) * 16 * LDS_ROW + lds_slot(l16, ks * 4 + g)]); \
         _Pragma("unroll") for (int nt = 0; nt < NTW; ++nt)                                                  \
           _Pragma("unroll") for (int i = 0; i < G0; ++i)                                                    \
             if (i < cnt_)                                                                                   \
               acc[nt][lo_ + i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wcur_[nt], bfrag_[i], acc[nt][lo_ + i], 0, 0, 0); \
-        __builtin_amdgcn_sched_barrier(0);                                                                  \
+        if (MN_SCHED_MODE == 0 || (MN_SCHED_MODE == 1 && grp == 1)) __builtin_amdgcn_sched_barrier(0);      \
       }                                                                                                     \
     }                                                                                                       \
-    if (!(MN_ABLATE & 2)) { MN_STORE_A(sa_, 0, MT, buf_ ^ 1) }                                              \
-    if (!(MN_ABLATE & 4)) __syncthreads();                                                                  \
+    MN_WAIT_VM(8);                                                                                          \
+    __builtin_amdgcn_s_barrier();                                                                           \
   }
 
     // pairs of iterations with no branch inside the loop (a conditional second half would give the
     // compiler a short path that shrinks every wait), then the odd one out
     int it = 0;
     for (; it + 1 < n_iter; it += 2) {
-      MN_GEMM_ITER(ring0, it)
-      MN_GEMM_ITER(ring1, it + 1)
+      MN_GEMM_ITER(ring0, s_a0, s_a1, it)
+      MN_GEMM_ITER(ring1, s_a1, s_a0, it + 1)
     }
-    if (it < n_iter) MN_GEMM_ITER(ring0, it)
+    if (it < n_iter) MN_GEMM_ITER(ring0, s_a0, s_a1, it)
 #undef MN_GEMM_ITER
   }
-#undef MN_LOAD_A
-#undef MN_STORE_A
+#undef MN_DMA_A
 #undef MN_W_PTR
+#undef MN_WAIT_VM
 
   // epilogue: lane holds D[n = base + 4g + i][m = mt*16 + l16]
   if constexpr (EPI == EPI_SWIGLU) {
     static_assert(NTW == 2, "gate and up tiles of one wave");
     f16_t* act = reinterpret_cast<f16_t*>(out_);
     const int F = N >> 1;
-    const int f = blockIdx.x * 64 + wave * 16 + g * 4;
+    const int f = nblk * 64 + w4 * 16 + g * 4;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       const int m = m0 + mt * 16 + l16;
@@ -215,7 +215,7 @@ __global__ void __launch_bounds__(256, 2) gemm_w16_kernel(const f16_t* __restric
     float* o = reinterpret_cast<float*>(out_) + (size_t)split * M * N;
 #pragma unroll
     for (int nt = 0; nt < NTW; ++nt) {
-      const int n = n_wg + (wave * NTW + nt) * 16 + g * 4;
+      const int n = n_wg + (w4 * NTW + nt) * 16 + g * 4;
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         const int m = m0 + mt * 16 + l16;
@@ -333,15 +333,28 @@ static GemmTune tune() {
   return t;
 }
 
+// 8-wave workgroups (256 columns) for this N?  (experiment switch MN_GEMM_WIDE: 0 never, 1 always)
+static bool gemm_wide(int N) {
+  static int mode = [] {
+    const char* e = getenv("MN_GEMM_WIDE");
+    return e ? atoi(e) : -1;
+  }();
+  if (mode >= 0) return mode != 0;
+  // wide when the halved grid still covers (nearly) every CU with the splits it can get
+  const int nb2 = ((N + NWG - 1) / NWG + 1) / 2;
+  return nb2 >= 100;
+}
+
 int gemm_pick_split(int M, int N, int K, int dtype) {
   if (dtype != MN_DT_BF16) return 1;
   const int forced = tune().split;
-  const int nblocks = (N + NWG - 1) / NWG;
+  const bool wide = M > 96 && gemm_wide(N);  // 8-wave workgroups: half as many, one per CU
+  const int nblocks = wide ? ((N + NWG - 1) / NWG + 1) / 2 : (N + NWG - 1) / NWG;
   const int iters = K / KB;
   // as many splits as keep the whole grid resident at once (two workgroups per CU), each split at
   // least 16 iterations long (measured: shorter splits lose more to ramp-up and partial sums than
   // the extra workgroups win)
-  int s = forced >= 1 ? forced : tune().target / nblocks;
+  int s = forced >= 1 ? forced : (wide ? tune().target / 2 : tune().target) / nblocks;
   if (forced < 1 && s > iters / 16) s = iters / 16;
   if (s > MN_MAX_SPLIT_K) s = MN_MAX_SPLIT_K;
   if (s < 1) s = 1;
@@ -350,24 +363,18 @@ int gemm_pick_split(int M, int N, int K, int dtype) {
   return (iters + per - 1) / per;
 }
 
-template <int MT>
+template <int MT, int NW>
 static void launch_bf16_mt(const GemmArgs& a, int m_chunks, hipStream_t st) {
   const int iters = a.K / KB;
   const int per = (iters + a.split_k - 1) / a.split_k;  // iterations per split
-  dim3 grid((a.N + NWG - 1) / NWG, a.split_k, m_chunks);
+  const int nblk = (a.N + NWG - 1) / NWG;
+  dim3 grid((nblk + NW / 4 - 1) / (NW / 4), a.split_k, m_chunks);
   const f16_t* A = reinterpret_cast<const f16_t*>(a.a);
   const bf16_t* W = reinterpret_cast<const bf16_t*>(a.w);
-  constexpr size_t smem = gemm_smem_bytes<MT>();
-  static bool attr_set = false;  // once per instantiation: allow more than 64 KB of dynamic LDS
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_w16_kernel<MT, 2, EPI_PARTIAL>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_w16_kernel<MT, 2, EPI_SWIGLU>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    attr_set = true;
-  }
   if (a.swiglu_act)
-    gemm_w16_kernel<MT, 2, EPI_SWIGLU><<<grid, 256, smem, st>>>(A, W, a.swiglu_act, nullptr, a.M, a.N, a.K, per * KB);
+    gemm_w16_kernel<MT, 2, EPI_SWIGLU, NW><<<grid, NW * 64, 0, st>>>(A, W, a.swiglu_act, nullptr, a.M, a.N, a.K, per * KB);
   else
-    gemm_w16_kernel<MT, 2, EPI_PARTIAL><<<grid, 256, smem, st>>>(A, W, a.out, a.bias, a.M, a.N, a.K, per * KB);
+    gemm_w16_kernel<MT, 2, EPI_PARTIAL, NW><<<grid, NW * 64, 0, st>>>(A, W, a.out, a.bias, a.M, a.N, a.K, per * KB);
 }
 
 void launch_gemm(const GemmArgs& a, hipStream_t st) {
@@ -380,13 +387,13 @@ void launch_gemm(const GemmArgs& a, hipStream_t st) {
   }
   const int tiles = (a.M + 15) / 16;
   // row tiles per workgroup: everything in one chunk up to 9 tiles (144 rows), else chunks of 8
-  if (tiles <= 1) launch_bf16_mt<1>(a, 1, st);
-  else if (tiles <= 2) launch_bf16_mt<2>(a, 1, st);
-  else if (tiles <= 3) launch_bf16_mt<3>(a, 1, st);
-  else if (tiles <= 4) launch_bf16_mt<4>(a, 1, st);
-  else if (tiles <= 6) launch_bf16_mt<6>(a, 1, st);
-  else if (tiles <= 9) launch_bf16_mt<9>(a, 1, st);
-  else launch_bf16_mt<8>(a, (tiles + 7) / 8, st);
+  if (tiles <= 1) launch_bf16_mt<1, 4>(a, 1, st);
+  else if (tiles <= 2) launch_bf16_mt<2, 4>(a, 1, st);
+  else if (tiles <= 3) launch_bf16_mt<3, 4>(a, 1, st);
+  else if (tiles <= 4) launch_bf16_mt<4, 4>(a, 1, st);
+  else if (tiles <= 6) launch_bf16_mt<6, 4>(a, 1, st);
+  else if (tiles <= 9) { if (gemm_wide(a.N)) launch_bf16_mt<9, 8>(a, 1, st); else launch_bf16_mt<9, 4>(a, 1, st); }
+  else launch_bf16_mt<8, 4>(a, (tiles + 7) / 8, st);
 }
 
 }  // namespace mn
