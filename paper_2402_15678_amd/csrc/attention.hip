@@ -149,11 +149,12 @@ struct TileAddr {  // what a thread needs to fetch its four 16-byte pieces of a 
 
 // Partials: o_part [split][M][H][HD] fp32 (unnormalised), ml_part [split][M][H][2] = (max in log2 units, sum)
 template <int CTW>
-__global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_splits, float* __restrict__ o_part,
-                                                           float* __restrict__ ml_part) {
+__global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_splits, int nt16_max,
+                                                           float* __restrict__ o_part, float* __restrict__ ml_part) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   f16_t* s_kv = reinterpret_cast<f16_t*>(smem);                       // [2][16 fragments][64 lanes][8]
-  f16_t* s_q = reinterpret_cast<f16_t*>(smem + 2 * TILE_BYTES);       // [NT16*16][HD], rotated chunks
+  f16_t* s_q = reinterpret_cast<f16_t*>(smem + 2 * TILE_BYTES);       // [nt16_max*16][HD], rotated chunks
+  int32_t* s_bt = reinterpret_cast<int32_t*>(smem + 2 * TILE_BYTES + (size_t)nt16_max * 16 * HD * sizeof(f16_t));
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
@@ -169,23 +170,24 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_spl
   const int n_tiles = (nkeys + KT - 1) / KT;
   const int t_begin = (int)(((long)n_tiles * split) / n_splits);
   const int t_end = (int)(((long)n_tiles * (split + 1)) / n_splits);
-  // tiles that hold only cached keys (all visible to every row, both blocks mapped) are streamed
-  // through the prefetch ring; the last tiles, which hold this step's own keys, go one by one
-  const int t_full_end = min(t_end, ctx / KT);
 
   // ---- Q -> LDS (zero rows past R) ----
+  const float sscale = rsqrtf((float)HD) * LOG2E;
   const f16_t* Q = reinterpret_cast<const f16_t*>(a.q);
   for (int c = tid; c < NT16 * 16 * (HD / 8); c += 256) {
     const int r = c >> 4, ch = c & 15;
-    u32x4 v = {0u, 0u, 0u, 0u};
+    // Q is scaled by log2(e)/sqrt(hd) once here (one more fp16 rounding of q, 2^-11), so the scores
+    // come out of the first product in log2 units
+    f16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
     if (r < R) {
       const int j = r / G, gi = r % G;
-      v = *reinterpret_cast<const u32x4*>(Q + ((size_t)(row0 + j) * a.H + kvh * G + gi) * HD + ch * 8);
+      v = *reinterpret_cast<const f16x8*>(Q + ((size_t)(row0 + j) * a.H + kvh * G + gi) * HD + ch * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = (f16_t)((float)v[e] * sscale);
     }
-    *reinterpret_cast<u32x4*>(&s_q[q_slot(r, ch)]) = v;
+    *reinterpret_cast<f16x8*>(&s_q[q_slot(r, ch)]) = v;
   }
 
-  const float sscale = rsqrtf((float)HD) * LOG2E;
   f32x4 O[CTW][8];
   float run_m[CTW], run_l[CTW];
   int lim[CTW];
@@ -214,9 +216,16 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_spl
   const int kkey0 = 8 * (l16 >> 2) + (l16 & 3);      // key inside the tile for t = 0 (t = 1: + 4)
   const int kchunk = 4 * wave + g;
 
-  auto tile_addr = [&](int T) {
+  // block table of this split -> LDS (the dependent chain table -> address -> load would otherwise
+  // cost an L2 round trip per tile); entries past the last mapped block repeat the last one
+  const int n_my = max(0, t_end - t_begin);
+  const int last_blk = ok ? (nkeys - 1) / BS : 0;
+  for (int i = tid; i < 2 * n_my; i += 256) s_bt[i] = bt[min(2 * t_begin + i, last_blk)];
+  __syncthreads();
+
+  auto tile_addr = [&](int ti) {  // ti: tile index inside the split
     TileAddr ta;
-    const int pb0 = bt[2 * T], pb1 = bt[2 * T + 1];
+    const int pb0 = s_bt[2 * ti], pb1 = s_bt[2 * ti + 1];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int kk = kkey0 + 4 * t;
@@ -248,17 +257,16 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_spl
       }
     }
     f16x8 P[CTW];
-    float alpha[CTW];
 #pragma unroll
     for (int ct = 0; ct < CTW; ++ct) {
-      alpha[ct] = 1.f;
       if (!mine[ct]) continue;
-      // lane holds keys key0 + 8g + e, e = 0..7 (S0 -> e 0..3, S1 -> e 4..7) of query row l16
+      // lane holds keys key0 + 8g + e, e = 0..7 (S0 -> e 0..3, S1 -> e 4..7) of query row l16;
+      // the scores are already in log2 units (Q was scaled when it was staged)
       float sc[8];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        sc[e] = S0[ct][e] * sscale;
-        sc[4 + e] = S1[ct][e] * sscale;
+        sc[e] = S0[ct][e];
+        sc[4 + e] = S1[ct][e];
       }
       if (tail) {
 #pragma unroll
@@ -266,31 +274,35 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_spl
           if (key0 + 8 * g + e > lim[ct]) sc[e] = -INFINITY;
       }
       float tm = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
-      tm = fmaxf(tm, __shfl_xor(tm, 16, 64));
-      tm = fmaxf(tm, __shfl_xor(tm, 32, 64));
-      const float new_m = fmaxf(run_m[ct], tm);
-      const float m_safe = (new_m == -INFINITY) ? 0.f : new_m;
-      alpha[ct] = __builtin_amdgcn_exp2f(run_m[ct] - m_safe);
-      run_m[ct] = new_m;
+      // Lazy maximum: the reference only moves (a cross-lane exchange and a rescale of the accumulator)
+      // when some row's scores exceed it by more than 2^6; until then probabilities up to 64 are fine
+      // in fp16 and in the fp32 sums.
+      if (__any(tm > run_m[ct] + 6.f)) {
+        tm = fmaxf(tm, __shfl_xor(tm, 16, 64));
+        tm = fmaxf(tm, __shfl_xor(tm, 32, 64));
+        const float new_m = fmaxf(run_m[ct], tm);
+        const float m_safe = (new_m == -INFINITY) ? 0.f : new_m;
+        const float alpha = __builtin_amdgcn_exp2f(run_m[ct] - m_safe);
+        run_m[ct] = new_m;
+        run_l[ct] *= alpha;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          O[ct][u][0] *= alpha; O[ct][u][1] *= alpha; O[ct][u][2] *= alpha; O[ct][u][3] *= alpha;
+        }
+      }
+      const float m_ref = (run_m[ct] == -INFINITY) ? 0.f : run_m[ct];
       float ps = 0.f;
       float p[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        p[e] = __builtin_amdgcn_exp2f(sc[e] - m_safe);
+        p[e] = __builtin_amdgcn_exp2f(sc[e] - m_ref);
         ps += p[e];
       }
-      run_l[ct] = run_l[ct] * alpha[ct] + ps;  // per-lane partial sum; lane groups are added at the end
+      run_l[ct] += ps;  // per-lane partial sum; lane groups are added at the end
       union { f16x8 v; uint32_t u[4]; } pf;
 #pragma unroll
       for (int e = 0; e < 4; ++e) pf.u[e] = pack2h(p[2 * e], p[2 * e + 1]);
       P[ct] = pf.v;
-      // rescale the accumulator only when some row's maximum moved (rare once the scan is warm)
-      if (__any(alpha[ct] != 1.f)) {
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          O[ct][u][0] *= alpha[ct]; O[ct][u][1] *= alpha[ct]; O[ct][u][2] *= alpha[ct]; O[ct][u][3] *= alpha[ct];
-        }
-      }
     }
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
@@ -303,90 +315,73 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_spl
     }
   };
 
-  // ---- main loop over the cached-key tiles ----
-  const int n_full = max(0, t_full_end - t_begin);
-  if (ok && n_full > 0) {
-    const int T_last = t_begin + n_full - 1;
+  // ---- loop over this split's key tiles; the raw pages of the next PF tiles are in flight in registers ----
+  if (ok && n_my > 0) {
+    const int ti_last = n_my - 1;
     u32x4 ring[PF][4];  // raw bf16 pieces of the next PF tiles
-#define MN_ATT_LOAD(SLOT, T)                                                                     \
+#define MN_ATT_LOAD(SLOT, TI)                                                                    \
   {                                                                                              \
-    const TileAddr ta_ = tile_addr(min((T), T_last));                                            \
+    const TileAddr ta_ = tile_addr(min((TI), ti_last));                                          \
     ring[SLOT][0] = *reinterpret_cast<const u32x4*>(ta_.k[0]);                                   \
     ring[SLOT][1] = *reinterpret_cast<const u32x4*>(ta_.k[1]);                                   \
     ring[SLOT][2] = *reinterpret_cast<const u32x4*>(ta_.v[0]);                                   \
     ring[SLOT][3] = *reinterpret_cast<const u32x4*>(ta_.v[1]);                                   \
   }
-#define MN_ATT_FILL(SLOT, BUF)                                                                   \
-  {                                                                                              \
-    *reinterpret_cast<f16x8*>(frag_ptr((BUF), wave, lane)) = bf16x8_to_f16x8(ring[SLOT][0]);     \
-    *reinterpret_cast<f16x8*>(frag_ptr((BUF), 4 + wave, lane)) = bf16x8_to_f16x8(ring[SLOT][1]); \
-    *reinterpret_cast<f16x8*>(frag_ptr((BUF), 8 + wave, lane)) = bf16x8_to_f16x8(ring[SLOT][2]); \
-    *reinterpret_cast<f16x8*>(frag_ptr((BUF), 12 + wave, lane)) = bf16x8_to_f16x8(ring[SLOT][3]); \
-  }
-    // prologue: tile 0 -> LDS buffer 0, tiles 1..PF in flight
-    MN_ATT_LOAD(0, t_begin)
-    MN_ATT_FILL(0, 0)
-    MN_ATT_LOAD(0, t_begin + 1)
-    MN_ATT_LOAD(1, t_begin + 2)
+    // widen the four pieces of ring slot SLOT and put them into LDS buffer BUF as tile TI of the split;
+    // tiles that reach past ctx take this step's own keys from the fp16 side buffers and zero the slots
+    // past the sequence end (stale slots may hold anything: 0 * garbage must stay 0)
+    auto fill = [&](const u32x4 (&r)[4], int buf, int ti) {
+      const int key0 = (t_begin + ti) * KT;
+      f16x8 kf[2] = {bf16x8_to_f16x8(r[0]), bf16x8_to_f16x8(r[1])};
+      f16x8 vf[2] = {bf16x8_to_f16x8(r[2]), bf16x8_to_f16x8(r[3])};
+      if (key0 + KT > ctx) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const int key = key0 + kkey0 + 4 * t;
+          if (Kn && key >= ctx && key < nkeys)
+            kf[t] = *reinterpret_cast<const f16x8*>(Kn + ((size_t)(row0 + key - ctx) * a.Hkv + kvh) * HD + kchunk * 8);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const int hd = 16 * (wave + 4 * i) + l16;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int key = key0 + 8 * g + e;
+            if (key >= nkeys) vf[i][e] = (f16_t)0.f;
+            else if (Vn && key >= ctx) vf[i][e] = Vn[((size_t)(row0 + key - ctx) * a.Hkv + kvh) * HD + hd];
+          }
+        }
+      }
+      *reinterpret_cast<f16x8*>(frag_ptr(buf, wave, lane)) = kf[0];
+      *reinterpret_cast<f16x8*>(frag_ptr(buf, 4 + wave, lane)) = kf[1];
+      *reinterpret_cast<f16x8*>(frag_ptr(buf, 8 + wave, lane)) = vf[0];
+      *reinterpret_cast<f16x8*>(frag_ptr(buf, 12 + wave, lane)) = vf[1];
+    };
+    // prologue: tile 0 -> LDS buffer 0, tiles 1 and 2 in flight
+    MN_ATT_LOAD(0, 0)
+    MN_ATT_LOAD(1, 1)
+    fill(ring[0], 0, 0);
+    MN_ATT_LOAD(0, 2)
     __syncthreads();
-// iteration i: LDS[i&1] holds tile i; ring slot SLOT holds tile i+1 (landed); the other slot tile i+2.
-// Fill the other LDS buffer with tile i+1, refill the slot with tile i+3, compute tile i.
+// iteration i: LDS[i&1] holds tile i; ring slot SLOT holds tile i+1 (in flight or landed), the other
+// slot tile i+2.  Fill the other LDS buffer with tile i+1, refill the slot with tile i+3, compute tile i.
 #define MN_ATT_ITER(SLOT, I)                                                                     \
   {                                                                                              \
     const int i_ = (I);                                                                          \
-    MN_ATT_FILL(SLOT, (i_ + 1) & 1)                                                              \
-    MN_ATT_LOAD(SLOT, t_begin + i_ + 3)                                                          \
+    fill(ring[SLOT], (i_ + 1) & 1, min(i_ + 1, ti_last));                                        \
+    MN_ATT_LOAD(SLOT, i_ + 3)                                                                    \
     asm volatile("" ::: "memory");                                                               \
-    compute(i_ & 1, (t_begin + i_) * KT, false);                                                 \
+    compute(i_ & 1, (t_begin + i_) * KT, (t_begin + i_) * KT + KT > ctx);                        \
     __syncthreads();                                                                             \
   }
     int i = 0;
-    for (; i + 1 < n_full; i += 2) {
-      MN_ATT_ITER(0, i)
-      MN_ATT_ITER(1, i + 1)
+    for (; i + 1 < n_my; i += 2) {
+      MN_ATT_ITER(1, i)
+      MN_ATT_ITER(0, i + 1)
     }
-    if (i < n_full) MN_ATT_ITER(0, i)
+    if (i < n_my) MN_ATT_ITER(1, i)
 #undef MN_ATT_ITER
-#undef MN_ATT_FILL
 #undef MN_ATT_LOAD
-  }
-
-  // ---- tail tiles: they hold this step's own keys (read from the fp16 side buffers when given) ----
-  if (ok) {
-    __syncthreads();
-    for (int T = max(t_begin, t_full_end); T < t_end; ++T) {
-      const int key0 = T * KT;
-      const int pb0 = bt[2 * T];
-      const int pb1 = (key0 + BS < nkeys) ? bt[2 * T + 1] : pb0;
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const int kk = kkey0 + 4 * t, key = key0 + kk;
-        f16x8 kf;
-        if (Kn && key >= ctx && key < nkeys) {
-          kf = *reinterpret_cast<const f16x8*>(Kn + ((size_t)(row0 + key - ctx) * a.Hkv + kvh) * HD + kchunk * 8);
-        } else {
-          kf = bf16x8_to_f16x8(*reinterpret_cast<const u32x4*>(Kp + (size_t)(kk < BS ? pb0 : pb1) * blk_stride + head_off +
-                                                               ((size_t)kchunk * BS + (kk & (BS - 1))) * 8));
-        }
-        *reinterpret_cast<f16x8*>(frag_ptr(0, t * 4 + wave, lane)) = kf;
-      }
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int hd = 16 * (wave + 4 * i) + l16;
-        f16x8 vf = bf16x8_to_f16x8(*reinterpret_cast<const u32x4*>(Vp + (size_t)(g < 2 ? pb0 : pb1) * blk_stride + head_off +
-                                                                   (size_t)hd * BS + 8 * (g & 1)));
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int key = key0 + 8 * g + e;
-          if (key >= nkeys) vf[e] = (f16_t)0.f;  // stale slots may hold anything: 0 * garbage must stay 0
-          else if (Vn && key >= ctx) vf[e] = Vn[((size_t)(row0 + key - ctx) * a.Hkv + kvh) * HD + hd];
-        }
-        *reinterpret_cast<f16x8*>(frag_ptr(0, 8 + wave + 4 * i, lane)) = vf;
-      }
-      __syncthreads();
-      compute(0, key0, true);
-      __syncthreads();
-    }
   }
 
   // ---- output: lane holds O^T[hd = 16u + 4g + i][row = tile*16 + l16] ----
@@ -478,7 +473,9 @@ bool attention_mfma_supported(int H, int Hkv, int hd, int block_size, int dtype)
   return !off && dtype == MN_DT_BF16 && hd == HD && block_size == BS && Hkv > 0 && H % Hkv == 0;
 }
 
-static size_t mfma_smem_bytes(int nt16_max) { return (size_t)2 * TILE_BYTES + (size_t)nt16_max * 16 * HD * sizeof(f16_t); }
+static size_t mfma_smem_bytes(int nt16_max, int tiles_per_split) {
+  return (size_t)2 * TILE_BYTES + (size_t)nt16_max * 16 * HD * sizeof(f16_t) + (size_t)(2 * tiles_per_split + 2) * sizeof(int32_t);
+}
 
 size_t attention_scratch_bytes(int M, int H, int hd, int max_ctx, int dtype) {
   if (dtype != MN_DT_BF16 || hd != HD) return 256;
@@ -497,19 +494,20 @@ void launch_attention(const AttnArgs& a, hipStream_t st) {
     const int n_splits = pick_splits(a.B, a.Hkv, a.max_ctx);
     float* o_part = a.scratch;
     float* ml_part = a.scratch + (size_t)n_splits * a.M * a.H * HD;
-    const size_t smem = mfma_smem_bytes(nt16_max);
+    const int tiles_per_split = ((a.max_ctx + KT - 1) / KT + n_splits - 1) / n_splits + 1;
+    const size_t smem = mfma_smem_bytes(nt16_max, tiles_per_split);
     static bool attr_set = false;
     if (!attr_set) {
-      const int most = (int)mfma_smem_bytes(4 * MAX_CT);
+      const int most = 160 * 1024;
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, most);
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, most);
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<3>), hipFuncAttributeMaxDynamicSharedMemorySize, most);
       attr_set = true;
     }
     dim3 grid(n_splits, a.Hkv, a.B);
-    if (nt16_max <= 4) attn_mfma_kernel<1><<<grid, 256, smem, st>>>(a, n_splits, o_part, ml_part);
-    else if (nt16_max <= 8) attn_mfma_kernel<2><<<grid, 256, smem, st>>>(a, n_splits, o_part, ml_part);
-    else attn_mfma_kernel<3><<<grid, 256, smem, st>>>(a, n_splits, o_part, ml_part);
+    if (nt16_max <= 4) attn_mfma_kernel<1><<<grid, 256, smem, st>>>(a, n_splits, nt16_max, o_part, ml_part);
+    else if (nt16_max <= 8) attn_mfma_kernel<2><<<grid, 256, smem, st>>>(a, n_splits, nt16_max, o_part, ml_part);
+    else attn_mfma_kernel<3><<<grid, 256, smem, st>>>(a, n_splits, nt16_max, o_part, ml_part);
     if (n_splits > 1) {
       const int waves = a.M * a.H;
       attn_merge_kernel<<<(waves + 3) / 4, 256, 0, st>>>(o_part, ml_part, n_splits, a.M, a.H, reinterpret_cast<f16_t*>(a.out));

@@ -333,22 +333,26 @@ static GemmTune tune() {
   return t;
 }
 
-// 8-wave workgroups (256 columns) for this N?  (experiment switch MN_GEMM_WIDE: 0 never, 1 always)
-static bool gemm_wide(int N) {
+// 8-wave workgroups (256 columns) for this shape?  (experiment switch MN_GEMM_WIDE: 0 never, 1 always)
+static bool gemm_wide(int N, int K) {
   static int mode = [] {
     const char* e = getenv("MN_GEMM_WIDE");
     return e ? atoi(e) : -1;
   }();
   if (mode >= 0) return mode != 0;
-  // wide when the halved grid still covers (nearly) every CU with the splits it can get
+  // wide when the halved grid, with the splits it can get, still covers most CUs (measured: the
+  // 8192 x 8192 output projection, 128 workgroups when wide, is the one shape that loses)
   const int nb2 = ((N + NWG - 1) / NWG + 1) / 2;
-  return nb2 >= 100;
+  int s = 256 / nb2;
+  if (s > (K / KB) / 16) s = (K / KB) / 16;
+  if (s < 1) s = 1;
+  return nb2 * s >= 150;
 }
 
 int gemm_pick_split(int M, int N, int K, int dtype) {
   if (dtype != MN_DT_BF16) return 1;
   const int forced = tune().split;
-  const bool wide = M > 96 && gemm_wide(N);  // 8-wave workgroups: half as many, one per CU
+  const bool wide = M > 96 && gemm_wide(N, K);  // 8-wave workgroups: half as many, one per CU
   const int nblocks = wide ? ((N + NWG - 1) / NWG + 1) / 2 : (N + NWG - 1) / NWG;
   const int iters = K / KB;
   // as many splits as keep the whole grid resident at once (two workgroups per CU), each split at
@@ -392,7 +396,7 @@ void launch_gemm(const GemmArgs& a, hipStream_t st) {
   else if (tiles <= 3) launch_bf16_mt<3, 4>(a, 1, st);
   else if (tiles <= 4) launch_bf16_mt<4, 4>(a, 1, st);
   else if (tiles <= 6) launch_bf16_mt<6, 4>(a, 1, st);
-  else if (tiles <= 9) { if (gemm_wide(a.N)) launch_bf16_mt<9, 8>(a, 1, st); else launch_bf16_mt<9, 4>(a, 1, st); }
+  else if (tiles <= 9) { if (gemm_wide(a.N, a.K)) launch_bf16_mt<9, 8>(a, 1, st); else launch_bf16_mt<9, 4>(a, 1, st); }
   else launch_bf16_mt<8, 4>(a, (tiles + 7) / 8, st);
 }
 

@@ -33,15 +33,17 @@ def test_llama70b_full_depth_b16_k8_properties():
     g = synth.stream(wl.seed, 600)
     last = _i32(g.integers(0, desc.vocab, size=B))
     # the library's own greedy continuation, one token at a time
-    one = harness.VerifySession(model, kvd, B, 0, 1, max_ctx, max_rows=B)
+    one = harness.VerifySession(model, kvd, B, 0, 1, max_ctx, max_rows=B, want_logits=True)
     zeros, dummy = _i32(np.zeros(B)), _i32(np.zeros((B, 1)))
-    cur, cont = last.clone(), []
+    cur, cont, seq_logits = last.clone(), [], []
     for _ in range(k + 1):
         one.forward(cur, zeros, [0] * B, voted=dummy)
         one.accept(zeros, voted=dummy)
         cur = one.next_last_tok.clone()
         cont.append(cur.cpu().numpy())
+        seq_logits.append(one.logits.cpu().numpy().copy())
     cont = np.stack(cont, axis=1)                                   # [B][k+1]: token after the pending one, ...
+    seq_logits = np.stack(seq_logits, axis=1)                       # [B][k+1][V]
     kvd.ctx_lens.copy_(ctx0)
     ses = harness.VerifySession(model, kvd, B, k, 3, max_ctx, max_rows=B * (k + 1), want_logits=True)
     spec, w = _i32(ks), torch.ones(3, device="cuda:0")
@@ -59,18 +61,28 @@ def test_llama70b_full_depth_b16_k8_properties():
     acc, out, logits, new_ctx = run(good)
     lg = logits.cpu().numpy().reshape(B, k + 1, -1)
     full = 0
+    worst_rel = 0.0
     for b in range(B):
         a = int(acc[b])
         assert np.array_equal(out[b, :a], cont[b, :a])
         assert new_ctx[b] == ctx[b] + a + 1
+        # up to the first position where the two decodings part they have seen the same tokens: their logits are
+        # the same quantity computed along two rounding paths (the sequential one re-reads its own K/V from
+        # the bf16 cache); 80 layers amplify that, so the bound is looser than the 2-layer tolerance
+        diff = lg[b, :a + 1] - seq_logits[b, :a + 1]
+        drift = np.abs(diff).max()
+        rel_rms = float(np.sqrt((diff ** 2).mean()) / lg[b, :a + 1].std())
+        worst_rel = max(worst_rel, rel_rms)
+        assert rel_rms < 0.05 and drift < 0.75, (b, drift, rel_rms)   # a wrong row or mask would give O(1)
         if a == k:
             full += 1
             assert out[b, k] == cont[b, k]
         else:
-            # one-pass and sequential decoding may only part at a near tie of the one-pass logits
+            # they may only part where the one-pass top-1 margin is within twice that drift
             part = np.partition(lg[b, a], -2)
-            assert part[-1] - part[-2] < 2 * TOL, (b, a, part[-1] - part[-2])
-    assert full >= B // 2, full                                   # 80 layers of fp16 noise: near ties do flip
+            assert part[-1] - part[-2] <= 2 * drift + 1e-6, (b, a, part[-1] - part[-2], drift)
+    assert full >= B // 2, full                                   # near ties do flip at this depth
+    print("full-depth one-pass vs sequential: rms drift / logit std = %.4f, fully accepted %d/%d" % (worst_rel, full, B))
     # bit reproducibility of the whole step
     acc2, out2, logits2, _ = run(good)
     assert torch.equal(logits, logits2) and np.array_equal(acc, acc2) and np.array_equal(out, out2)
