@@ -55,10 +55,11 @@ __device__ __forceinline__ int lds_slot(int row, int chunk) { return row * LDS_R
 // columns; it stores silu(gate) * up as fp16 [M][F] and nothing else.
 enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1 };
 
-template <int MT, int NTW, int EPI, int NW>
+template <int MT, int NTW, int EPI, int NW, int RD>
 __global__ void __launch_bounds__(NW * 64, 2) gemm_w16_kernel(const f16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                            void* __restrict__ out_, const float* __restrict__ bias,
-                                                           int M, int N, int K, int k_per_split) {
+                                                           int M, int N, int K, int k_per_split, int m_chunks, int gx,
+                                                           int n_split) {
   // two activation-tile buffers as separate objects: the compiler then knows that a DMA into one
   // does not touch the reads of the other
   __shared__ __attribute__((aligned(1024))) f16_t s_a0[16 * MT * LDS_ROW];
@@ -69,13 +70,26 @@ __global__ void __launch_bounds__(NW * 64, 2) gemm_w16_kernel(const f16_t* __res
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
-  const int w4 = wave & 3;                                      // wave inside its 128-column block
+  constexpr int WPB = 8 / NTW;                                  // waves per 128-column block
+  const int w4 = wave % WPB;                                    // wave inside its 128-column block
   const int nblk_all = (N + NWG - 1) / NWG;
-  const int nblk = blockIdx.x * (NW / 4) + (wave >> 2);         // this wave's column block
+  // Grid.  One row chunk: (column blocks, splits, 1).  More rows than one chunk holds (M > 144): a 1-D
+  // grid in which the row chunks of one (column block, split) pair get consecutive slots on the SAME
+  // XCD (workgroup ids are dealt round-robin over the 8 XCDs), so the chunks run together and the
+  // weight block comes from HBM once and from that XCD's L2 for the other chunks.
+  int bx = blockIdx.x, split = blockIdx.y, bz = 0;
+  if (m_chunks > 1) {
+    const int id = blockIdx.x, xcd = id & 7, slot = id >> 3;
+    const int pair = (slot / m_chunks) * 8 + xcd;
+    if (pair >= gx * n_split) return;  // (whole workgroup)
+    bz = slot % m_chunks;
+    bx = pair % gx;
+    split = pair / gx;
+  }
+  const int nblk = bx * (NW / WPB) + wave / WPB;                // this wave's column block
   const int nblk_rd = min(nblk, nblk_all - 1);                  // past the end: re-read the last block, store nothing
   const int n_wg = nblk * NWG;
-  const int split = blockIdx.y;
-  const int m0 = blockIdx.z * (16 * MT);
+  const int m0 = bz * (16 * MT);
   const int k_begin = split * k_per_split;
   const int k_end = min(K, k_begin + k_per_split);
   const int n_iter = (k_end - k_begin) / KB;
@@ -124,7 +138,9 @@ __global__ void __launch_bounds__(NW * 64, 2) gemm_w16_kernel(const f16_t* __res
     for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
   if (n_iter > 0) {  // (uniform per workgroup)
-    u32x4 ring0[NTW][KS], ring1[NTW][KS];  // raw bf16 fragments of the next two iterations
+    // raw bf16 fragments of the next RD iterations (RD = 2: two slots, used alternately; RD = 1: the
+    // wide-column variant for many rows, where the registers go to accumulators instead)
+    u32x4 ring0[NTW][KS], ring1[RD == 2 ? NTW : 1][RD == 2 ? KS : 1];
     MN_DMA_A(s_a0, 0)
     asm volatile("" ::: "memory");
 #pragma unroll
@@ -132,7 +148,7 @@ __global__ void __launch_bounds__(NW * 64, 2) gemm_w16_kernel(const f16_t* __res
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         ring0[nt][ks] = *MN_W_PTR(0, nt, ks);
-        ring1[nt][ks] = *MN_W_PTR(1, nt, ks);
+        if constexpr (RD == 2) ring1[nt][ks] = *MN_W_PTR(1, nt, ks);
       }
     // everything lands before the loop (the two ring slots arrive together with the tile anyway): the
     // compiler sizes its in-loop waits by the worst path into the loop, and this path is then empty
@@ -161,7 +177,7 @@ __global__ void __launch_bounds__(NW * 64, 2) gemm_w16_kernel(const f16_t* __res
       f16x8 wcur_[NTW];                                                                                     \
       _Pragma("unroll") for (int nt = 0; nt < NTW; ++nt) {                                                  \
         wcur_[nt] = bf16x8_to_f16x8(RING[nt][ks]);                                                          \
-        RING[nt][ks] = *MN_W_PTR(it_ + 2, nt, ks);                                                          \
+        RING[nt][ks] = *MN_W_PTR(it_ + RD, nt, ks);                                                         \
       }                                                                                                     \
       _Pragma("unroll") for (int grp = 0; grp < 2; ++grp) {                                                 \
         constexpr int G0 = (MT + 1) / 2;                                                                    \
@@ -177,7 +193,7 @@ __global__ void __launch_bounds__(NW * 64, 2) gemm_w16_kernel(const f16_t* __res
         if (MN_SCHED_MODE == 0 || (MN_SCHED_MODE == 1 && grp == 1)) __builtin_amdgcn_sched_barrier(0);      \
       }                                                                                                     \
     }                                                                                                       \
-    MN_WAIT_VM(8);                                                                                          \
+    MN_WAIT_VM(NTW * KS);                                                                                   \
     __builtin_amdgcn_s_barrier();                                                                           \
   }
 
@@ -186,7 +202,8 @@ __global__ void __launch_bounds__(NW * 64, 2) gemm_w16_kernel(const f16_t* __res
     int it = 0;
     for (; it + 1 < n_iter; it += 2) {
       MN_GEMM_ITER(ring0, s_a0, s_a1, it)
-      MN_GEMM_ITER(ring1, s_a1, s_a0, it + 1)
+      if constexpr (RD == 2) MN_GEMM_ITER(ring1, s_a1, s_a0, it + 1)
+      else MN_GEMM_ITER(ring0, s_a1, s_a0, it + 1)
     }
     if (it < n_iter) MN_GEMM_ITER(ring0, s_a0, s_a1, it)
 #undef MN_GEMM_ITER
@@ -197,19 +214,22 @@ __global__ void __launch_bounds__(NW * 64, 2) gemm_w16_kernel(const f16_t* __res
 
   // epilogue: lane holds D[n = base + 4g + i][m = mt*16 + l16]
   if constexpr (EPI == EPI_SWIGLU) {
-    static_assert(NTW == 2, "gate and up tiles of one wave");
+    static_assert(NTW % 2 == 0, "gate and up tiles alternate inside a wave");
     f16_t* act = reinterpret_cast<f16_t*>(out_);
     const int F = N >> 1;
-    const int f = nblk * 64 + w4 * 16 + g * 4;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int m = m0 + mt * 16 + l16;
-      if (m >= M || f >= F) continue;
-      const f32x4 gt = acc[0][mt], up = acc[1][mt];
-      float r[4];
+    for (int pr = 0; pr < NTW / 2; ++pr) {
+      const int f = nblk * 64 + (w4 * (NTW / 2) + pr) * 16 + g * 4;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) r[i] = gt[i] / (1.f + __expf(-gt[i])) * up[i];
-      *reinterpret_cast<uint2*>(act + (size_t)m * F + f) = make_uint2(pack2h(r[0], r[1]), pack2h(r[2], r[3]));
+      for (int mt = 0; mt < MT; ++mt) {
+        const int m = m0 + mt * 16 + l16;
+        if (m >= M || f >= F) continue;
+        const f32x4 gt = acc[2 * pr][mt], up = acc[2 * pr + 1][mt];
+        float r[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = gt[i] / (1.f + __expf(-gt[i])) * up[i];
+        *reinterpret_cast<uint2*>(act + (size_t)m * F + f) = make_uint2(pack2h(r[0], r[1]), pack2h(r[2], r[3]));
+      }
     }
   } else {
     float* o = reinterpret_cast<float*>(out_) + (size_t)split * M * N;
@@ -367,18 +387,21 @@ int gemm_pick_split(int M, int N, int K, int dtype) {
   return (iters + per - 1) / per;
 }
 
-template <int MT, int NW>
+template <int MT, int NW, int NTW = 2, int RD = 2>
 static void launch_bf16_mt(const GemmArgs& a, int m_chunks, hipStream_t st) {
   const int iters = a.K / KB;
   const int per = (iters + a.split_k - 1) / a.split_k;  // iterations per split
   const int nblk = (a.N + NWG - 1) / NWG;
-  dim3 grid((nblk + NW / 4 - 1) / (NW / 4), a.split_k, m_chunks);
+  constexpr int BPW = NW * NTW / 8;                     // 128-column blocks per workgroup
+  const int gx = (nblk + BPW - 1) / BPW;
+  dim3 grid(gx, a.split_k, 1);
+  if (m_chunks > 1) grid = dim3(((gx * a.split_k + 7) / 8) * 8 * m_chunks, 1, 1);
   const f16_t* A = reinterpret_cast<const f16_t*>(a.a);
   const bf16_t* W = reinterpret_cast<const bf16_t*>(a.w);
   if (a.swiglu_act)
-    gemm_w16_kernel<MT, 2, EPI_SWIGLU, NW><<<grid, NW * 64, 0, st>>>(A, W, a.swiglu_act, nullptr, a.M, a.N, a.K, per * KB);
+    gemm_w16_kernel<MT, NTW, EPI_SWIGLU, NW, RD><<<grid, NW * 64, 0, st>>>(A, W, a.swiglu_act, nullptr, a.M, a.N, a.K, per * KB, m_chunks, gx, a.split_k);
   else
-    gemm_w16_kernel<MT, 2, EPI_PARTIAL, NW><<<grid, NW * 64, 0, st>>>(A, W, a.out, a.bias, a.M, a.N, a.K, per * KB);
+    gemm_w16_kernel<MT, NTW, EPI_PARTIAL, NW, RD><<<grid, NW * 64, 0, st>>>(A, W, a.out, a.bias, a.M, a.N, a.K, per * KB, m_chunks, gx, a.split_k);
 }
 
 void launch_gemm(const GemmArgs& a, hipStream_t st) {
@@ -397,7 +420,7 @@ void launch_gemm(const GemmArgs& a, hipStream_t st) {
   else if (tiles <= 4) launch_bf16_mt<4, 4>(a, 1, st);
   else if (tiles <= 6) launch_bf16_mt<6, 4>(a, 1, st);
   else if (tiles <= 9) { if (gemm_wide(a.N, a.K)) launch_bf16_mt<9, 8>(a, 1, st); else launch_bf16_mt<9, 4>(a, 1, st); }
-  else launch_bf16_mt<8, 4>(a, (tiles + 7) / 8, st);
+  else launch_bf16_mt<6, 4, 4, 1>(a, (tiles + 5) / 6, st);  // many rows: 64 columns per wave, 96-row chunks
 }
 
 }  // namespace mn
