@@ -5,11 +5,11 @@
 // Two kernels:
 //  * attn_mfma_kernel  bf16 pages / fp16 queries, head_dim 128, 16-token blocks.  The G*q_b query rows that share one
 //    KV head (grouped-query attention stacks the group's heads on top of the speculated tokens)
-//    are the column index of every MFMA, so each K/V byte is read once per KV head.  K and V
-//    fragments go HBM -> registers (bf16 widened exactly to fp16) -> MFMA directly: the page layouts put 8 consecutive
-//    contraction elements in 16 bytes for both products (head-dim chunks for K, tokens for V).
-//    The KV range of a sequence is split across workgroups; partial (max, sum, output) triples
-//    are merged by attn_merge_kernel.
+//    are the column index of every MFMA, so each K/V byte is read once per KV head.  Key tiles go
+//    HBM -> LDS by direct loads, are widened in place (bf16 to fp16, exact) and feed the MFMAs of all
+//    four waves: the page layouts put 8 consecutive contraction elements in 16 bytes for both
+//    products (head-dim chunks for K, tokens for V).  The KV range of a sequence is split across
+//    workgroups; partial (max, sum, output) triples are merged by attn_merge_kernel.
 //  * attn_generic_kernel  any storage type / head_dim / block size; plain FMA, one (row, head)
 //    per workgroup.  Used by the fp32 model and as the fallback.
 #include "launch.h"
@@ -121,40 +121,109 @@ __global__ void __launch_bounds__(GEN_THREADS) attn_generic_kernel(AttnArgs a) {
 // MFMA kernel (bf16 pages, fp16 queries, head_dim 128, block 16)
 // ------------------------------------------------------------------------------------------
 // Workgroup (4 waves) = one (KV split, KV head, sequence).  The R = G*q_b query rows that share the
-// KV head are cut into 16-row column tiles; wave w owns tiles w, w+4, (w+8).  Key tiles of 32 keys
-// (two blocks) travel HBM -> registers (raw bf16, a ring of PF tiles in flight per workgroup) ->
-// widened once to fp16 -> LDS in MFMA fragment order -> every wave's MFMAs, so each K/V byte is
-// loaded and converted once per KV head.  Q sits in LDS for the whole kernel.
+// KV head are cut into 16-row column tiles; wave w owns tiles w, w+4, (w+8) and keeps their query
+// fragments (pre-multiplied by log2(e)/sqrt(hd)) in registers.
 //
 // Both products have the query row as the MFMA column index (S^T = K Q^T, O^T = V^T P^T): softmax
 // statistics are per-lane scalars.  Inside a tile the K rows are permuted (S^T row 4g'+r of half t
 // is key 8g' + 4t + r) so that the lane group g of the first product's output holds keys
 // 8g..8g+7, exactly the operand order of the second product and 16 contiguous bytes of a V page.
+//
+// Data path of a key tile (32 keys = two blocks, 16 KB): HBM -> LDS by direct loads (no staging
+// registers) into one of NS slots, already in MFMA fragment order (a wave load drops lane i's 16 bytes
+// at slot base + 16 i, so lane i asks for the piece that belongs there); the wave that brought a
+// fragment in widens it in place from bf16 to fp16 (both are two bytes); after a barrier every wave's
+// MFMAs read it.  Three tiles are in flight or landed ahead of the one being multiplied, and the loads
+// of tile i+3 are issued before the wait for tile i+1, so the memory queue never runs dry while the
+// waves wait for one another.
+//
+// The kernel is bound by instruction issue and LDS latency, not by HBM, at 128 query rows per KV head,
+// hence: tiles that lie wholly inside the cached context take a branch-free body (no mask, no
+// patching); the accumulators of the first product start at minus the running reference, so the
+// scores come out already shifted; the reference moves lazily; the row sums are one more MFMA with
+// an all-ones operand (they add exactly the fp16 probabilities the second product uses, and need no
+// cross-lane reduction); the K fragments of the next tile and the V fragments of this one are read
+// into registers early, and the phases are ordered so that every batch of MFMAs has independent
+// vector work beside it (widening beside the first product of column tile 0, the softmax of tile
+// ct beside the products of its neighbour).
 constexpr int HD = 128;
 constexpr int BS = 16;
 constexpr int KT = 32;                         // keys per tile (two blocks)
-constexpr int TILE_BYTES = 2 * KT * HD * 2;    // K + V of one tile in fp16: 16 KB
-constexpr int PF = 2;                          // key tiles in flight in registers per workgroup
+constexpr int TILE_HALFS = 2 * KT * HD;        // fp16 elements of K + V of one tile
+constexpr int TILE_BYTES = TILE_HALFS * 2;     // 16 KB
+constexpr int NS = 4;                          // tile slots in LDS
 constexpr int MAX_CT = 3;                      // column tiles per wave at most (R <= 192)
 constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LAZY_MAX = 6.f;                // the reference moves when a score exceeds it by 2^6
 
-// Q in LDS: 256-byte rows with the sixteen 16-byte chunks of row r rotated by 2r (bank pattern of a
-// 288-byte stride: conflict-free for 16 rows x one chunk per quarter wave).
-__device__ __forceinline__ int q_slot(int row, int chunk) { return row * HD + (((chunk + 2 * row) & 15) << 3); }
+__device__ __forceinline__ float max3(float x, float y, float z) { return __builtin_fmaxf(__builtin_fmaxf(x, y), z); }
 
-struct TileAddr {  // what a thread needs to fetch its four 16-byte pieces of a key tile
-  const bf16_t* k[2];
-  const bf16_t* v[2];
-};
+// 64 lanes x 16 bytes, global (g + OFFSET) -> LDS at lds_base + 16 * lane.  The instruction adds its
+// immediate offset to BOTH addresses, so the LDS base handed to it is lowered by the same amount.  The load
+// is invisible to the compiler's wait-count bookkeeping: the kernel waits for these loads itself
+// (att_wait_vm) and issues no other memory load while one of them may still be needed.
+template <int OFFSET>
+__device__ __forceinline__ void dma16(const char* g, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off offset:%2" ::"v"(g), "s"(lds_base - (uint32_t)OFFSET), "n"(OFFSET) : "memory");
+}
+// wait until at most N of this wave's memory loads are outstanding (they complete in order)
+template <int N>
+__device__ __forceinline__ void att_wait_vm() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(((N & 15) | ((N >> 4) << 14)) | (7 << 4) | (15 << 8));
+  asm volatile("" ::: "memory");
+}
+
+// Online-softmax step of one column tile on one key tile.  S0/S1: scores of keys 8g+0..3 / 8g+4..7 of
+// this lane's query row, already minus the reference (negm4 = -reference in all four elements, 0 while
+// nothing was seen).  Returns the probabilities as the B operand of the second product.
+template <bool MASK>
+__device__ __forceinline__ f16x8 softmax_tile(const f32x4& S0, const f32x4& S1, float& run_m, f32x4& negm4, float& thr,
+                                              f32x4 (&O)[8], f32x4& L, int keyg, int lim) {
+  float sc[8] = {S0[0], S0[1], S0[2], S0[3], S1[0], S1[1], S1[2], S1[3]};
+  if (MASK) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (keyg + e > lim) sc[e] = -INFINITY;
+  }
+  float tm = max3(max3(sc[0], sc[1], sc[2]), max3(sc[3], sc[4], sc[5]), __builtin_fmaxf(sc[6], sc[7]));
+  // thr is -inf until the row has seen a key, LAZY_MAX afterwards: probabilities up to 2^6 are fine
+  // in fp16 and in the fp32 accumulators, so the common tile needs no exchange and no rescale
+  if (__any(tm > thr)) {
+    tm = __builtin_fmaxf(tm, __shfl_xor(tm, 16, 64));
+    tm = __builtin_fmaxf(tm, __shfl_xor(tm, 32, 64));
+    const bool fresh = run_m == -INFINITY;
+    float d = fresh ? tm : __builtin_fmaxf(tm, 0.f);  // how far the reference moves (shifted units)
+    if (d == -INFINITY) d = 0.f;                      // still nothing visible
+    const float alpha = fresh ? 1.f : __builtin_amdgcn_exp2f(-d);
+    if (!(fresh && tm == -INFINITY)) run_m = d - negm4[0];
+    const float nm = (run_m == -INFINITY) ? 0.f : -run_m;
+    negm4 = (f32x4){nm, nm, nm, nm};
+    thr = (run_m == -INFINITY) ? -INFINITY : LAZY_MAX;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sc[e] -= d;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      O[u][0] *= alpha; O[u][1] *= alpha; O[u][2] *= alpha; O[u][3] *= alpha;
+    }
+    L[0] *= alpha; L[1] *= alpha; L[2] *= alpha; L[3] *= alpha;
+  }
+  union { f16x8 v; uint32_t u[4]; } pf;
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+    pf.u[e] = pack2h(__builtin_amdgcn_exp2f(sc[2 * e]), __builtin_amdgcn_exp2f(sc[2 * e + 1]));
+  return pf.v;
+}
+
+template <int N> struct IntC { static constexpr int value = N; };
 
 // Partials: o_part [split][M][H][HD] fp32 (unnormalised), ml_part [split][M][H][2] = (max in log2 units, sum)
 template <int CTW>
-__global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_splits, int nt16_max,
-                                                           float* __restrict__ o_part, float* __restrict__ ml_part) {
+__global__ void __launch_bounds__(256, CTW >= 3 ? 1 : 2) attn_mfma_kernel(AttnArgs a, int n_splits, float* __restrict__ o_part,
+                                                                          float* __restrict__ ml_part) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  f16_t* s_kv = reinterpret_cast<f16_t*>(smem);                       // [2][16 fragments][64 lanes][8]
-  f16_t* s_q = reinterpret_cast<f16_t*>(smem + 2 * TILE_BYTES);       // [nt16_max*16][HD], rotated chunks
-  int32_t* s_bt = reinterpret_cast<int32_t*>(smem + 2 * TILE_BYTES + (size_t)nt16_max * 16 * HD * sizeof(f16_t));
+  f16_t* s_kv = reinterpret_cast<f16_t*>(smem);                          // [NS][16 fragments][64 lanes][8]
+  int32_t* s_bidx = reinterpret_cast<int32_t*>(smem + NS * TILE_BYTES);  // physical block of every block of the split
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
@@ -170,229 +239,234 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_spl
   const int n_tiles = (nkeys + KT - 1) / KT;
   const int t_begin = (int)(((long)n_tiles * split) / n_splits);
   const int t_end = (int)(((long)n_tiles * (split + 1)) / n_splits);
-
-  // ---- Q -> LDS (zero rows past R) ----
-  const float sscale = rsqrtf((float)HD) * LOG2E;
-  const f16_t* Q = reinterpret_cast<const f16_t*>(a.q);
-  for (int c = tid; c < NT16 * 16 * (HD / 8); c += 256) {
-    const int r = c >> 4, ch = c & 15;
-    // Q is scaled by log2(e)/sqrt(hd) once here (one more fp16 rounding of q, 2^-11), so the scores
-    // come out of the first product in log2 units
-    f16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (r < R) {
-      const int j = r / G, gi = r % G;
-      v = *reinterpret_cast<const f16x8*>(Q + ((size_t)(row0 + j) * a.H + kvh * G + gi) * HD + ch * 8);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = (f16_t)((float)v[e] * sscale);
-    }
-    *reinterpret_cast<f16x8*>(&s_q[q_slot(r, ch)]) = v;
-  }
-
-  f32x4 O[CTW][8];
-  float run_m[CTW], run_l[CTW];
-  int lim[CTW];
-  bool mine[CTW];
-#pragma unroll
-  for (int ct = 0; ct < CTW; ++ct) {
-    run_m[ct] = -INFINITY;
-    run_l[ct] = 0.f;
-    const int tile = wave + 4 * ct;
-    mine[ct] = ok && tile < NT16;
-    const int r = tile * 16 + l16;
-    lim[ct] = ctx + min(r / G, qb - 1);  // last visible key of this lane's query row
-#pragma unroll
-    for (int u = 0; u < 8; ++u) O[ct][u] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  }
-
-  const bf16_t* Kp = reinterpret_cast<const bf16_t*>(a.kv.k);
-  const bf16_t* Vp = reinterpret_cast<const bf16_t*>(a.kv.v);
-  const f16_t* Kn = reinterpret_cast<const f16_t*>(a.knew);
-  const f16_t* Vn = reinterpret_cast<const f16_t*>(a.vnew);
-  const int32_t* bt = a.kv.block_tables + (size_t)b * a.kv.max_blocks_per_seq;
-  const size_t head_off = (size_t)kvh * (HD * BS);
-  const size_t blk_stride = (size_t)a.Hkv * (HD * BS);
-  // Loader role of this thread: K pieces (t = 0, 1; head-dim step s = wave) and V pieces (u = wave, wave + 4).
-  // K piece: S^T row l16 = 4g'+r of half t <-> key 8g' + 4t + r of the tile; head-dim chunk 4*wave + g.
-  const int kkey0 = 8 * (l16 >> 2) + (l16 & 3);      // key inside the tile for t = 0 (t = 1: + 4)
-  const int kchunk = 4 * wave + g;
+  const int n_my = max(0, t_end - t_begin);
+  const int nct = ok ? min(CTW, max(0, (NT16 - wave + 3) >> 2)) : 0;  // real column tiles of this wave
 
   // block table of this split -> LDS (the dependent chain table -> address -> load would otherwise
   // cost an L2 round trip per tile); entries past the last mapped block repeat the last one
-  const int n_my = max(0, t_end - t_begin);
+  const int32_t* bt = a.kv.block_tables + (size_t)b * a.kv.max_blocks_per_seq;
   const int last_blk = ok ? (nkeys - 1) / BS : 0;
-  for (int i = tid; i < 2 * n_my; i += 256) s_bt[i] = bt[min(2 * t_begin + i, last_blk)];
-  __syncthreads();
+  for (int i = tid; i < 2 * n_my; i += 256) s_bidx[i] = bt[min(2 * t_begin + i, last_blk)];
 
-  auto tile_addr = [&](int ti) {  // ti: tile index inside the split
-    TileAddr ta;
-    const int pb0 = s_bt[2 * ti], pb1 = s_bt[2 * ti + 1];
+  // ---- Q fragments -> registers, scaled by log2(e)/sqrt(hd) (one more fp16 rounding of q, 2^-11), so
+  // the scores come out of the first product in log2 units.  Rows past R are zero. ----
+  const float sscale = rsqrtf((float)HD) * LOG2E;
+  const f16_t* Q = reinterpret_cast<const f16_t*>(a.q);
+  f16x8 qf[CTW][4];
+  f32x4 O[CTW][8], L[CTW], negm4[CTW];
+  float run_m[CTW], thr[CTW];
+  int lim[CTW];
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int kk = kkey0 + 4 * t;
-      ta.k[t] = Kp + (size_t)(kk < BS ? pb0 : pb1) * blk_stride + head_off + ((size_t)kchunk * BS + (kk & (BS - 1))) * 8;
-    }
+  for (int ct = 0; ct < CTW; ++ct) {
+    run_m[ct] = -INFINITY;
+    thr[ct] = -INFINITY;
+    negm4[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    L[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    const int r = (wave + 4 * ct) * 16 + l16;
+    lim[ct] = ctx + min(r / G, qb - 1);  // last visible key of this lane's query row
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-      ta.v[i] = Vp + (size_t)(g < 2 ? pb0 : pb1) * blk_stride + head_off + (size_t)(16 * (wave + 4 * i) + l16) * BS + 8 * (g & 1);
-    return ta;
-  };
-  // LDS fragment slots this thread fills: K fragment (t*4 + wave), V fragment 8 + wave + 4i
-  auto frag_ptr = [&](int buf, int f, int ln) { return s_kv + (size_t)buf * (TILE_BYTES / 2) + ((size_t)f * 64 + ln) * 8; };
-
-  // ---- one key tile on this wave's column tiles; `tail` tiles apply the causal mask ----
-  auto compute = [&](int buf, int key0, bool tail) {
-    f32x4 S0[CTW], S1[CTW];
-#pragma unroll
-    for (int ct = 0; ct < CTW; ++ct) S0[ct] = S1[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int u = 0; u < 8; ++u) O[ct][u] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      const f16x8 k0 = *reinterpret_cast<const f16x8*>(frag_ptr(buf, s, lane));
-      const f16x8 k1 = *reinterpret_cast<const f16x8*>(frag_ptr(buf, 4 + s, lane));
+      f16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (r < R) {
+        v = *reinterpret_cast<const f16x8*>(Q + ((size_t)(row0 + r / G) * a.H + kvh * G + r % G) * HD + 32 * s + 8 * g);
 #pragma unroll
-      for (int ct = 0; ct < CTW; ++ct) {
-        if (!mine[ct]) continue;
-        const f16x8 qf = *reinterpret_cast<const f16x8*>(&s_q[q_slot((wave + 4 * ct) * 16 + l16, 4 * s + g)]);
-        S0[ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(k0, qf, S0[ct], 0, 0, 0);
-        S1[ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(k1, qf, S1[ct], 0, 0, 0);
+        for (int e = 0; e < 8; ++e) v[e] = (f16_t)((float)v[e] * sscale);
       }
+      qf[ct][s] = v;
     }
-    f16x8 P[CTW];
-#pragma unroll
-    for (int ct = 0; ct < CTW; ++ct) {
-      if (!mine[ct]) continue;
-      // lane holds keys key0 + 8g + e, e = 0..7 (S0 -> e 0..3, S1 -> e 4..7) of query row l16;
-      // the scores are already in log2 units (Q was scaled when it was staged)
-      float sc[8];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        sc[e] = S0[ct][e];
-        sc[4 + e] = S1[ct][e];
-      }
-      if (tail) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-          if (key0 + 8 * g + e > lim[ct]) sc[e] = -INFINITY;
-      }
-      float tm = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
-      // Lazy maximum: the reference only moves (a cross-lane exchange and a rescale of the accumulator)
-      // when some row's scores exceed it by more than 2^6; until then probabilities up to 64 are fine
-      // in fp16 and in the fp32 sums.
-      if (__any(tm > run_m[ct] + 6.f)) {
-        tm = fmaxf(tm, __shfl_xor(tm, 16, 64));
-        tm = fmaxf(tm, __shfl_xor(tm, 32, 64));
-        const float new_m = fmaxf(run_m[ct], tm);
-        const float m_safe = (new_m == -INFINITY) ? 0.f : new_m;
-        const float alpha = __builtin_amdgcn_exp2f(run_m[ct] - m_safe);
-        run_m[ct] = new_m;
-        run_l[ct] *= alpha;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          O[ct][u][0] *= alpha; O[ct][u][1] *= alpha; O[ct][u][2] *= alpha; O[ct][u][3] *= alpha;
-        }
-      }
-      const float m_ref = (run_m[ct] == -INFINITY) ? 0.f : run_m[ct];
-      float ps = 0.f;
-      float p[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        p[e] = __builtin_amdgcn_exp2f(sc[e] - m_ref);
-        ps += p[e];
-      }
-      run_l[ct] += ps;  // per-lane partial sum; lane groups are added at the end
-      union { f16x8 v; uint32_t u[4]; } pf;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) pf.u[e] = pack2h(p[2 * e], p[2 * e + 1]);
-      P[ct] = pf.v;
-    }
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const f16x8 vf = *reinterpret_cast<const f16x8*>(frag_ptr(buf, 8 + u, lane));
-#pragma unroll
-      for (int ct = 0; ct < CTW; ++ct) {
-        if (!mine[ct]) continue;
-        O[ct][u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf, P[ct], O[ct][u], 0, 0, 0);
-      }
-    }
-  };
+  }
 
-  // ---- loop over this split's key tiles; the raw pages of the next PF tiles are in flight in registers ----
+  const f16_t* Kn = reinterpret_cast<const f16_t*>(a.knew);
+  const f16_t* Vn = reinterpret_cast<const f16_t*>(a.vnew);
+  // Loader role of this thread: the pieces of its own lane in K fragments (t = 0, 1; head-dim step s = wave)
+  // and V fragments (u = wave, wave + 4).  K: S^T row l16 = 4g'+r of half t <-> key 8g' + 4t + r of the
+  // tile, head-dim chunk 4*wave + g (t = 1: +64 bytes).  V: head-dim row 16u + l16, keys 8g..8g+7
+  // (u + 4: +2048 bytes).
+  const int kkey0 = 8 * (l16 >> 2) + (l16 & 3);  // key inside the tile for t = 0 (t = 1: + 4)
+  const int kchunk = 4 * wave + g;
+  const int ksel = l16 >> 3, vsel = g >> 1;      // which of the tile's two blocks the pieces live in
+  const uint32_t blk_bytes = (uint32_t)a.Hkv * (HD * BS) * (uint32_t)sizeof(bf16_t);
+  const uint32_t blk_last = (uint32_t)max(a.kv.num_blocks - 1, 0);
+  const size_t head_bytes = (size_t)kvh * (HD * BS) * sizeof(bf16_t);
+  const char* kbase = reinterpret_cast<const char*>(a.kv.k) + head_bytes + ((size_t)kchunk * BS + (kkey0 & (BS - 1))) * 8 * sizeof(bf16_t);
+  const char* vbase = reinterpret_cast<const char*>(a.kv.v) + head_bytes + ((size_t)(16 * wave + l16) * BS + 8 * (g & 1)) * sizeof(bf16_t);
+  // LDS byte address of fragment `wave` of slot 0 (wave-uniform)
+  const uint32_t lds_w = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem + (uint32_t)wave * 1024u);
+  f16_t* const my_piece = s_kv + (wave * 64 + lane) * 8;  // this thread's piece of fragment `wave` in slot 0
+  __syncthreads();  // block indices are in LDS; every load issued so far has been consumed
+
   if (ok && n_my > 0) {
     const int ti_last = n_my - 1;
-    u32x4 ring[PF][4];  // raw bf16 pieces of the next PF tiles
-#define MN_ATT_LOAD(SLOT, TI)                                                                    \
-  {                                                                                              \
-    const TileAddr ta_ = tile_addr(min((TI), ti_last));                                          \
-    ring[SLOT][0] = *reinterpret_cast<const u32x4*>(ta_.k[0]);                                   \
-    ring[SLOT][1] = *reinterpret_cast<const u32x4*>(ta_.k[1]);                                   \
-    ring[SLOT][2] = *reinterpret_cast<const u32x4*>(ta_.v[0]);                                   \
-    ring[SLOT][3] = *reinterpret_cast<const u32x4*>(ta_.v[1]);                                   \
+    // all loads of tile TI of the split -> slot SLOT (tiles past the end repeat the last one)
+#define MN_ATT_DMA(TI, SLOT)                                                                      \
+  {                                                                                               \
+    const int t_ = min((TI), ti_last);                                                            \
+    /* (the clamp costs two instructions and keeps a damaged table from becoming a wild address) */ \
+    const char* kp_ = kbase + (uint64_t)min((uint32_t)s_bidx[2 * t_ + ksel], blk_last) * blk_bytes; \
+    const char* vp_ = vbase + (uint64_t)min((uint32_t)s_bidx[2 * t_ + vsel], blk_last) * blk_bytes; \
+    const uint32_t l_ = __builtin_amdgcn_readfirstlane(lds_w + (uint32_t)(SLOT) * TILE_BYTES);    \
+    dma16<0>(kp_, l_);                                                                            \
+    dma16<4 * 8 * 2>(kp_, l_ + 4 * 1024);                                                         \
+    dma16<0>(vp_, l_ + 8 * 1024);                                                                 \
+    dma16<64 * BS * 2>(vp_, l_ + 12 * 1024);                                                      \
   }
-    // widen the four pieces of ring slot SLOT and put them into LDS buffer BUF as tile TI of the split;
-    // tiles that reach past ctx take this step's own keys from the fp16 side buffers and zero the slots
-    // past the sequence end (stale slots may hold anything: 0 * garbage must stay 0)
-    auto fill = [&](const u32x4 (&r)[4], int buf, int ti) {
-      const int key0 = (t_begin + ti) * KT;
-      f16x8 kf[2] = {bf16x8_to_f16x8(r[0]), bf16x8_to_f16x8(r[1])};
-      f16x8 vf[2] = {bf16x8_to_f16x8(r[2]), bf16x8_to_f16x8(r[3])};
-      if (key0 + KT > ctx) {
+    // this thread's four raw pieces of slot SLOT, widened; SLOW: the tile may reach past ctx, then this
+    // step's own keys come from the fp16 side buffers and V slots past the sequence end are zeroed (stale
+    // slots may hold anything: 0 * garbage must stay 0; garbage scores are masked)
+    auto widen = [&](const u32x4 (&raw)[4], f16x8 (&w)[4], bool slow, int ti) {
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const int key = key0 + kkey0 + 4 * t;
-          if (Kn && key >= ctx && key < nkeys)
-            kf[t] = *reinterpret_cast<const f16x8*>(Kn + ((size_t)(row0 + key - ctx) * a.Hkv + kvh) * HD + kchunk * 8);
-        }
+      for (int i = 0; i < 4; ++i) w[i] = bf16x8_to_f16x8(raw[i]);
+      if (slow) {
+        const int key0 = (t_begin + ti) * KT;
+        if (key0 + KT > ctx) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          const int hd = 16 * (wave + 4 * i) + l16;
+          for (int t = 0; t < 2; ++t) {
+            const int key = key0 + kkey0 + 4 * t;
+            if (Kn && key >= ctx && key < nkeys)
+              w[t] = *reinterpret_cast<const f16x8*>(Kn + ((size_t)(row0 + key - ctx) * a.Hkv + kvh) * HD + kchunk * 8);
+          }
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const int key = key0 + 8 * g + e;
-            if (key >= nkeys) vf[i][e] = (f16_t)0.f;
-            else if (Vn && key >= ctx) vf[i][e] = Vn[((size_t)(row0 + key - ctx) * a.Hkv + kvh) * HD + hd];
+          for (int i = 0; i < 2; ++i) {
+            const int hd = 16 * (wave + 4 * i) + l16;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              const int key = key0 + 8 * g + e;
+              if (key >= nkeys) w[2 + i][e] = (f16_t)0.f;
+              else if (Vn && key >= ctx) w[2 + i][e] = Vn[((size_t)(row0 + key - ctx) * a.Hkv + kvh) * HD + hd];
+            }
           }
         }
       }
-      *reinterpret_cast<f16x8*>(frag_ptr(buf, wave, lane)) = kf[0];
-      *reinterpret_cast<f16x8*>(frag_ptr(buf, 4 + wave, lane)) = kf[1];
-      *reinterpret_cast<f16x8*>(frag_ptr(buf, 8 + wave, lane)) = vf[0];
-      *reinterpret_cast<f16x8*>(frag_ptr(buf, 12 + wave, lane)) = vf[1];
     };
-    // prologue: tile 0 -> LDS buffer 0, tiles 1 and 2 in flight
-    MN_ATT_LOAD(0, 0)
-    MN_ATT_LOAD(1, 1)
-    fill(ring[0], 0, 0);
-    MN_ATT_LOAD(0, 2)
-    __syncthreads();
-// iteration i: LDS[i&1] holds tile i; ring slot SLOT holds tile i+1 (in flight or landed), the other
-// slot tile i+2.  Fill the other LDS buffer with tile i+1, refill the slot with tile i+3, compute tile i.
-#define MN_ATT_ITER(SLOT, I)                                                                     \
-  {                                                                                              \
-    const int i_ = (I);                                                                          \
-    fill(ring[SLOT], (i_ + 1) & 1, min(i_ + 1, ti_last));                                        \
-    MN_ATT_LOAD(SLOT, i_ + 3)                                                                    \
-    asm volatile("" ::: "memory");                                                               \
-    compute(i_ & 1, (t_begin + i_) * KT, (t_begin + i_) * KT + KT > ctx);                        \
-    __syncthreads();                                                                             \
-  }
-    int i = 0;
-    for (; i + 1 < n_my; i += 2) {
-      MN_ATT_ITER(1, i)
-      MN_ATT_ITER(0, i + 1)
+    f16x8 kf[8];  // K fragments of the tile about to be multiplied
+    // prologue: tiles 0, 1, 2 on their way; tile 0 widened and its K fragments in registers
+    MN_ATT_DMA(0, 0)
+    MN_ATT_DMA(1, 1)
+    MN_ATT_DMA(2, 2)
+    att_wait_vm<8>();
+    {
+      u32x4 raw[4];
+      f16x8 w[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) raw[i] = *reinterpret_cast<const u32x4*>(my_piece + i * 4 * 512);
+      widen(raw, w, true, 0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) *reinterpret_cast<f16x8*>(my_piece + i * 4 * 512) = w[i];
     }
-    if (i < n_my) MN_ATT_ITER(1, i)
-#undef MN_ATT_ITER
-#undef MN_ATT_LOAD
+    __syncthreads();
+#pragma unroll
+    for (int f = 0; f < 8; ++f) kf[f] = *reinterpret_cast<const f16x8*>(s_kv + (f * 64 + lane) * 8);
+
+    // Iteration i: slot i%NS holds tile i widened (its K fragments already in kf); tile i+1 landed or
+    // landing in slot (i+1)%NS, tile i+2 in flight; slot (i+3)%NS is free since the last barrier.
+    const f16x8 ones = {1, 1, 1, 1, 1, 1, 1, 1};
+    auto iter = [&](auto nct_c, auto slow_c, int i) {
+      constexpr int NCT = decltype(nct_c)::value;
+      constexpr bool SLOW = decltype(slow_c)::value != 0;
+      constexpr int NC = NCT > 0 ? NCT : 1;
+      const int cur = i & (NS - 1), nxt = (i + 1) & (NS - 1);
+      MN_ATT_DMA(i + 3, (i + 3) & (NS - 1))
+      f16x8 vf[8];
+      if (NCT > 0) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) vf[u] = *reinterpret_cast<const f16x8*>(s_kv + cur * TILE_HALFS + ((8 + u) * 64 + lane) * 8);
+      }
+      f16_t* const np = my_piece + nxt * TILE_HALFS;
+      att_wait_vm<8>();  // tile i+1 has landed (tiles i+2 and i+3 may be in flight)
+      u32x4 raw[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) raw[j] = *reinterpret_cast<const u32x4*>(np + j * 4 * 512);
+      __builtin_amdgcn_sched_barrier(0);
+      // first product of column tile 0 beside the widening of tile i+1
+      f32x4 S0[NC], S1[NC];
+      f16x8 P[NC];
+      const int keyg = (t_begin + i) * KT + 8 * g;
+      if (NCT > 0) {
+        S0[0] = negm4[0];
+        S1[0] = negm4[0];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          S0[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[s], qf[0][s], S0[0], 0, 0, 0);
+          S1[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[4 + s], qf[0][s], S1[0], 0, 0, 0);
+        }
+      }
+      {
+        f16x8 w[4];
+        widen(raw, w, SLOW, min(i + 1, ti_last));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) *reinterpret_cast<f16x8*>(np + j * 4 * 512) = w[j];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      // first product of column tile ct beside the softmax of tile ct-1
+#pragma unroll
+      for (int ct = 1; ct < NCT; ++ct) {
+        S0[ct] = negm4[ct];
+        S1[ct] = negm4[ct];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          S0[ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[s], qf[ct][s], S0[ct], 0, 0, 0);
+          S1[ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[4 + s], qf[ct][s], S1[ct], 0, 0, 0);
+        }
+        P[ct - 1] = softmax_tile<SLOW>(S0[ct - 1], S1[ct - 1], run_m[ct - 1], negm4[ct - 1], thr[ct - 1], O[ct - 1], L[ct - 1], keyg, lim[ct - 1]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // every LDS read of tile i has been issued and tile i+1 is widened: hand over
+      __syncthreads();
+#pragma unroll
+      for (int f = 0; f < 8; ++f) kf[f] = *reinterpret_cast<const f16x8*>(s_kv + nxt * TILE_HALFS + (f * 64 + lane) * 8);
+      __builtin_amdgcn_sched_barrier(0);
+      // second product of tiles 0..NCT-2 beside the softmax of the last tile, then the last second product
+      if (NCT > 0) {
+#pragma unroll
+        for (int ct = 0; ct + 1 < NCT; ++ct) {
+#pragma unroll
+          for (int u = 0; u < 8; ++u) O[ct][u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[u], P[ct], O[ct][u], 0, 0, 0);
+          L[ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones, P[ct], L[ct], 0, 0, 0);
+        }
+        P[NCT - 1] = softmax_tile<SLOW>(S0[NCT - 1], S1[NCT - 1], run_m[NCT - 1], negm4[NCT - 1], thr[NCT - 1], O[NCT - 1], L[NCT - 1], keyg, lim[NCT - 1]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) O[NCT - 1][u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[u], P[NCT - 1], O[NCT - 1][u], 0, 0, 0);
+        L[NCT - 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones, P[NCT - 1], L[NCT - 1], 0, 0, 0);
+      }
+    };
+    // fast iterations: tiles i and i+1 lie wholly below ctx
+    const int n_clean = min(n_my, max(0, ctx / KT - t_begin));
+    const int n_fast = max(0, n_clean - 1);
+    int i = 0;
+    if (nct == CTW) {
+      for (; i < n_fast; ++i) iter(IntC<CTW>{}, IntC<0>{}, i);
+      for (; i < n_my; ++i) iter(IntC<CTW>{}, IntC<1>{}, i);
+    } else if (nct == 0) {
+      for (; i < n_my; ++i) iter(IntC<0>{}, IntC<1>{}, i);
+    } else {
+      if constexpr (CTW > 1) {
+        if (nct == 1) {
+          for (; i < n_fast; ++i) iter(IntC<1>{}, IntC<0>{}, i);
+          for (; i < n_my; ++i) iter(IntC<1>{}, IntC<1>{}, i);
+        }
+      }
+      if constexpr (CTW > 2) {
+        if (nct == 2) {
+          for (; i < n_fast; ++i) iter(IntC<2>{}, IntC<0>{}, i);
+          for (; i < n_my; ++i) iter(IntC<2>{}, IntC<1>{}, i);
+        }
+      }
+    }
+    att_wait_vm<0>();  // the loads of the tiles past the end must land before the LDS is given back
+#undef MN_ATT_DMA
   }
 
-  // ---- output: lane holds O^T[hd = 16u + 4g + i][row = tile*16 + l16] ----
+  // ---- output: lane holds O^T[hd = 16u + 4g + i][row = tile*16 + l16]; every lane has its row's sum ----
 #pragma unroll
   for (int ct = 0; ct < CTW; ++ct) {
     const int tile = wave + 4 * ct;
     const int r = tile * 16 + l16;
     if (tile >= NT16 || r >= R) continue;
-    float l = run_l[ct];
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
+    const float l = L[ct][0];
     const int j = r / G, gi = r % G;
     const int m = row0 + j, h = kvh * G + gi;
     if (n_splits == 1) {
@@ -458,7 +532,10 @@ static int pick_splits(int B, int Hkv, int max_ctx) {
   }();
   const int tiles = (max_ctx + KT - 1) / KT;
   int s = forced > 0 ? forced : (attn_target_wgs() + B * Hkv - 1) / (B * Hkv);
-  const int cap = (tiles + 7) / 8;  // at least eight key tiles per split
+  // at least sixteen key tiles per split (measured: below that the prologue of a workgroup, three tiles
+  // of lead-in and the query fragments, and the larger partial sums cost more than the extra
+  // workgroups hide)
+  const int cap = tiles / 16;
   if (s > cap) s = cap;
   if (s > 16) s = 16;
   if (s < 1) s = 1;
@@ -473,8 +550,8 @@ bool attention_mfma_supported(int H, int Hkv, int hd, int block_size, int dtype)
   return !off && dtype == MN_DT_BF16 && hd == HD && block_size == BS && Hkv > 0 && H % Hkv == 0;
 }
 
-static size_t mfma_smem_bytes(int nt16_max, int tiles_per_split) {
-  return (size_t)2 * TILE_BYTES + (size_t)nt16_max * 16 * HD * sizeof(f16_t) + (size_t)(2 * tiles_per_split + 2) * sizeof(int32_t);
+static size_t mfma_smem_bytes(int tiles_per_split) {
+  return (size_t)NS * TILE_BYTES + (size_t)(2 * tiles_per_split + 2) * sizeof(int32_t);
 }
 
 size_t attention_scratch_bytes(int M, int H, int hd, int max_ctx, int dtype) {
@@ -495,7 +572,7 @@ void launch_attention(const AttnArgs& a, hipStream_t st) {
     float* o_part = a.scratch;
     float* ml_part = a.scratch + (size_t)n_splits * a.M * a.H * HD;
     const int tiles_per_split = ((a.max_ctx + KT - 1) / KT + n_splits - 1) / n_splits + 1;
-    const size_t smem = mfma_smem_bytes(nt16_max, tiles_per_split);
+    const size_t smem = mfma_smem_bytes(tiles_per_split);
     static bool attr_set = false;
     if (!attr_set) {
       const int most = 160 * 1024;
@@ -505,9 +582,9 @@ void launch_attention(const AttnArgs& a, hipStream_t st) {
       attr_set = true;
     }
     dim3 grid(n_splits, a.Hkv, a.B);
-    if (nt16_max <= 4) attn_mfma_kernel<1><<<grid, 256, smem, st>>>(a, n_splits, nt16_max, o_part, ml_part);
-    else if (nt16_max <= 8) attn_mfma_kernel<2><<<grid, 256, smem, st>>>(a, n_splits, nt16_max, o_part, ml_part);
-    else attn_mfma_kernel<3><<<grid, 256, smem, st>>>(a, n_splits, nt16_max, o_part, ml_part);
+    if (nt16_max <= 4) attn_mfma_kernel<1><<<grid, 256, smem, st>>>(a, n_splits, o_part, ml_part);
+    else if (nt16_max <= 8) attn_mfma_kernel<2><<<grid, 256, smem, st>>>(a, n_splits, o_part, ml_part);
+    else attn_mfma_kernel<3><<<grid, 256, smem, st>>>(a, n_splits, o_part, ml_part);
     if (n_splits > 1) {
       const int waves = a.M * a.H;
       attn_merge_kernel<<<(waves + 3) / 4, 256, 0, st>>>(o_part, ml_part, n_splits, a.M, a.H, reinterpret_cast<f16_t*>(a.out));
