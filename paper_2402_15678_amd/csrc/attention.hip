@@ -152,7 +152,7 @@ constexpr int KT = 32;                         // keys per tile (two blocks)
 constexpr int TILE_HALFS = 2 * KT * HD;        // fp16 elements of K + V of one tile
 constexpr int TILE_BYTES = TILE_HALFS * 2;     // 16 KB
 constexpr int NS = 4;                          // tile slots in LDS
-constexpr int MAX_CT = 3;                      // column tiles per wave at most (R <= 192)
+constexpr int MAX_CT = 2;                      // column tiles per wave; a workgroup covers 64 * MAX_CT stacked rows
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LAZY_MAX = 6.f;                // the reference moves when a score exceeds it by 2^6
 
@@ -219,12 +219,14 @@ template <int N> struct IntC { static constexpr int value = N; };
 
 // Partials: o_part [split][M][H][HD] fp32 (unnormalised), ml_part [split][M][H][2] = (max in log2 units, sum)
 template <int CTW>
-__global__ void __launch_bounds__(256, CTW >= 3 ? 1 : 2) attn_mfma_kernel(AttnArgs a, int n_splits, float* __restrict__ o_part,
-                                                                          float* __restrict__ ml_part) {
+__global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_splits, int n_rg, float* __restrict__ o_part,
+                                                           float* __restrict__ ml_part) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   f16_t* s_kv = reinterpret_cast<f16_t*>(smem);                          // [NS][16 fragments][64 lanes][8]
   int32_t* s_bidx = reinterpret_cast<int32_t*>(smem + NS * TILE_BYTES);  // physical block of every block of the split
-  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  // row group rg: column tiles [4*CTW*rg, 4*CTW*(rg+1)) of the stack; sequences with more than 64*CTW
+  // stacked rows get a workgroup per group (each streams the keys again), the others leave at once
+  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z / n_rg, rg = blockIdx.z % n_rg;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
   const int G = a.H / a.Hkv;
@@ -234,13 +236,15 @@ __global__ void __launch_bounds__(256, CTW >= 3 ? 1 : 2) attn_mfma_kernel(AttnAr
   const int ok = a.rows.seq_ok[b];
   const int ctx = a.rows.seq_ctx[b];
   const int R = G * qb;                   // query rows sharing this KV head; row r = j*G + gi
-  const int NT16 = (R + 15) >> 4;         // column tiles in use (<= 4*CTW, checked by the launcher)
+  const int NT16 = (R + 15) >> 4;         // column tiles in use
+  const int tile0 = 4 * CTW * rg;         // first column tile of this workgroup
+  if (tile0 >= NT16) return;              // (whole workgroup)
   const int nkeys = ok ? ctx + qb : 0;
   const int n_tiles = (nkeys + KT - 1) / KT;
   const int t_begin = (int)(((long)n_tiles * split) / n_splits);
   const int t_end = (int)(((long)n_tiles * (split + 1)) / n_splits);
   const int n_my = max(0, t_end - t_begin);
-  const int nct = ok ? min(CTW, max(0, (NT16 - wave + 3) >> 2)) : 0;  // real column tiles of this wave
+  const int nct = ok ? min(CTW, max(0, (NT16 - tile0 - wave + 3) >> 2)) : 0;  // real column tiles of this wave
 
   // block table of this split -> LDS (the dependent chain table -> address -> load would otherwise
   // cost an L2 round trip per tile); entries past the last mapped block repeat the last one
@@ -262,7 +266,7 @@ __global__ void __launch_bounds__(256, CTW >= 3 ? 1 : 2) attn_mfma_kernel(AttnAr
     thr[ct] = -INFINITY;
     negm4[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
     L[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    const int r = (wave + 4 * ct) * 16 + l16;
+    const int r = (tile0 + wave + 4 * ct) * 16 + l16;
     lim[ct] = ctx + min(r / G, qb - 1);  // last visible key of this lane's query row
 #pragma unroll
     for (int u = 0; u < 8; ++u) O[ct][u] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -449,12 +453,6 @@ __global__ void __launch_bounds__(256, CTW >= 3 ? 1 : 2) attn_mfma_kernel(AttnAr
           for (; i < n_my; ++i) iter(IntC<1>{}, IntC<1>{}, i);
         }
       }
-      if constexpr (CTW > 2) {
-        if (nct == 2) {
-          for (; i < n_fast; ++i) iter(IntC<2>{}, IntC<0>{}, i);
-          for (; i < n_my; ++i) iter(IntC<2>{}, IntC<1>{}, i);
-        }
-      }
     }
     att_wait_vm<0>();  // the loads of the tiles past the end must land before the LDS is given back
 #undef MN_ATT_DMA
@@ -463,7 +461,7 @@ __global__ void __launch_bounds__(256, CTW >= 3 ? 1 : 2) attn_mfma_kernel(AttnAr
   // ---- output: lane holds O^T[hd = 16u + 4g + i][row = tile*16 + l16]; every lane has its row's sum ----
 #pragma unroll
   for (int ct = 0; ct < CTW; ++ct) {
-    const int tile = wave + 4 * ct;
+    const int tile = tile0 + wave + 4 * ct;
     const int r = tile * 16 + l16;
     if (tile >= NT16 || r >= R) continue;
     const float l = L[ct][0];
@@ -562,10 +560,10 @@ size_t attention_scratch_bytes(int M, int H, int hd, int max_ctx, int dtype) {
 void launch_attention(const AttnArgs& a, hipStream_t st) {
   if (a.M <= 0 || a.B <= 0) return;
   const int G = a.Hkv > 0 ? a.H / a.Hkv : 1;
-  // the MFMA kernel stacks at most 4 * MAX_CT column tiles of 16 query rows per KV head
+  // the MFMA kernel covers 4 * MAX_CT column tiles of 16 stacked query rows per workgroup; longer stacks
+  // are cut into row groups
   const int nt16_max = (G * a.max_q + 15) / 16;
-  const bool mfma = attention_mfma_supported(a.H, a.Hkv, a.hd, a.kv.block_size, a.dtype) && nt16_max <= 4 * MAX_CT &&
-                    a.scratch != nullptr &&
+  const bool mfma = attention_mfma_supported(a.H, a.Hkv, a.hd, a.kv.block_size, a.dtype) && a.scratch != nullptr &&
                     a.scratch_bytes >= attention_scratch_bytes(a.M, a.H, a.hd, a.max_ctx, a.dtype);
   if (mfma) {
     const int n_splits = pick_splits(a.B, a.Hkv, a.max_ctx);
@@ -578,13 +576,14 @@ void launch_attention(const AttnArgs& a, hipStream_t st) {
       const int most = 160 * 1024;
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, most);
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, most);
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<3>), hipFuncAttributeMaxDynamicSharedMemorySize, most);
       attr_set = true;
     }
-    dim3 grid(n_splits, a.Hkv, a.B);
-    if (nt16_max <= 4) attn_mfma_kernel<1><<<grid, 256, smem, st>>>(a, n_splits, o_part, ml_part);
-    else if (nt16_max <= 8) attn_mfma_kernel<2><<<grid, 256, smem, st>>>(a, n_splits, o_part, ml_part);
-    else attn_mfma_kernel<3><<<grid, 256, smem, st>>>(a, n_splits, o_part, ml_part);
+    if (nt16_max <= 4) {
+      attn_mfma_kernel<1><<<dim3(n_splits, a.Hkv, a.B), 256, smem, st>>>(a, n_splits, 1, o_part, ml_part);
+    } else {
+      const int n_rg = (nt16_max + 4 * MAX_CT - 1) / (4 * MAX_CT);
+      attn_mfma_kernel<2><<<dim3(n_splits, a.Hkv, a.B * n_rg), 256, smem, st>>>(a, n_splits, n_rg, o_part, ml_part);
+    }
     if (n_splits > 1) {
       const int waves = a.M * a.H;
       attn_merge_kernel<<<(waves + 3) / 4, 256, 0, st>>>(o_part, ml_part, n_splits, a.M, a.H, reinterpret_cast<f16_t*>(a.out));

@@ -2,8 +2,8 @@
 //
 // The verification step scores only M = sum_b (k_b + 1) rows (tens to a few hundred) against
 // matrices of 10^8..10^9 parameters, so every weight byte is needed exactly once per step and
-// the kernel is a weight streamer: weights go HBM -> registers (bf16 widened exactly to fp16) ->
-// MFMA with no staging (both operands are contiguous along k, which is what the 16x16x32 MFMA
+// the kernel is a weight streamer: weights go HBM -> registers -> MFMA with no staging and no
+// conversion (the packed matrices hold the bf16 values re-encoded as fp16, see below) (both operands are contiguous along k, which is what the 16x16x32 MFMA
 // wants: 8 consecutive k per lane), the small fp16 activation tile is shared by the four waves of
 // a workgroup through LDS, and all M rows of a chunk are covered by one workgroup so no weight
 // byte is read twice.
@@ -14,7 +14,11 @@
 // (nb * K/128 + kb) * 32 KB, so one workgroup walks one contiguous stream.  Inside a block the
 // fragment of wave w, column tile nt, k-step ks is the 1 KB at ((w*2 + nt)*4 + ks) KB, stored in
 // lane order: lane l holds output column (w*2 + nt)*16 + l%16, k = ks*32 + (l/16)*8 .. +7.
-// Rows past N are zero.  pack_weight_kernel converts from row-major.
+// Rows past N are zero.  pack_weight_kernel converts from row-major and re-encodes every bf16 value as
+// the fp16 value the MFMA consumes (same two bytes per parameter; every bf16 value of magnitude in
+// [2^-14, 65504] is an fp16 value, smaller ones land on the fp16 subnormal grid with an absolute
+// error under 2^-24, larger ones do not occur in weights), so the main loop spends no vector
+// instruction on the weight stream: the widening used to take more issue slots than the MFMAs.
 #include "launch.h"
 #include "../../include/minions_verify.h"
 
@@ -45,8 +49,8 @@ __device__ __forceinline__ int lds_slot(int row, int chunk) { return row * LDS_R
 // with 4 consecutive n for one m.
 //
 // Pipeline per wave: the raw bf16 weight fragments of iterations it+1 and it+2 are in flight in a
-// two-slot register ring while iteration it runs on the MFMA (the slot of iteration it is widened
-// to fp16 at the top of the iteration and refilled at once for it+2); the activation tile of
+// two-slot register ring while iteration it runs on the MFMA (the slot of iteration it is consumed
+// k-step by k-step and refilled at once for it+2); the activation tile of
 // iteration it+1 travels global -> registers -> the other LDS buffer during the same time.
 //
 // Epilogues: EPI_PARTIAL stores the fp32 partial sums of this split ([S][M][N], bias on split 0).
@@ -56,7 +60,7 @@ __device__ __forceinline__ int lds_slot(int row, int chunk) { return row * LDS_R
 enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1 };
 
 template <int MT, int NTW, int EPI, int NW, int RD>
-__global__ void __launch_bounds__(NW * 64, 2) gemm_w16_kernel(const f16_t* __restrict__ A, const bf16_t* __restrict__ W,
+__global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) gemm_w16_kernel(const f16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                            void* __restrict__ out_, const float* __restrict__ bias,
                                                            int M, int N, int K, int k_per_split, int m_chunks, int gx,
                                                            int n_split) {
@@ -176,7 +180,7 @@ __global__ void __launch_bounds__(NW * 64, 2) gemm_w16_kernel(const f16_t* __res
     _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                                     \
       f16x8 wcur_[NTW];                                                                                     \
       _Pragma("unroll") for (int nt = 0; nt < NTW; ++nt) {                                                  \
-        wcur_[nt] = bf16x8_to_f16x8(RING[nt][ks]);                                                          \
+        wcur_[nt] = __builtin_bit_cast(f16x8, RING[nt][ks]); /* packed weights are fp16 already */           \
         RING[nt][ks] = *MN_W_PTR(it_ + RD, nt, ks);                                                         \
       }                                                                                                     \
       _Pragma("unroll") for (int grp = 0; grp < 2; ++grp) {                                                 \
@@ -282,7 +286,11 @@ __global__ void __launch_bounds__(256) pack_weight_kernel(const bf16_t* __restri
       }
       v = *reinterpret_cast<const uint4*>(src + (size_t)srow * K + k);
     }
-    *reinterpret_cast<uint4*>(dst + idx * 8) = v;
+    // re-encode once, here, instead of in every pass over the matrix: the same conversion the kernels
+    // apply to bf16 data in registers (exact for magnitudes in [2^-14, 65504], below that truncated to
+    // the fp16 subnormal grid, an absolute error under 2^-24)
+    const f16x8 h = bf16x8_to_f16x8(v);
+    *reinterpret_cast<f16x8*>(dst + idx * 8) = h;
   }
 }
 
@@ -420,7 +428,7 @@ void launch_gemm(const GemmArgs& a, hipStream_t st) {
   else if (tiles <= 4) launch_bf16_mt<4, 4>(a, 1, st);
   else if (tiles <= 6) launch_bf16_mt<6, 4>(a, 1, st);
   else if (tiles <= 9) { if (gemm_wide(a.N, a.K)) launch_bf16_mt<9, 8>(a, 1, st); else launch_bf16_mt<9, 4>(a, 1, st); }
-  else launch_bf16_mt<6, 4, 4, 1>(a, (tiles + 5) / 6, st);  // many rows: 64 columns per wave, 96-row chunks
+  else launch_bf16_mt<8, 4>(a, (tiles + 7) / 8, st);  // many rows: 128-row chunks, each streaming the weights (from L2 after the first)
 }
 
 }  // namespace mn
