@@ -68,17 +68,16 @@ __global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) ge
   // does not touch the reads of the other
   __shared__ __attribute__((aligned(1024))) f16_t s_a0[16 * MT * LDS_ROW];
   __shared__ __attribute__((aligned(1024))) f16_t s_a1[16 * MT * LDS_ROW];
-  // NW = 4: one 128-column block per workgroup, two workgroups per CU.  NW = 8: two adjacent blocks per
-  // workgroup (waves 0-3 / 4-7), one workgroup per CU: the activation tile is then fetched once per 256
-  // columns, which halves the L2 -> LDS traffic and the load-unit time it costs.
+  // NW = 4: 128 columns per workgroup, two workgroups per CU.  NW = 5..8: up to 256 columns per
+  // workgroup, one workgroup per CU: the activation tile is then fetched once for all of them, which
+  // cuts the L2 -> LDS traffic and the load-unit time it costs.
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
   constexpr int WPB = 8 / NTW;                                  // waves per 128-column block
-  const int w4 = wave % WPB;                                    // wave inside its 128-column block
   const int nblk_all = (N + NWG - 1) / NWG;
-  // Grid.  One row chunk: (column blocks, splits, 1).  More rows than one chunk holds (M > 144): a 1-D
-  // grid in which the row chunks of one (column block, split) pair get consecutive slots on the SAME
+  // Grid.  One row chunk: (column groups, splits, 1).  More rows than one chunk holds (M > 144): a 1-D
+  // grid in which the row chunks of one (column group, split) pair get consecutive slots on the SAME
   // XCD (workgroup ids are dealt round-robin over the 8 XCDs), so the chunks run together and the
   // weight block comes from HBM once and from that XCD's L2 for the other chunks.
   int bx = blockIdx.x, split = blockIdx.y, bz = 0;
@@ -90,7 +89,12 @@ __global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) ge
     bx = pair % gx;
     split = pair / gx;
   }
-  const int nblk = bx * (NW / WPB) + wave / WPB;                // this wave's column block
+  // A workgroup covers NW consecutive wave slices (16*NTW columns each) of the matrix, whatever NW is: the
+  // launcher picks the wave count that makes the grid fill the chip (7 waves = 224 columns give the
+  // 57344-column matrix exactly 256 workgroups).  All waves share the activation tile.
+  const int wslice = bx * NW + wave;                            // this wave's slice of the matrix
+  const int nblk = wslice / WPB;                                // its 128-column block ...
+  const int w4 = wslice % WPB;                                  // ... and its place inside the block
   const int nblk_rd = min(nblk, nblk_all - 1);                  // past the end: re-read the last block, store nothing
   const int n_wg = nblk * NWG;
   const int m0 = bz * (16 * MT);
@@ -361,47 +365,68 @@ static GemmTune tune() {
   return t;
 }
 
-// 8-wave workgroups (256 columns) for this shape?  (experiment switch MN_GEMM_WIDE: 0 never, 1 always)
-static bool gemm_wide(int N, int K) {
-  static int mode = [] {
-    const char* e = getenv("MN_GEMM_WIDE");
-    return e ? atoi(e) : -1;
+// Shape of the grid for one projection: waves per workgroup (each wave owns 32 columns; all waves of a
+// workgroup share the activation tile, so more waves mean less L2 -> LDS traffic per weight byte) and
+// k-splits.  Goal: every CU streams (a CU's share of the HBM rate is bounded by what its waves keep in
+// flight), the whole grid is resident at once, and every split runs at least 16 iterations (measured:
+// shorter splits lose more to ramp-up and partial sums than the extra workgroups win).
+// Experiment switches: MN_GEMM_NW forces the wave count, MN_GEMM_SPLIT the splits.
+struct GemmPlan {
+  int nw, split;
+};
+static GemmPlan gemm_plan(int M, int N, int K, int forced_split) {
+  static int forced_nw = [] {
+    const char* e = getenv("MN_GEMM_NW");
+    return e ? atoi(e) : 0;
   }();
-  if (mode >= 0) return mode != 0;
-  // wide when the halved grid, with the splits it can get, still covers most CUs (measured: the
-  // 8192 x 8192 output projection, 128 workgroups when wide, is the one shape that loses)
-  const int nb2 = ((N + NWG - 1) / NWG + 1) / 2;
-  int s = 256 / nb2;
-  if (s > (K / KB) / 16) s = (K / KB) / 16;
-  if (s < 1) s = 1;
-  return nb2 * s >= 150;
+  const int slices = ((N + NWG - 1) / NWG) * 4;  // 32-column wave slices of the padded matrix
+  const int iters = K / KB;
+  if (forced_split < 1 && tune().split >= 1) forced_split = tune().split;
+  auto splits_for = [&](int gx, int slots) {
+    int s = forced_split >= 1 ? forced_split : slots / gx;
+    if (forced_split < 1 && s > iters / 16) s = iters / 16;
+    if (s > MN_MAX_SPLIT_K) s = MN_MAX_SPLIT_K;
+    if (s < 1) s = 1;
+    const int per = (iters + s - 1) / s;  // drop splits that would get no iteration
+    return (iters + per - 1) / per;
+  };
+  GemmPlan best{4, 1};
+  if (M <= 96) {  // up to six row tiles: 4-wave workgroups, two per CU
+    best.split = splits_for((slices + 3) / 4, tune().target);
+    return best;
+  }
+  int best_cus = 0, best_waves = 0;
+  for (int nw = 8; nw >= 4; --nw) {
+    if (forced_nw && nw != forced_nw) continue;
+    const int gx = (slices + nw - 1) / nw;
+    const int slots = nw == 4 ? tune().target : tune().target / 2;  // 4 waves: two workgroups per CU
+    const int sp = splits_for(gx, slots);
+    const int wgs = gx * sp;
+    const int cus = wgs < 256 ? wgs : 256;
+    const int waves = (wgs < slots ? wgs : slots) * nw;
+    // fewer waves per workgroup only when that puts clearly more CUs (or waves) to work (measured at 144
+    // rows: 224 -> 256 CUs gains nothing on the 57344-column matrix, 160 -> 256 gains 6 % on the
+    // 10240-column one)
+    if (best_cus == 0 || cus * 100 >= best_cus * 115 || (cus >= best_cus && waves * 100 >= best_waves * 115)) {
+      best = GemmPlan{nw, sp};
+      best_cus = cus;
+      best_waves = waves;
+    }
+  }
+  return best;
 }
 
 int gemm_pick_split(int M, int N, int K, int dtype) {
   if (dtype != MN_DT_BF16) return 1;
-  const int forced = tune().split;
-  const bool wide = M > 96 && gemm_wide(N, K);  // 8-wave workgroups: half as many, one per CU
-  const int nblocks = wide ? ((N + NWG - 1) / NWG + 1) / 2 : (N + NWG - 1) / NWG;
-  const int iters = K / KB;
-  // as many splits as keep the whole grid resident at once (two workgroups per CU), each split at
-  // least 16 iterations long (measured: shorter splits lose more to ramp-up and partial sums than
-  // the extra workgroups win)
-  int s = forced >= 1 ? forced : (wide ? tune().target / 2 : tune().target) / nblocks;
-  if (forced < 1 && s > iters / 16) s = iters / 16;
-  if (s > MN_MAX_SPLIT_K) s = MN_MAX_SPLIT_K;
-  if (s < 1) s = 1;
-  // drop splits that would get no iteration
-  const int per = (iters + s - 1) / s;
-  return (iters + per - 1) / per;
+  return gemm_plan(M, N, K, 0).split;
 }
 
 template <int MT, int NW, int NTW = 2, int RD = 2>
 static void launch_bf16_mt(const GemmArgs& a, int m_chunks, hipStream_t st) {
   const int iters = a.K / KB;
   const int per = (iters + a.split_k - 1) / a.split_k;  // iterations per split
-  const int nblk = (a.N + NWG - 1) / NWG;
-  constexpr int BPW = NW * NTW / 8;                     // 128-column blocks per workgroup
-  const int gx = (nblk + BPW - 1) / BPW;
+  const int slices = ((a.N + NWG - 1) / NWG) * (8 / NTW);
+  const int gx = (slices + NW - 1) / NW;
   dim3 grid(gx, a.split_k, 1);
   if (m_chunks > 1) grid = dim3(((gx * a.split_k + 7) / 8) * 8 * m_chunks, 1, 1);
   const f16_t* A = reinterpret_cast<const f16_t*>(a.a);
@@ -427,7 +452,15 @@ void launch_gemm(const GemmArgs& a, hipStream_t st) {
   else if (tiles <= 3) launch_bf16_mt<3, 4>(a, 1, st);
   else if (tiles <= 4) launch_bf16_mt<4, 4>(a, 1, st);
   else if (tiles <= 6) launch_bf16_mt<6, 4>(a, 1, st);
-  else if (tiles <= 9) { if (gemm_wide(a.N, a.K)) launch_bf16_mt<9, 8>(a, 1, st); else launch_bf16_mt<9, 4>(a, 1, st); }
+  else if (tiles <= 9) {
+    switch (gemm_plan(a.M, a.N, a.K, a.split_k).nw) {
+      case 8: launch_bf16_mt<9, 8>(a, 1, st); break;
+      case 7: launch_bf16_mt<9, 7>(a, 1, st); break;
+      case 6: launch_bf16_mt<9, 6>(a, 1, st); break;
+      case 5: launch_bf16_mt<9, 5>(a, 1, st); break;
+      default: launch_bf16_mt<9, 4>(a, 1, st); break;
+    }
+  }
   else launch_bf16_mt<8, 4>(a, (tiles + 7) / 8, st);  // many rows: 128-row chunks, each streaming the weights (from L2 after the first)
 }
 
