@@ -207,6 +207,45 @@ mn_status mn_accept_and_commit(mn_ctx *ctx, const int32_t *voted, const int32_t 
                                int32_t *n_out, int32_t *next_last_tok, int32_t *blocks_in_use,
                                int32_t *dev_status, void *stream);
 
+/* ---- after the step: closing the loop (sections 3.2 and 3.3) --------------------------------- */
+
+/* Speculation quality metric and SSM weight update (section 3.2, equation ACR).  For every SSM i,
+ * ACR_i = mean over the verified outputs b whose voted_ssm[b] == i of accepted_len[b] / spec_len[b]
+ * (fp64, outputs taken in ascending b; outputs with spec_len[b] <= 0, or with n_out[b] <= 0 when n_out
+ * is given, i.e. not verified by this step, are not in the set).  ssm_w[i] is multiplied (fp32) by
+ * reward_factor when ACR_i > reward_threshold and by punish_factor when ACR_i < punish_threshold; an
+ * SSM that won no vote keeps its weight and reports NaN.  The paper leaves the four constants to the
+ * operator; they are arguments here.
+ *   voted_ssm dev [B] (from mn_mv_vote)      accepted_len, n_out dev [B] (from mn_accept_and_commit;
+ *   spec_len  dev [B]                         n_out may be NULL)
+ *   ssm_w     dev [n] fp32, updated in place (the next mn_mv_vote reads it: no host round trip)
+ *   acr       dev [n] fp64 (out) or NULL
+ * 1 <= n <= MN_MAX_DRAFTS, 0 <= B <= MN_MAX_BATCH, factors > 0, punish_threshold <= reward_threshold.
+ * ctx may be NULL. */
+mn_status mn_acr_update(mn_ctx *ctx, const int32_t *voted_ssm, const int32_t *accepted_len, const int32_t *spec_len,
+                        const int32_t *n_out, int B, int n, double reward_threshold, double punish_threshold,
+                        float reward_factor, float punish_factor, float *ssm_w, double *acr, void *stream);
+
+/* Adaptive speculation length selector (section 3.3).  Host-side state, no device work.  Every
+ * verification step contributes one sample t_llm / vl (step time over the average number of tokens
+ * a request gained from the step).  When decision_threshold samples have been collected since the
+ * last change (the text's "greater than or equal"; the listing's strict comparison differs by one
+ * sample), the least-squares line through (0, y_0) .. (m-1, y_{m-1}) is fitted: slope > 0 lowers s by
+ * s_penalty, any other slope raises it by s_reward (the listing's else branch); s is clamped to
+ * [s_min, s_max] and the samples are discarded.
+ * mn_selector_create: 0 <= s_min <= s_init <= s_max, decision_threshold >= 2, s_penalty, s_reward >= 0.
+ * mn_selector_observe: t_llm >= 0 and vl > 0, both finite (MN_EINVAL otherwise, nothing recorded);
+ * *s_out (may be NULL) = the speculation length to use next; *slope_out (may be NULL) = the fitted slope
+ * when this call triggered a decision, NaN otherwise.  The caller owns the object; calls on one object
+ * must not overlap. */
+typedef struct mn_selector mn_selector;
+mn_status mn_selector_create(mn_selector **out, int s_init, int s_min, int s_max, int decision_threshold,
+                             int s_penalty, int s_reward);
+void mn_selector_destroy(mn_selector *sel);
+mn_status mn_selector_observe(mn_selector *sel, double t_llm, double vl, int *s_out, double *slope_out);
+int mn_selector_current(const mn_selector *sel);   /* -1 when sel is NULL */
+long mn_selector_adjustments(const mn_selector *sel); /* decisions taken so far; -1 when sel is NULL */
+
 /* ---- component entry points (the kernels mn_verify_forward is made of, at their own shapes) -- */
 
 /* The projection GEMM of a bf16 model: out[m][n] = sum_k a[m][k] * w[n][k] (+ bias[n]).

@@ -27,6 +27,9 @@ What it computes, with the passage of the paper each part follows:
                      grows by the accepted prefix plus the pending token.
 * ``acr_update``     speculation quality metric (equation ACR) and the multiplicative weight
                      update of section 3.2.
+* ``fit_slope`` / ``Selector``  the adaptive speculation length selector of section 3.3: a
+                     least-squares line through the monitored t_LLM / vl samples decides whether the
+                     speculation length goes down (rising trend) or up.
 
 Arithmetic: parameters are taken as stored (bf16 values arrive widened exactly);
 every intermediate is fp64; nothing is rounded on the way.  Vote weights are summed
@@ -383,17 +386,19 @@ def verify_step(desc, W, caches: Sequence[SeqCache], last_tok: Sequence[int], dr
 
 def acr_update(ssm_w: Sequence[float], voted_ssm: Sequence[int], accepted_len: Sequence[int],
                spec_len: Sequence[int], reward_threshold: float, punish_threshold: float,
-               reward_factor: float, punish_factor: float) -> Tuple[np.ndarray, np.ndarray]:
+               reward_factor: float, punish_factor: float,
+               verified: Optional[Sequence[bool]] = None) -> Tuple[np.ndarray, np.ndarray]:
     """ACR_i = mean over the outputs whose voted SSM is i of (accepted length / speculation length);
     w_i is multiplied by the reward factor when ACR_i exceeds the reward threshold and by the punish
     factor when it falls below the punish threshold.  SSMs that won no vote keep their weight
-    (their ACR is reported as NaN).  Returns (new weights fp32, ACR fp64)."""
+    (their ACR is reported as NaN).  The set o_SSM_i holds verified outputs only: ``verified`` marks the
+    outputs the LLM actually scored (all of them when omitted).  Returns (new weights fp32, ACR fp64)."""
     n = len(ssm_w)
     acr = np.full((n,), np.nan, np.float64)
     w = np.asarray(ssm_w, np.float32).copy()
     for i in range(n):
         rates = [float(accepted_len[b]) / float(spec_len[b]) for b in range(len(voted_ssm))
-                 if int(voted_ssm[b]) == i and int(spec_len[b]) > 0]
+                 if int(voted_ssm[b]) == i and int(spec_len[b]) > 0 and (verified is None or bool(verified[b]))]
         if not rates:
             continue
         acr[i] = sum(rates) / len(rates)
@@ -402,3 +407,44 @@ def acr_update(ssm_w: Sequence[float], voted_ssm: Sequence[int], accepted_len: S
         elif acr[i] < punish_threshold:
             w[i] = np.float32(w[i] * np.float32(punish_factor))
     return w, acr
+
+
+# ---------------------------------------------------------------------------
+# adaptive speculation length selector (section 3.3)
+# ---------------------------------------------------------------------------
+
+def fit_slope(y: Sequence[float]) -> float:
+    """Slope of the least-squares line through (0, y_0) .. (m-1, y_{m-1}): the textbook
+    sum((x - mean x)(y - mean y)) / sum((x - mean x)^2), in fp64."""
+    m = len(y)
+    xm = sum(float(i) for i in range(m)) / m
+    ym = sum(float(v) for v in y) / m
+    sxy = sum((i - xm) * (float(y[i]) - ym) for i in range(m))
+    sxx = sum((i - xm) ** 2 for i in range(m))
+    return sxy / sxx
+
+
+class Selector:
+    """Section 3.3.  ``observe(t_llm, vl)`` records t_llm / vl; once ``decision_threshold`` samples have
+    been collected since the last change (reading: the text's "greater than or equal"), the fitted
+    slope decides: positive -> s - s_penalty, otherwise -> s + s_reward (the listing's else branch);
+    s stays inside [s_min, s_max]; the samples are dropped.  Returns the s to use next."""
+
+    def __init__(self, s_init: int, s_min: int, s_max: int, decision_threshold: int, s_penalty: int, s_reward: int):
+        self.s, self.s_min, self.s_max = s_init, s_min, s_max
+        self.decision_threshold, self.s_penalty, self.s_reward = decision_threshold, s_penalty, s_reward
+        self.samples: List[float] = []
+        self.adjustments = 0
+        self.last_slope = math.nan
+
+    def observe(self, t_llm: float, vl: float) -> int:
+        self.last_slope = math.nan
+        self.samples.append(float(t_llm) / float(vl))
+        if len(self.samples) >= self.decision_threshold:
+            slope = fit_slope(self.samples)
+            self.last_slope = slope
+            self.s = self.s - self.s_penalty if slope > 0.0 else self.s + self.s_reward
+            self.s = max(self.s_min, min(self.s_max, self.s))
+            self.samples = []
+            self.adjustments += 1
+        return self.s

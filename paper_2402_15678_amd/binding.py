@@ -22,7 +22,9 @@ MN_MAX_DRAFTS, MN_MAX_BATCH, MN_MAX_SPLIT_K = 64, 4096, 16
 
 EXPORTS = ("mn_create", "mn_destroy", "mn_last_error", "mn_status_str", "mn_workspace_bytes", "mn_mv_vote",
            "mn_verify_forward", "mn_accept_and_commit", "mn_proj_gemm", "mn_attention", "mn_profile_enable",
-           "mn_profile_collect", "mn_packed_weight_bytes", "mn_pack_weight")
+           "mn_profile_collect", "mn_packed_weight_bytes", "mn_pack_weight", "mn_acr_update",
+           "mn_selector_create", "mn_selector_destroy", "mn_selector_observe", "mn_selector_current",
+           "mn_selector_adjustments")
 PROF_KINDS = ("prepare", "norm", "gemm", "rope_append", "attention", "act", "argmax", "vote", "accept")
 
 
@@ -77,6 +79,18 @@ def _load() -> C.CDLL:
     lib.mn_packed_weight_bytes.argtypes = [i32, i32]
     lib.mn_pack_weight.restype = i32
     lib.mn_pack_weight.argtypes = [vp, vp, i32, i32, i32, vp]
+    lib.mn_acr_update.restype = i32
+    lib.mn_acr_update.argtypes = [vp, vp, vp, vp, vp, i32, i32, C.c_double, C.c_double, C.c_float, C.c_float, vp, vp, vp]
+    lib.mn_selector_create.restype = i32
+    lib.mn_selector_create.argtypes = [C.POINTER(vp), i32, i32, i32, i32, i32, i32]
+    lib.mn_selector_destroy.restype = None
+    lib.mn_selector_destroy.argtypes = [vp]
+    lib.mn_selector_observe.restype = i32
+    lib.mn_selector_observe.argtypes = [vp, C.c_double, C.c_double, C.POINTER(C.c_int), C.POINTER(C.c_double)]
+    lib.mn_selector_current.restype = i32
+    lib.mn_selector_current.argtypes = [vp]
+    lib.mn_selector_adjustments.restype = C.c_long
+    lib.mn_selector_adjustments.argtypes = [vp]
     lib.mn_profile_enable.restype = i32
     lib.mn_profile_enable.argtypes = [vp, i32]
     lib.mn_profile_collect.restype = i32
@@ -170,3 +184,36 @@ def mn_packed_weight_bytes(N: int, K: int) -> int:
 
 def mn_pack_weight(src, dst, N, K, interleave_half=0, stream=None) -> None:
     _check(lib.mn_pack_weight(src, dst, N, K, interleave_half, stream), None)
+
+
+def mn_acr_update(ctx, voted_ssm, accepted_len, spec_len, n_out, B, n, reward_threshold, punish_threshold,
+                  reward_factor, punish_factor, ssm_w, acr=None, stream=None) -> None:
+    _check(lib.mn_acr_update(ctx, voted_ssm, accepted_len, spec_len, n_out, B, n, reward_threshold, punish_threshold,
+                             reward_factor, punish_factor, ssm_w, acr, stream), ctx)
+
+
+def mn_selector_create(s_init: int, s_min: int, s_max: int, decision_threshold: int, s_penalty: int,
+                       s_reward: int) -> int:
+    out = C.c_void_p()
+    _check(lib.mn_selector_create(C.byref(out), s_init, s_min, s_max, decision_threshold, s_penalty, s_reward), None)
+    return out.value
+
+
+def mn_selector_destroy(sel: Optional[int]) -> None:
+    if sel:
+        lib.mn_selector_destroy(sel)
+
+
+def mn_selector_observe(sel: int, t_llm: float, vl: float):
+    """Returns (speculation length to use next, fitted slope or NaN when no decision was taken)."""
+    s, slope = C.c_int(), C.c_double()
+    _check(lib.mn_selector_observe(sel, t_llm, vl, C.byref(s), C.byref(slope)), None)
+    return s.value, slope.value
+
+
+def mn_selector_current(sel: int) -> int:
+    return int(lib.mn_selector_current(sel))
+
+
+def mn_selector_adjustments(sel: int) -> int:
+    return int(lib.mn_selector_adjustments(sel))

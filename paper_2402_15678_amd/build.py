@@ -10,7 +10,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libminions_verify.so")
-SOURCES = ("api.hip", "vote_accept.hip", "rows.hip", "gemm.hip", "attention.hip")
+SOURCES = ("api.hip", "vote_accept.hip", "rows.hip", "gemm.hip", "attention.hip", "selector.cpp")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-variable",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -40,7 +40,7 @@ def build(verbose: bool = False) -> str:
     jobs = []
     with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         for src in SOURCES:
-            obj = os.path.join(objdir, src.replace(".hip", ".o"))
+            obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
             objs.append(obj)
             jobs.append(ex.submit(_run, [hipcc, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]))
         for src, j in zip(SOURCES, jobs):

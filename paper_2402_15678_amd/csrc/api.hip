@@ -236,6 +236,25 @@ extern "C" mn_status mn_accept_and_commit(mn_ctx* ctx, const int32_t* voted, con
   return hip_check(ctx, "mn_accept_and_commit");
 }
 
+// ---- speculation quality metric + SSM weight update ------------------------------------------------
+extern "C" mn_status mn_acr_update(mn_ctx* ctx, const int32_t* voted_ssm, const int32_t* accepted_len,
+                                   const int32_t* spec_len, const int32_t* n_out, int B, int n, double reward_threshold,
+                                   double punish_threshold, float reward_factor, float punish_factor, float* ssm_w,
+                                   double* acr, void* stream) {
+  if (B < 0 || B > MN_MAX_BATCH) return fail(ctx, MN_EINVAL, "mn_acr_update: B = %d", B);
+  if (n < 1 || n > MN_MAX_DRAFTS) return fail(ctx, MN_EINVAL, "mn_acr_update: n = %d", n);
+  if (!(reward_factor > 0.f) || !(punish_factor > 0.f)) return fail(ctx, MN_EINVAL, "mn_acr_update: factors must be positive");
+  if (!(punish_threshold <= reward_threshold)) return fail(ctx, MN_EINVAL, "mn_acr_update: punish_threshold above reward_threshold");
+  if (!ssm_w) return fail(ctx, MN_ENULL, "mn_acr_update: ssm_w is NULL");
+  if (B > 0 && (!voted_ssm || !accepted_len || !spec_len)) return fail(ctx, MN_ENULL, "mn_acr_update: a required pointer is NULL");
+  {
+    Tap t(ctx ? &ctx->prof : nullptr, MN_PROF_ACCEPT, (hipStream_t)stream);
+    launch_acr_update(voted_ssm, accepted_len, spec_len, n_out, B, n, reward_threshold, punish_threshold, reward_factor,
+                      punish_factor, ssm_w, acr, (hipStream_t)stream);
+  }
+  return hip_check(ctx, "mn_acr_update");
+}
+
 // ---- shared checks --------------------------------------------------------------------------------
 static mn_status check_kv(mn_ctx* c, const mn_kv* kv, int max_ctx, const char* who) {
   if (!kv) return fail(c, MN_ENULL, "%s: kv is NULL", who);

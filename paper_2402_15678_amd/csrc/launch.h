@@ -8,6 +8,9 @@ namespace mn {
 // ---- vote_accept.hip ----
 void launch_vote(const int32_t* drafts, const int32_t* spec_len, const float* ssm_w, int B, int n, int k_max, int mode,
                  int32_t* voted, int32_t* voted_ssm, int32_t* dev_status, hipStream_t st);
+void launch_acr_update(const int32_t* voted_ssm, const int32_t* accepted_len, const int32_t* spec_len,
+                       const int32_t* n_out, int B, int n, double reward_threshold, double punish_threshold,
+                       float reward_factor, float punish_factor, float* ssm_w, double* acr, hipStream_t st);
 void launch_accept_commit(const int32_t* voted, const int32_t* greedy, const int32_t* spec_len, int B, int k_max,
                           int32_t* ctx_lens, int block_size, int max_blocks_per_seq, int32_t* accepted_len,
                           int32_t* out_tokens, int32_t* n_out, int32_t* next_last_tok, int32_t* blocks_in_use,

@@ -1,6 +1,8 @@
 // Integer kernels of the verification step: the majority vote over SSM drafts (paper section 3.2,
-// "Tree-based Weighted Majority Decision") and longest-prefix acceptance with KV commit (section
-// 2.1 in its greedy case; section 4 for the deletion of rejected tokens' cache entries).
+// "Tree-based Weighted Majority Decision"), longest-prefix acceptance with KV commit (section
+// 2.1 in its greedy case; section 4 for the deletion of rejected tokens' cache entries), and the
+// speculation quality metric with the SSM weight update that closes the loop (section 3.2,
+// equation ACR).
 #include "launch.h"
 #include "../../include/minions_verify.h"
 
@@ -131,6 +133,43 @@ void launch_accept_commit(const int32_t* voted, const int32_t* greedy, const int
   accept_commit_kernel<<<(B + bs - 1) / bs, bs, 0, st>>>(voted, greedy, spec_len, B, k_max, ctx_lens, block_size,
                                                         max_blocks_per_seq, accepted_len, out_tokens, n_out,
                                                         next_last_tok, blocks_in_use, dev_status);
+}
+
+// Average acceptance rate per SSM and the multiplicative weight update (section 3.2, equation ACR).
+// Thread i owns SSM i and walks the batch in ascending order: ACR_i is the mean, in fp64, of
+// accepted_len / spec_len over the verified outputs whose voted SSM is i (outputs with nothing
+// speculated, or that the step did not verify, are not in the set).  An SSM that won no vote keeps its
+// weight and reports NaN.  The sum is sequential, so the result does not depend on the launch.
+__global__ void acr_update_kernel(const int32_t* __restrict__ voted_ssm, const int32_t* __restrict__ accepted_len,
+                                  const int32_t* __restrict__ spec_len, const int32_t* __restrict__ n_out, int B, int n,
+                                  double reward_threshold, double punish_threshold, float reward_factor,
+                                  float punish_factor, float* ssm_w, double* __restrict__ acr) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  double sum = 0.0;
+  int cnt = 0;
+  for (int b = 0; b < B; ++b) {
+    const int k = spec_len[b];
+    if (voted_ssm[b] != i || k <= 0 || (n_out && n_out[b] <= 0)) continue;
+    sum += (double)accepted_len[b] / (double)k;
+    ++cnt;
+  }
+  if (cnt == 0) {
+    if (acr) acr[i] = __longlong_as_double(0x7ff8000000000000ll);
+    return;
+  }
+  const double r = sum / (double)cnt;
+  if (acr) acr[i] = r;
+  if (r > reward_threshold) ssm_w[i] = ssm_w[i] * reward_factor;
+  else if (r < punish_threshold) ssm_w[i] = ssm_w[i] * punish_factor;
+}
+
+void launch_acr_update(const int32_t* voted_ssm, const int32_t* accepted_len, const int32_t* spec_len,
+                       const int32_t* n_out, int B, int n, double reward_threshold, double punish_threshold,
+                       float reward_factor, float punish_factor, float* ssm_w, double* acr, hipStream_t st) {
+  if (n <= 0) return;
+  acr_update_kernel<<<1, 64, 0, st>>>(voted_ssm, accepted_len, spec_len, n_out, B, n, reward_threshold, punish_threshold,
+                                      reward_factor, punish_factor, ssm_w, acr);
 }
 
 }  // namespace mn

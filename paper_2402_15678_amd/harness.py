@@ -235,6 +235,13 @@ class VerifySession:
                                self.n_out.data_ptr(), self.next_last_tok.data_ptr(), self.blocks_in_use.data_ptr(),
                                self.dev_status.data_ptr(), stream_ptr())
 
+    def acr_update(self, spec_len: torch.Tensor, ssm_w: torch.Tensor, reward_threshold: float, punish_threshold: float,
+                   reward_factor: float, punish_factor: float, acr: Optional[torch.Tensor] = None) -> None:
+        """Speculation quality metric + SSM weight update on this step's outcome (ssm_w changes in place)."""
+        B.mn_acr_update(self.model.ctx, self.voted_ssm.data_ptr(), self.accepted_len.data_ptr(), spec_len.data_ptr(),
+                        self.n_out.data_ptr(), self.B, self.n, reward_threshold, punish_threshold, reward_factor,
+                        punish_factor, ssm_w.data_ptr(), acr.data_ptr() if acr is not None else None, stream_ptr())
+
     def step(self, last_tok, drafts, spec_len, h_spec_len, ssm_w, mode: int = 0) -> None:
         """vote -> verify forward -> accept + commit, back to back on the current stream."""
         self.vote(drafts, spec_len, ssm_w, mode)

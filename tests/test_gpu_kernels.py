@@ -181,3 +181,34 @@ def test_attention_matches_oracle(hb, name, desc, ctx_lens, spec_lens):
     # of the output is 2^-11 relative each; fp32 path: accumulation order only
     tol = 2e-3 if desc.dtype == synth.DT_BF16 else 1e-5
     assert worst < tol, worst
+
+
+# ---------------------------------------------------------------------------- ACR + SSM weight update
+@pytest.mark.parametrize("B,n,seed", [(1, 1, 0), (16, 4, 1), (64, 5, 2), (257, 7, 3), (4096, 64, 4), (0, 3, 5)])
+def test_acr_update_bit_exact(hb, B, n, seed):
+    harness, binding = hb
+    g = synth.stream(31, B, n, seed)
+    ssm = g.integers(-1, n, size=B).astype(np.int32)
+    k = g.integers(0, 17, size=B).astype(np.int32)
+    a = np.array([g.integers(0, kk + 1) for kk in k], np.int32).reshape(B)
+    n_out = np.where(g.random(B) < 0.9, a + 1, 0).astype(np.int32)
+    w0 = (g.random(n) + 0.5).astype(np.float32)
+    want_w, want_acr = orc.acr_update(w0, ssm, a, k, 0.625, 0.375, 1.25, 0.75, verified=(n_out > 0))
+    ssm_d, a_d, k_d, no_d = _dev(ssm if B else [0]), _dev(a if B else [0]), _dev(k if B else [0]), _dev(n_out if B else [0])
+    w_d = _dev(w0, torch.float32)
+    acr_d = torch.zeros(n, dtype=torch.float64, device="cuda:0")
+    binding.mn_acr_update(None, ssm_d.data_ptr(), a_d.data_ptr(), k_d.data_ptr(), no_d.data_ptr(), B, n, 0.625, 0.375,
+                          1.25, 0.75, w_d.data_ptr(), acr_d.data_ptr(), harness.stream_ptr())
+    torch.cuda.synchronize()
+    got_acr, got_w = acr_d.cpu().numpy(), w_d.cpu().numpy()
+    assert np.array_equal(np.isnan(got_acr), np.isnan(want_acr))
+    assert np.array_equal(got_acr[~np.isnan(want_acr)], want_acr[~np.isnan(want_acr)])   # same sums in the same order
+    assert np.array_equal(got_w, want_w)
+    # without n_out every output with a speculation counts
+    want_w2, want_acr2 = orc.acr_update(want_w, ssm, a, k, 0.625, 0.375, 1.25, 0.75)
+    binding.mn_acr_update(None, ssm_d.data_ptr(), a_d.data_ptr(), k_d.data_ptr(), None, B, n, 0.625, 0.375, 1.25, 0.75,
+                          w_d.data_ptr(), acr_d.data_ptr(), harness.stream_ptr())
+    torch.cuda.synchronize()
+    assert np.array_equal(w_d.cpu().numpy(), want_w2)
+    m = ~np.isnan(want_acr2)
+    assert np.array_equal(acr_d.cpu().numpy()[m], want_acr2[m])

@@ -80,6 +80,23 @@ def test_config0_tiny_opt_fp32_end_to_end(hb):
     assert kvd.ctx_lens.cpu().tolist() == want["ctx_lens"].tolist()
     assert ses.blocks_in_use.cpu().tolist() == want["blocks_in_use"].tolist()
     _compare_cache(desc, kvd, kvh.block_tables, 16, [cache], 1e-4)
+    # closing the loop: the weights the next vote will use, updated on the device from this step's outcome
+    _check_acr(ses, t_k, [4], 3)
+
+
+def _check_acr(ses, t_k, ks, n):
+    """mn_acr_update on the session's own outputs against the oracle on the same integers."""
+    w0 = np.linspace(0.5, 1.5, n).astype(np.float32)
+    t_w = torch.tensor(w0, device="cuda:0")
+    t_acr = torch.zeros(n, dtype=torch.float64, device="cuda:0")
+    ses.acr_update(t_k, t_w, 0.75, 0.5, 1.25, 0.5, acr=t_acr)
+    torch.cuda.synchronize()
+    want_w, want_acr = orc.acr_update(w0, ses.voted_ssm.cpu().numpy(), ses.accepted_len.cpu().numpy(), ks, 0.75, 0.5,
+                                      1.25, 0.5, verified=ses.n_out.cpu().numpy() > 0)
+    got_acr = t_acr.cpu().numpy()
+    assert np.array_equal(np.isnan(got_acr), np.isnan(want_acr))
+    assert np.array_equal(got_acr[~np.isnan(want_acr)], want_acr[~np.isnan(want_acr)])
+    assert np.array_equal(t_w.cpu().numpy(), want_w)
 
 
 def _reduced_case(hb, wl, n_layers, B, n_cand, ctx_override=None, k_override=None):
@@ -154,6 +171,7 @@ def _reduced_case(hb, wl, n_layers, B, n_cand, ctx_override=None, k_override=Non
             # of the absolute noise the fp16 activations upstream leave on O(1) values
             for got, ref in ((K, c.K[l]), (V, c.V[l])):
                 assert (np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-2).all()
+    _check_acr(ses, t_k, ks, wl.n_drafts)
     return err, decisive_seqs
 
 

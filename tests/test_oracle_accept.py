@@ -144,3 +144,28 @@ def test_acr_update_worked_sets():
     w, acr = orc.acr_update([1.0, 1.0, 1.0, 1.0], voted_ssm, acc, k, 0.7, 0.3, 1.5, 0.5)
     assert np.allclose(acr[:3], [(1.0 + 0.5 + 0.0) / 3, 0.25, 0.75]) and np.isnan(acr[3])
     assert w.tolist() == [1.0, 0.5, 1.5, 1.0]
+
+
+def test_acr_update_thresholds_are_strict_and_unverified_outputs_do_not_count():
+    # ACR exactly at a threshold neither rewards nor punishes ("exceeds" / "falls below")
+    w, acr = orc.acr_update([2.0, 2.0], [0, 1], [3, 1], [4, 4], 0.75, 0.25, 1.5, 0.5)
+    assert acr.tolist() == [0.75, 0.25] and w.tolist() == [2.0, 2.0]
+    # an output that was not verified, or that speculated nothing, is not in the set
+    w, acr = orc.acr_update([1.0, 1.0], [0, 0, 0, 1], [4, 0, 2, 0], [4, 4, 0, 4], 0.9, 0.1, 2.0, 0.25,
+                            verified=[True, False, True, True])
+    assert acr.tolist() == [1.0, 0.0] and w.tolist() == [2.0, 0.25]
+    # brute force over the definition on random data: mean of the per-output rates of each SSM's set
+    g = synth.stream(3, 1)
+    B, n = 200, 5
+    ssm = g.integers(-1, n, size=B)
+    k = g.integers(0, 9, size=B)
+    a = np.array([g.integers(0, kk + 1) for kk in k])
+    ok = g.random(B) < 0.9
+    w0 = (g.random(n) + 0.5).astype(np.float32)
+    w, acr = orc.acr_update(w0, ssm, a, k, 0.6, 0.4, 1.25, 0.8, verified=ok)
+    for i in range(n):
+        sel = [b for b in range(B) if ssm[b] == i and k[b] > 0 and ok[b]]
+        want = np.mean([a[b] / k[b] for b in sel]) if sel else np.nan
+        assert (np.isnan(want) and np.isnan(acr[i])) or abs(acr[i] - want) < 1e-12
+        f = np.float32(1.25) if want > 0.6 else np.float32(0.8) if want < 0.4 else np.float32(1.0)
+        assert w[i] == np.float32(w0[i] * f)
