@@ -30,7 +30,7 @@ def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=2, help="index into the workload list (default: 70B b16 k8)")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the real depth); for experiments")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -158,15 +158,40 @@ def main():
 
     for _ in range(args.warmup):
         step()
+    # one event per step boundary on the launch stream: per-step device times for the median and the minimum
+    # (the headline stays wall clock over exactly K steps between two synchronisations)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         step()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     assert ses.dev_status.item() == 0
     ms_per_step = dt / args.steps * 1e3
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     acc = ses.accepted_len.cpu().numpy()
+
+    # the two rows that close the loop after the step (not part of the timed step): the SSM weight update
+    # on the device and the host-side speculation length selector
+    acr_buf = torch.zeros((n,), dtype=torch.float64, device=dev)
+    w_scratch = ssm_w.clone()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ses.acr_update(spec, w_scratch, 0.8, 0.4, 1.1, 0.9, acr=acr_buf)
+    e0.record()
+    for _ in range(50):
+        ses.acr_update(spec, w_scratch, 0.8, 0.4, 1.1, 0.9, acr=acr_buf)
+    e1.record()
+    torch.cuda.synchronize()
+    acr_us = e0.elapsed_time(e1) / 50 * 1e3
+    sel = binding.mn_selector_create(max(1, k_max), 1, 64, 8, 1, 1)
+    t_sel = time.perf_counter()
+    for i in range(10000):
+        binding.mn_selector_observe(sel, ms_per_step * (1.0 + 1e-3 * (i % 7)), float((acc + 1).mean()))
+    sel_ns = (time.perf_counter() - t_sel) / 10000 * 1e9
+    binding.mn_selector_destroy(sel)
 
     # the same steps again with the timing taps on: per-family device time from HIP events on the launch stream
     prof = None
@@ -218,14 +243,18 @@ def main():
         "metric": "verified_positions_per_sec", "value": M / (ms_per_step * 1e-3), "unit": "positions/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16", "storage_dtype": "bf16", "accumulate_dtype": "f32", "data": "synthetic",
+        "dtype": "f16", "storage_dtype": "bf16 (16 bits per parameter; weights re-encoded as fp16 when packed)",
+        "accumulate_dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "arch": "llama" if desc.arch == synth.ARCH_LLAMA else "opt",
                    "n_layers": desc.n_layers, "d_model": desc.d_model, "batch": B, "k_max": k_max, "rows": M,
                    "ctx_min": int(ctx.min()), "ctx_max": int(ctx.max()), "n_drafts": n, "block_size": wl.block_size,
                    "seed": wl.seed},
         "accepted_tokens_per_sec": float((acc + 1).sum()) / (ms_per_step * 1e-3),
         "acceptance_rate": float(acc.sum()) / max(1, int(ks.sum())),
+        "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
         "setup_s": t_setup,
+        "after_step": {"acr_update_us": acr_us, "acr": [None if x != x else x for x in acr_buf.cpu().tolist()],
+                       "selector_observe_ns_incl_binding": sel_ns},
         "roofline": roofline, "kernel_families": families, "cpu_baseline": cpu,
     }
     print(json.dumps(out))
