@@ -105,6 +105,100 @@ def cpu_baseline(wl, desc, M, ks, ctx, n_drafts):
                                                                                  t_layer, t_head)}
 
 
+def measure_ceilings(torch, binding, harness):
+    """What this machine sustains: a plain streaming read over 1 GiB and a dense fp16 MFMA loop (both in the
+    library, timed here with events on the launch stream)."""
+    dev = torch.device("cuda:0")
+    buf = torch.empty((1 << 30,), dtype=torch.uint8, device=dev).fill_(3)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    st = harness.stream_ptr()
+    for _ in range(2):
+        binding.mn_probe_stream_read(buf.data_ptr(), buf.numel(), st)
+    e0.record()
+    for _ in range(10):
+        binding.mn_probe_stream_read(buf.data_ptr(), buf.numel(), st)
+    e1.record()
+    torch.cuda.synchronize()
+    hbm = 10.0 * buf.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del buf
+    binding.mn_probe_mfma(2000, st)
+    e0.record()
+    flop = binding.mn_probe_mfma(100000, st)      # about 40 ms: long enough for the clocks to settle
+    e1.record()
+    torch.cuda.synchronize()
+    mfma = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    return {"hbm_stream_read_GBps": hbm, "mfma_f16_dense_TFLOPs": mfma,
+            "note": "measured on this box by mn_probe_stream_read / mn_probe_mfma; the roofline peaks above are the published ones"}
+
+
+def attention_only(args, wl):
+    """Workload 4: the paged multi-query attention of one layer at its own shape (no model around it).
+    One JSON line: KV bytes streamed per second by attn_mfma_kernel + attn_merge_kernel."""
+    import numpy as np
+    import torch
+    from paper_2402_15678_amd import binding, harness, synth
+    dev = torch.device("cuda:0")
+    desc = wl.desc
+    ctx = synth.draw_ctx_lens(wl)
+    ks = synth.draw_spec_lens(wl)
+    B = wl.batch
+    total = ctx + ks + 1
+    M = int((ks + 1).sum())
+    tiny = synth.ModelDesc(desc.arch, desc.dtype, 1, 128, desc.n_heads, desc.n_kv_heads, desc.head_dim, 128, 8, desc.max_pos + 64)
+    model = harness.DeviceModel.from_host(tiny, synth.make_weights(tiny, wl.seed))
+    kvd = harness.DeviceKV.random_on_device(desc, ctx, ks, wl.seed, wl.block_size)
+    q = torch.randn((M, desc.n_heads, desc.head_dim), device=dev, dtype=torch.float16)
+    out = torch.empty((M, desc.n_heads * desc.head_dim), device=dev, dtype=torch.float16)
+    max_ctx = int(total.max())
+    wsb = binding.mn_workspace_bytes(model.ctx, B, M, max_ctx)
+    ws = torch.empty((wsb,), dtype=torch.uint8, device=dev)
+    spec = torch.tensor(ks, dtype=torch.int32, device=dev)
+    hs = binding.host_i32(ks.tolist())
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+
+    def step():
+        binding.mn_attention(model.ctx, q.data_ptr(), spec.data_ptr(), hs, B, max_ctx, kvd.c, 0, out.data_ptr(),
+                             ws.data_ptr(), wsb, status.data_ptr(), harness.stream_ptr())
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    assert status.item() == 0
+    binding.mn_profile_enable(model.ctx, True)
+    for _ in range(max(1, args.profile_steps)):
+        step()
+    torch.cuda.synchronize()
+    prof = binding.mn_profile_collect(model.ctx)
+    binding.mn_profile_enable(model.ctx, False)
+    att_ms = prof["attention"][0] / max(1, prof["attention"][1])      # attention + merge, per call
+    kv_bytes = float(total.astype(np.int64).sum()) * 2 * desc.n_kv_heads * desc.head_dim * 2
+    achieved = kv_bytes / (att_ms * 1e-3) / 1e9
+    flops = 4.0 * desc.n_heads * desc.head_dim * float(((ks + 1).astype(np.int64) * total).sum())
+    out_line = {
+        "metric": "attention_kv_stream", "value": achieved, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "storage_dtype": "bf16", "accumulate_dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "batch": B, "rows": M, "ctx_min": int(ctx.min()), "ctx_max": int(ctx.max()),
+                   "heads": desc.n_heads, "kv_heads": desc.n_kv_heads, "head_dim": desc.head_dim,
+                   "block_size": wl.block_size, "seed": wl.seed},
+        "note": "ms_per_step is one mn_attention call (row bookkeeping kernel + attention + merge); the roofline "
+                "covers the attention and merge kernels, timed by the library's event taps",
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_launch": kv_bytes,
+                     "kernel": "attn_mfma_kernel + attn_merge_kernel", "avg_launch_us": att_ms * 1e3,
+                     "mfma_tflops": flops / (att_ms * 1e-3) / 1e12,
+                     "mfma_frac": flops / (att_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS},
+        "ceilings": measure_ceilings(torch, binding, harness),
+        "cpu_baseline": None,
+    }
+    print(json.dumps(out_line))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -116,6 +210,9 @@ def main():
     from paper_2402_15678_amd import binding, harness, synth
 
     wl = synth.WORKLOADS[args.workload]
+    if wl.desc is synth.LLAMA2_70B_ATTN:
+        attention_only(args, wl)
+        return
     desc = wl.desc if args.layers <= 0 else wl.desc.with_layers(args.layers)
     dev = torch.device("cuda:0")
     t_setup = time.perf_counter()
@@ -255,7 +352,8 @@ def main():
         "setup_s": t_setup,
         "after_step": {"acr_update_us": acr_us, "acr": [None if x != x else x for x in acr_buf.cpu().tolist()],
                        "selector_observe_ns_incl_binding": sel_ns},
-        "roofline": roofline, "kernel_families": families, "cpu_baseline": cpu,
+        "roofline": roofline, "kernel_families": families,
+        "ceilings": measure_ceilings(torch, binding, harness), "cpu_baseline": cpu,
     }
     print(json.dumps(out))
 

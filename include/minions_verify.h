@@ -137,8 +137,10 @@ size_t mn_workspace_bytes(const mn_ctx *ctx, int B, int max_rows, int max_ctx);
 /* ---- weight packing (bf16 models) ---------------------------------------------------------------
  * HBM streams near its peak only over long contiguous runs, so the projection kernel reads its
  * weights pre-tiled: blocks of 128 output columns x 128 inputs, 32 KB each, consecutive along k for
- * one column block, every 1 KB inside in the order the MFMA lanes consume it.  Columns are padded
- * with zeros to a multiple of 128. */
+ * one column block, every 1 KB inside in the order the MFMA lanes consume it, every value re-encoded
+ * from bf16 to the fp16 the MFMA multiplies (still two bytes; exact for magnitudes in [2^-14, 65504],
+ * smaller ones truncated to the fp16 subnormal grid, an absolute error below 2^-24).  Columns are
+ * padded with zeros to a multiple of 128.  The packed form is private to this library version. */
 
 /* Bytes of the packed form of an [N][K] bf16 matrix (K a multiple of 128).  0 on invalid arguments. */
 size_t mn_packed_weight_bytes(int N, int K);
@@ -181,8 +183,10 @@ mn_status mn_mv_vote(mn_ctx *ctx, const int32_t *drafts, const int32_t *spec_len
  *   logits     dev [sum_b q_b][vocab] fp32 (out), rows packed in sequence order, or NULL
  *   workspace  dev, >= mn_workspace_bytes(ctx, B, sum_b q_b, max_ctx), 256-byte aligned
  * Arithmetic: fp32 residual stream, norm statistics, softmax and logits in both storage types.
- * With MN_DT_BF16 the weights and cache entries are bf16 in memory and are widened exactly to
- * fp16 in registers; the activations fed to the matrix products (norm outputs, queries, softmax
+ * With MN_DT_BF16 the weights are given as bf16 and re-encoded as fp16 by mn_pack_weight (same 16 bits
+ * per parameter; exact for magnitudes in [2^-14, 65504], the range weights live in), cache entries
+ * are bf16 in memory and are widened exactly to fp16 on their way to the MFMA; the activations fed to
+ * the matrix products (norm outputs, queries, softmax
  * probabilities, attention outputs, FFN activations) are rounded to fp16 (round-to-nearest-even)
  * and the products run on the fp16 MFMA with fp32 accumulation.  New K/V rows are rounded to
  * bf16 when they are written to the cache. */
@@ -246,11 +250,21 @@ mn_status mn_selector_observe(mn_selector *sel, double t_llm, double vl, int *s_
 int mn_selector_current(const mn_selector *sel);   /* -1 when sel is NULL */
 long mn_selector_adjustments(const mn_selector *sel); /* decisions taken so far; -1 when sel is NULL */
 
+/* ---- measuring sticks (no part of the method) ---------------------------------------------------
+ * For callers who cannot bring their own microbenchmarks: what a plain streaming read and a dense fp16
+ * MFMA loop sustain on the chip at hand, to read the roofline fractions against.  The caller times the
+ * launches (events on `stream`).
+ * mn_probe_stream_read: one pass over buf (dev, 16-byte aligned, >= 1 MiB; bytes / time = read rate).
+ * mn_probe_mfma: every SIMD runs iters x 32 independent 16x16x32 fp16 MFMAs on two waves; *flop (HOST,
+ * may be NULL) receives the floating-point operations of the launch. */
+mn_status mn_probe_stream_read(const void *buf, size_t bytes, void *stream);
+mn_status mn_probe_mfma(int iters, double *flop, void *stream);
+
 /* ---- component entry points (the kernels mn_verify_forward is made of, at their own shapes) -- */
 
 /* The projection GEMM of a bf16 model: out[m][n] = sum_k a[m][k] * w[n][k] (+ bias[n]).
  * a dev [M][K] fp16 (the activation type of bf16 models), w dev: the [N][K] bf16 matrix in packed
- * layout (mn_pack_weight with interleave_half = 0; widened exactly to fp16 in registers),
+ * layout (mn_pack_weight with interleave_half = 0, which also re-encodes the values as fp16),
  * fp16 MFMA with fp32 accumulation, bias dev [N] fp32 or NULL, out dev [M][N]
  * fp32.  split_k in [0, MN_MAX_SPLIT_K]: 0 lets the library choose; with split_k > 1 `workspace`
  * (dev, >= split_k*M*N*4 bytes, 256-byte aligned) holds the partial sums, which are added in a

@@ -24,7 +24,7 @@ EXPORTS = ("mn_create", "mn_destroy", "mn_last_error", "mn_status_str", "mn_work
            "mn_verify_forward", "mn_accept_and_commit", "mn_proj_gemm", "mn_attention", "mn_profile_enable",
            "mn_profile_collect", "mn_packed_weight_bytes", "mn_pack_weight", "mn_acr_update",
            "mn_selector_create", "mn_selector_destroy", "mn_selector_observe", "mn_selector_current",
-           "mn_selector_adjustments")
+           "mn_selector_adjustments", "mn_probe_stream_read", "mn_probe_mfma")
 PROF_KINDS = ("prepare", "norm", "gemm", "rope_append", "attention", "act", "argmax", "vote", "accept")
 
 
@@ -91,6 +91,10 @@ def _load() -> C.CDLL:
     lib.mn_selector_current.argtypes = [vp]
     lib.mn_selector_adjustments.restype = C.c_long
     lib.mn_selector_adjustments.argtypes = [vp]
+    lib.mn_probe_stream_read.restype = i32
+    lib.mn_probe_stream_read.argtypes = [vp, sz, vp]
+    lib.mn_probe_mfma.restype = i32
+    lib.mn_probe_mfma.argtypes = [i32, C.POINTER(C.c_double), vp]
     lib.mn_profile_enable.restype = i32
     lib.mn_profile_enable.argtypes = [vp, i32]
     lib.mn_profile_collect.restype = i32
@@ -217,3 +221,14 @@ def mn_selector_current(sel: int) -> int:
 
 def mn_selector_adjustments(sel: int) -> int:
     return int(lib.mn_selector_adjustments(sel))
+
+
+def mn_probe_stream_read(buf, nbytes: int, stream=None) -> None:
+    _check(lib.mn_probe_stream_read(buf, nbytes, stream), None)
+
+
+def mn_probe_mfma(iters: int, stream=None) -> float:
+    """Launches the MFMA loop; returns the floating-point operations of the launch."""
+    flop = C.c_double()
+    _check(lib.mn_probe_mfma(iters, C.byref(flop), stream), None)
+    return flop.value

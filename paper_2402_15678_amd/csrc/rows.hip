@@ -13,6 +13,7 @@ namespace mn {
 __global__ void __launch_bounds__(256) prepare_kernel(PrepArgs a) {
   __shared__ int32_t s_row0[MN_MAX_BATCH + 1];
   __shared__ int32_t s_ok[MN_MAX_BATCH];
+  __shared__ int32_t s_nb[MN_MAX_BATCH];  // blocks each sequence needs mapped (0: nothing to check)
   __shared__ int s_bad;
   const int tid = threadIdx.x;
   if (tid == 0) s_bad = 0;
@@ -23,30 +24,44 @@ __global__ void __launch_bounds__(256) prepare_kernel(PrepArgs a) {
     const int ctx = a.ctx_lens[b];
     int ok = 1;
     int flags = 0;
+    int nb = 0;
     if (k < 0 || k > a.k_max) { ok = 0; flags |= MN_DEV_SPEC_LEN; }
     s_row0[b + 1] = (k < 0 || k > a.k_max) ? 1 : k + 1;
     if (ok) {
       const long need = (long)ctx + k + 1;
       if (ctx < 0 || need > (long)a.max_blocks_per_seq * a.block_size) { ok = 0; flags |= MN_DEV_BLOCK_TABLE; }
       if (ok && need > a.max_pos) { ok = 0; flags |= MN_DEV_TOKEN; }
-      if (ok) {
-        const int nb = (int)((need + a.block_size - 1) / a.block_size);
-        for (int i = 0; i < nb; ++i) {
-          const int pb = a.block_tables[(size_t)b * a.max_blocks_per_seq + i];
-          if (pb < 0 || pb >= a.num_blocks) { ok = 0; flags |= MN_DEV_BLOCK_TABLE; break; }
-        }
-      }
-      if (ok && a.last_tok) {
-        for (int j = 0; j <= k; ++j) {
-          const int tok = (j == 0) ? a.last_tok[b] : a.voted[(size_t)b * a.k_max + j - 1];
-          if (tok < 0 || tok >= a.vocab) { ok = 0; flags |= MN_DEV_TOKEN; break; }
-        }
-      }
+      if (ok) nb = (int)((need + a.block_size - 1) / a.block_size);
     }
     s_ok[b] = ok;
+    s_nb[b] = ok ? nb : 0;
     if (flags) {
       if (a.dev_status) atomicOr(a.dev_status, flags);
       if (flags & MN_DEV_SPEC_LEN) atomicOr(&s_bad, 1);
+    }
+  }
+  __syncthreads();
+  // pass 1b: every mapped block of every sequence, all threads side by side (a long context has
+  // hundreds of table entries; one thread walking them is a chain of dependent loads)
+  for (long idx = tid; idx < (long)a.B * a.max_blocks_per_seq; idx += blockDim.x) {
+    const int b = (int)(idx / a.max_blocks_per_seq), i = (int)(idx % a.max_blocks_per_seq);
+    if (i >= s_nb[b]) continue;
+    const int pb = a.block_tables[idx];
+    if (pb < 0 || pb >= a.num_blocks) {
+      atomicAnd(&s_ok[b], 0);
+      if (a.dev_status) atomicOr(a.dev_status, MN_DEV_BLOCK_TABLE);
+    }
+  }
+  // pass 1c: every input token of every sequence that passed the shape checks, likewise
+  if (a.last_tok) {
+    for (long idx = tid; idx < (long)a.B * (a.k_max + 1); idx += blockDim.x) {
+      const int b = (int)(idx / (a.k_max + 1)), j = (int)(idx % (a.k_max + 1));
+      if (s_nb[b] == 0 || j >= s_row0[b + 1]) continue;  // (s_row0[b+1] still holds q_b = k_b + 1 here)
+      const int tok = (j == 0) ? a.last_tok[b] : a.voted[(size_t)b * a.k_max + j - 1];
+      if (tok < 0 || tok >= a.vocab) {
+        atomicAnd(&s_ok[b], 0);
+        if (a.dev_status) atomicOr(a.dev_status, MN_DEV_TOKEN);
+      }
     }
   }
   __syncthreads();
