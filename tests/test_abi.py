@@ -105,4 +105,18 @@ def test_step_calls_reject_bad_arguments_before_launch(binding):
     assert binding.mn_packed_weight_bytes(130, 100) == 0
     with pytest.raises(binding.MinionsError):
         binding.mn_pack_weight(p, 0x2000, 64, 256, 48)                          # N != 2 * half
+    # the rows after the step and the measuring sticks: argument checks come before any launch
+    for bad in [dict(B=-1), dict(n=0), dict(n=65), dict(rf=0.0), dict(pt=0.9, rt=0.1), dict(w=None)]:
+        a = dict(B=2, n=3, rt=0.8, pt=0.2, rf=1.5, pf=0.5, w=p)
+        a.update(bad)
+        with pytest.raises(binding.MinionsError):
+            binding.mn_acr_update(ctx, p, p, p, None, a["B"], a["n"], a["rt"], a["pt"], a["rf"], a["pf"], a["w"])
+    with pytest.raises(binding.MinionsError):
+        binding.mn_acr_update(ctx, None, p, p, None, 2, 3, 0.8, 0.2, 1.5, 0.5, p)   # B > 0 needs the arrays
+    for buf, nbytes in [(None, 1 << 24), (p, 1 << 10), (p + 8, 1 << 24)]:
+        with pytest.raises(binding.MinionsError):
+            binding.mn_probe_stream_read(buf, nbytes)
+    for iters in (0, -3, 1 << 23):
+        with pytest.raises(binding.MinionsError):
+            binding.mn_probe_mfma(iters)
     binding.mn_destroy(ctx)

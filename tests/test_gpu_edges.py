@@ -155,3 +155,26 @@ def test_device_detected_errors_disable_only_the_bad_sequence(env):
     torch.cuda.synchronize()
     assert ses4.dev_status.item() & binding.MN_DEV_SPEC_LEN
     assert (ses4.greedy.cpu().numpy() == -1).all() and torch.equal(kvd4.k_pages[0], before4)
+
+
+def test_measuring_sticks_run_and_report_plausible_rates(env):
+    """The two probes behind the ABI: they launch, finish, and land in the range of a working MI355X
+    (loose bounds: they are a ruler for the bench, not a performance test)."""
+    harness, binding = env[0], env[1]
+    buf = torch.empty((1 << 28,), dtype=torch.uint8, device="cuda:0").fill_(1)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    binding.mn_probe_stream_read(buf.data_ptr(), buf.numel(), harness.stream_ptr())
+    e0.record()
+    for _ in range(5):
+        binding.mn_probe_stream_read(buf.data_ptr(), buf.numel(), harness.stream_ptr())
+    e1.record()
+    torch.cuda.synchronize()
+    gbps = 5.0 * buf.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    assert 1000.0 < gbps < 8000.0, gbps
+    binding.mn_probe_mfma(100, harness.stream_ptr())
+    e0.record()
+    flop = binding.mn_probe_mfma(4000, harness.stream_ptr())
+    e1.record()
+    torch.cuda.synchronize()
+    tflops = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    assert 300.0 < tflops < 2600.0, tflops
