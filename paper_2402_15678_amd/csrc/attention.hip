@@ -158,22 +158,6 @@ constexpr float LAZY_MAX = 6.f;                // the reference moves when a sco
 
 __device__ __forceinline__ float max3(float x, float y, float z) { return __builtin_fmaxf(__builtin_fmaxf(x, y), z); }
 
-// 64 lanes x 16 bytes, global (g + OFFSET) -> LDS at lds_base + 16 * lane.  The instruction adds its
-// immediate offset to BOTH addresses, so the LDS base handed to it is lowered by the same amount.  The load
-// is invisible to the compiler's wait-count bookkeeping: the kernel waits for these loads itself
-// (att_wait_vm) and issues no other memory load while one of them may still be needed.
-template <int OFFSET>
-__device__ __forceinline__ void dma16(const char* g, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off offset:%2" ::"v"(g), "s"(lds_base - (uint32_t)OFFSET), "n"(OFFSET) : "memory");
-}
-// wait until at most N of this wave's memory loads are outstanding (they complete in order)
-template <int N>
-__device__ __forceinline__ void att_wait_vm() {
-  asm volatile("" ::: "memory");
-  __builtin_amdgcn_s_waitcnt(((N & 15) | ((N >> 4) << 14)) | (7 << 4) | (15 << 8));
-  asm volatile("" ::: "memory");
-}
-
 // Online-softmax step of one column tile on one key tile.  S0/S1: scores of keys 8g+0..3 / 8g+4..7 of
 // this lane's query row, already minus the reference (negm4 = -reference in all four elements, 0 while
 // nothing was seen).  Returns the probabilities as the B operand of the second product.
@@ -350,7 +334,7 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_spl
     MN_ATT_DMA(0, 0)
     MN_ATT_DMA(1, 1)
     MN_ATT_DMA(2, 2)
-    att_wait_vm<8>();
+    wait_vm<8>();
     {
       u32x4 raw[4];
       f16x8 w[4];
@@ -379,7 +363,7 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_spl
         for (int u = 0; u < 8; ++u) vf[u] = *reinterpret_cast<const f16x8*>(s_kv + cur * TILE_HALFS + ((8 + u) * 64 + lane) * 8);
       }
       f16_t* const np = my_piece + nxt * TILE_HALFS;
-      att_wait_vm<8>();  // tile i+1 has landed (tiles i+2 and i+3 may be in flight)
+      wait_vm<8>();  // tile i+1 has landed (tiles i+2 and i+3 may be in flight)
       u32x4 raw[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) raw[j] = *reinterpret_cast<const u32x4*>(np + j * 4 * 512);
@@ -454,7 +438,7 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_spl
         }
       }
     }
-    att_wait_vm<0>();  // the loads of the tiles past the end must land before the LDS is given back
+    wait_vm<0>();  // the loads of the tiles past the end must land before the LDS is given back
 #undef MN_ATT_DMA
   }
 

@@ -88,6 +88,22 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return t;
 }
 
+// 64 lanes x 16 bytes, global (g + OFFSET) -> LDS at lds_base + 16 * lane.  The instruction adds its
+// immediate offset to BOTH addresses, so the LDS base handed to it is lowered by the same amount.  The load
+// is invisible to the compiler's wait-count bookkeeping: the kernel waits for these loads itself
+// (wait_vm) and issues no other memory load while one of them may still be needed.
+template <int OFFSET>
+__device__ __forceinline__ void dma16(const char* g, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off offset:%2" ::"v"(g), "s"(lds_base - (uint32_t)OFFSET), "n"(OFFSET) : "memory");
+}
+// wait until at most N of this wave's memory loads are outstanding (they complete in order)
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(((N & 15) | ((N >> 4) << 14)) | (7 << 4) | (15 << 8));
+  asm volatile("" ::: "memory");
+}
+
 // ---- per-row metadata produced by the prepare kernel ----
 struct RowInfo {
   const int32_t* row_seq;   // [M] sequence of row m

@@ -267,6 +267,186 @@ __global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) ge
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Many rows (M > 144): the MFMA-bound regime.  Both operands go through LDS.
+// ------------------------------------------------------------------------------------------
+// Workgroup = 8 waves (one per CU, two per SIMD) on a tile of 32*AT rows x 256 columns: wave (wm, wn)
+// owns AT x 4 tiles of 16 x 16 (16*AT rows x 64 columns: 4*AT accumulator registers per tile row), so one
+// k-step of 32 costs it AT + 4 fragment reads (1 KB each) for 4*AT MFMAs: with the weights streamed to
+// registers instead, a wave cannot hold more than one iteration of lead once the accumulators take
+// 100+ registers, and the counters showed it waiting for memory two thirds of its life.
+// Everything arrives by direct global->LDS loads (no staging registers), one barrier per k-step:
+//  * weights: a k-step is 16 column tiles x 1 KB, contiguous in the packed layout, landing as they are
+//    in a ring of four stages, three k-steps ahead;
+//  * activations: blocks of 64 k (32*AT rows x 128 bytes: whole cache lines; 64-byte row pieces cost the
+//    L2 twice the requests), double-buffered, one block (two k-steps) ahead.  A load instruction brings
+//    8 rows; the eight 16-byte pieces of row r are exchanged by XOR with (r/2) mod 8, which makes the
+//    operand reads (16 rows x one piece per quarter wave) as fast as contiguous ones (measured).
+// Loads complete in order, so "at most n outstanding" names exactly which have landed: the waits below
+// count the loads issued after the ones needed next.
+// Grid: as for the streaming kernel with several row chunks: the row blocks of one (column group, split)
+// pair sit on consecutive slots of the same XCD and share the weights through its L2.
+constexpr int BIG_NST = 4;                 // weight stages in LDS
+constexpr int BIG_W_BYTES = 16 * 1024;     // 16 column tiles x 1 KB per k-step
+
+template <int AT, int EPI>
+__global__ void __launch_bounds__(512, 1) gemm_big_kernel(const f16_t* __restrict__ A, const bf16_t* __restrict__ W,
+                                                          void* __restrict__ out_, const float* __restrict__ bias, int M,
+                                                          int N, int K, int k_per_split, int m_chunks, int gx,
+                                                          int n_split) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  constexpr int A_TILE = 32 * AT * 128;                  // one 64-k block of activations
+  constexpr int W_BASE = 2 * A_TILE;
+  constexpr int UA = (4 * AT) / 8;                       // activation loads per wave and block (8 rows each)
+  constexpr int UW = 2;                                  // weight loads per wave and k-step
+  static_assert((4 * AT) % 8 == 0, "row tiles per wave must be even");
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, g = lane >> 4;
+  const int wm = wave >> 2, wn = wave & 3;
+  const int id = blockIdx.x, xcd = id & 7, slot = id >> 3;
+  const int pair = (slot / m_chunks) * 8 + xcd;
+  if (pair >= gx * n_split) return;  // (whole workgroup)
+  const int bz = slot % m_chunks, bx = pair % gx, split = pair / gx;
+  const int nblk_all = (N + NWG - 1) / NWG;
+  const int m0 = bz * (32 * AT);
+  const int k_begin = split * k_per_split;
+  const int k_end = min(K, k_begin + k_per_split);
+  const int n_stage = (k_end - k_begin) / KSTEP;         // a multiple of 4 (splits are cut at 128 k)
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem);
+
+  // ---- loader role of this lane ----
+  const char* a_src[UA];     // activation piece at block 0
+  const char* w_src[UW];     // weight piece at k-step 0
+#pragma unroll
+  for (int j = 0; j < UA; ++j) {
+    const int c = wave * UA + j;                         // 8-row chunk of the tile
+    const int row = m0 + 8 * c + (lane >> 3);
+    const int piece = (lane & 7) ^ (4 * (c & 1) + (lane >> 4));  // key = ((row mod 16) / 2)
+    a_src[j] = reinterpret_cast<const char*>(A + (size_t)min(row, M - 1) * K + k_begin + 8 * piece);
+  }
+#pragma unroll
+  for (int j = 0; j < UW; ++j) {
+    const int wt = wave * UW + j;                        // column tile of the 256-column group
+    const int nblk = min(bx * 2 + (wt >> 3), nblk_all - 1);
+    w_src[j] = reinterpret_cast<const char*>(W + ((size_t)nblk * (K / KB) + k_begin / KB) * (size_t)WBLOCK +
+                                             (size_t)(wt & 7) * (KS * 512) + lane * 8);
+  }
+  const int last_stage = n_stage - 1, last_blk = (n_stage >> 1) - 1;
+  // block JB of the split -> activation buffer JB % 2; k-step ST -> weight stage ST % 4 (past the end: repeats)
+#define MN_BIG_DMA_A(JB)                                                                                    \
+  {                                                                                                         \
+    const size_t off_ = (size_t)min((JB), last_blk) * (2 * KSTEP * sizeof(f16_t));                          \
+    const uint32_t base_ = lds0 + (uint32_t)((JB) & 1) * A_TILE + (uint32_t)(wave * UA) * 1024u;            \
+    _Pragma("unroll") for (int j = 0; j < UA; ++j)                                                          \
+      dma16<0>(a_src[j] + off_, __builtin_amdgcn_readfirstlane(base_ + (uint32_t)j * 1024u));               \
+  }
+#define MN_BIG_DMA_W(ST)                                                                                    \
+  {                                                                                                         \
+    const int st_ = min((ST), last_stage);                                                                  \
+    const size_t off_ = ((size_t)(st_ >> 2) * WBLOCK + (size_t)(st_ & 3) * 512) * sizeof(bf16_t);           \
+    const uint32_t base_ = lds0 + W_BASE + (uint32_t)((ST) & (BIG_NST - 1)) * BIG_W_BYTES + (uint32_t)(wave * UW) * 1024u; \
+    _Pragma("unroll") for (int j = 0; j < UW; ++j)                                                          \
+      dma16<0>(w_src[j] + off_, __builtin_amdgcn_readfirstlane(base_ + (uint32_t)j * 1024u));               \
+  }
+
+  f32x4 acc[AT][4];
+#pragma unroll
+  for (int a = 0; a < AT; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) acc[a][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  if (n_stage > 0) {  // (uniform per workgroup)
+    const uint32_t a_row = (uint32_t)(wm * AT) * 2048u + (uint32_t)l16 * 128u;
+    const uint32_t key = (uint32_t)(l16 >> 1) & 7u;
+    const uint32_t a_rd0 = a_row + ((uint32_t)g ^ key) * 16u;          // first k-step of a block
+    const uint32_t a_rd1 = a_row + ((uint32_t)(4 + g) ^ key) * 16u;    // second
+    const uint32_t w_rd = (uint32_t)W_BASE + (uint32_t)(wn * 4) * 1024u + (uint32_t)lane * 16u;
+    // one k-step on the MFMAs: activation buffer ABUF, its half HALF, weight stage WST
+#define MN_BIG_STEP(ABUF, HALF, WST)                                                                        \
+  {                                                                                                         \
+    const unsigned char* sa_ = smem + (ABUF) * A_TILE + ((HALF) ? a_rd1 : a_rd0);                           \
+    const unsigned char* sw_ = smem + w_rd + (WST) * BIG_W_BYTES;                                           \
+    f16x8 wf[4], af[AT];                                                                                    \
+    _Pragma("unroll") for (int b = 0; b < 4; ++b) wf[b] = *reinterpret_cast<const f16x8*>(sw_ + b * 1024);  \
+    _Pragma("unroll") for (int a = 0; a < AT; ++a) af[a] = *reinterpret_cast<const f16x8*>(sa_ + a * 2048); \
+    _Pragma("unroll") for (int a = 0; a < AT; ++a)                                                          \
+      _Pragma("unroll") for (int b = 0; b < 4; ++b)                                                         \
+        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[b], af[a], acc[a][b], 0, 0, 0);               \
+  }
+    // issue order (per wave): A(0) W(0) W(1) W(2) | even k-step st: A(st/2+1) W(st+3) | odd: W(st+3) | ...
+    MN_BIG_DMA_A(0)
+    MN_BIG_DMA_W(0)
+    MN_BIG_DMA_W(1)
+    MN_BIG_DMA_W(2)
+    wait_vm<2 * UW>();  // A(0), W(0) landed; W(1), W(2) may be in flight
+    __syncthreads();
+    for (int st = 0; st < n_stage; st += 2) {
+      const int jb = st >> 1;
+      // even k-step: the other activation buffer was last read before the previous barrier
+      MN_BIG_DMA_A(jb + 1)
+      MN_BIG_DMA_W(st + 3)
+      MN_BIG_STEP(jb & 1, 0, st & 3)
+      wait_vm<UA + 2 * UW>();  // W(st+1) landed; W(st+2), A(jb+1), W(st+3) may be in flight
+      __syncthreads();
+      // odd k-step
+      MN_BIG_DMA_W(st + 4)
+      MN_BIG_STEP(jb & 1, 1, (st + 1) & 3)
+      wait_vm<2 * UW>();       // W(st+2) and A(jb+1) landed; W(st+3), W(st+4) may be in flight
+      __syncthreads();
+    }
+    wait_vm<0>();  // the repeats past the end must land before the LDS is given back
+#undef MN_BIG_STEP
+  }
+#undef MN_BIG_DMA_A
+#undef MN_BIG_DMA_W
+
+  // epilogue: lane holds D[n = 16*(wn*4 + b) + 4g + i][m = 16*(wm*AT + a) + l16] of the workgroup tile
+  const int n_wg = bx * 256;
+  if constexpr (EPI == EPI_SWIGLU) {
+    f16_t* act = reinterpret_cast<f16_t*>(out_);
+    const int F = N >> 1;
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) {
+      const int f = (bx * 8 + wn * 2 + pr) * 16 + g * 4;
+#pragma unroll
+      for (int a = 0; a < AT; ++a) {
+        const int m = m0 + (wm * AT + a) * 16 + l16;
+        if (m >= M || f >= F) continue;
+        const f32x4 gt = acc[a][2 * pr], up = acc[a][2 * pr + 1];
+        float r[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = gt[i] / (1.f + __expf(-gt[i])) * up[i];
+        *reinterpret_cast<uint2*>(act + (size_t)m * F + f) = make_uint2(pack2h(r[0], r[1]), pack2h(r[2], r[3]));
+      }
+    }
+  } else {
+    float* o = reinterpret_cast<float*>(out_) + (size_t)split * M * N;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const int n = n_wg + (wn * 4 + b) * 16 + g * 4;
+#pragma unroll
+      for (int a = 0; a < AT; ++a) {
+        const int m = m0 + (wm * AT + a) * 16 + l16;
+        if (m >= M || n >= N) continue;
+        f32x4 v = acc[a][b];
+        if (bias && split == 0) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (n + i < N) v[i] += bias[n + i];
+        }
+        float* p = o + (size_t)m * N + n;
+        if (n + 3 < N && (N & 3) == 0) {
+          *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (n + i < N) p[i] = v[i];
+        }
+      }
+    }
+  }
+}
+
 // Row-major [N][K] bf16 -> the packed layout described at the top.  One thread per 16-byte piece.
 // With half > 0 (Llama gate||up, N = 2*half) packed column tile 2t holds gate rows [16t, 16t+16)
 // and tile 2t+1 the up rows half + [16t, 16t+16).
@@ -391,6 +571,17 @@ static GemmPlan gemm_plan(int M, int N, int K, int forced_split) {
     return (iters + per - 1) / per;
   };
   GemmPlan best{4, 1};
+  if (M > 144) {  // big-tile kernel: 256-column groups x row blocks, one workgroup per CU
+    const int gx = (slices / 4 + 1) / 2;
+    int rb = 1 << 30;
+    for (int at : {10, 8, 6}) rb = min(rb, (M + 32 * at - 1) / (32 * at) * at);  // (rows padded least; see big_at)
+    int blocks = 1;
+    for (int at : {10, 8, 6})
+      if ((M + 32 * at - 1) / (32 * at) * at == rb) { blocks = (M + 32 * at - 1) / (32 * at); break; }
+    best.nw = 8;
+    best.split = splits_for(gx * blocks, tune().target / 2);
+    return best;
+  }
   if (M <= 96) {  // up to six row tiles: 4-wave workgroups, two per CU
     best.split = splits_for((slices + 3) / 4, tune().target);
     return best;
@@ -437,6 +628,41 @@ static void launch_bf16_mt(const GemmArgs& a, int m_chunks, hipStream_t st) {
     gemm_w16_kernel<MT, NTW, EPI_PARTIAL, NW, RD><<<grid, NW * 64, 0, st>>>(A, W, a.out, a.bias, a.M, a.N, a.K, per * KB, m_chunks, gx, a.split_k);
 }
 
+// rows per workgroup of the big-tile kernel: the AT (row tiles per wave, two waves deep) that pads M least
+static int big_at(int M) {
+  int best = 10, best_rows = 1 << 30;
+  for (int at : {10, 8, 6}) {
+    const int rb = (M + 32 * at - 1) / (32 * at);
+    if (rb * 32 * at < best_rows) {
+      best_rows = rb * 32 * at;
+      best = at;
+    }
+  }
+  return best;
+}
+
+template <int AT>
+static void launch_big(const GemmArgs& a, hipStream_t st) {
+  const int iters = a.K / KB;
+  const int per = (iters + a.split_k - 1) / a.split_k;  // 128-k blocks per split
+  const int gx = ((a.N + NWG - 1) / NWG + 1) / 2;       // 256-column groups
+  const int rb = (a.M + 32 * AT - 1) / (32 * AT);
+  const dim3 grid(((gx * a.split_k + 7) / 8) * 8 * rb, 1, 1);
+  const size_t smem = (size_t)2 * 32 * AT * 128 + (size_t)BIG_NST * BIG_W_BYTES;
+  const f16_t* A = reinterpret_cast<const f16_t*>(a.a);
+  const bf16_t* W = reinterpret_cast<const bf16_t*>(a.w);
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_big_kernel<AT, EPI_PARTIAL>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_big_kernel<AT, EPI_SWIGLU>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    attr_set = true;
+  }
+  if (a.swiglu_act)
+    gemm_big_kernel<AT, EPI_SWIGLU><<<grid, 512, smem, st>>>(A, W, a.swiglu_act, nullptr, a.M, a.N, a.K, per * KB, rb, gx, a.split_k);
+  else
+    gemm_big_kernel<AT, EPI_PARTIAL><<<grid, 512, smem, st>>>(A, W, a.out, a.bias, a.M, a.N, a.K, per * KB, rb, gx, a.split_k);
+}
+
 void launch_gemm(const GemmArgs& a, hipStream_t st) {
   if (a.M <= 0 || a.N <= 0) return;
   if (a.dtype != MN_DT_BF16) {
@@ -461,7 +687,21 @@ void launch_gemm(const GemmArgs& a, hipStream_t st) {
       default: launch_bf16_mt<9, 4>(a, 1, st); break;
     }
   }
-  else launch_bf16_mt<8, 4>(a, (tiles + 7) / 8, st);  // many rows: 128-row chunks, each streaming the weights (from L2 after the first)
+  else {
+    static int big = [] {
+      const char* e = getenv("MN_GEMM_BIG");  // experiment switch: 0 = chunks of the streaming kernel
+      return e ? atoi(e) : 1;
+    }();
+    if (!big) {
+      launch_bf16_mt<8, 4>(a, (tiles + 7) / 8, st);
+    } else {
+      switch (big_at(a.M)) {
+        case 10: launch_big<10>(a, st); break;
+        case 8: launch_big<8>(a, st); break;
+        default: launch_big<6>(a, st); break;
+      }
+    }
+  }
 }
 
 }  // namespace mn
