@@ -361,17 +361,41 @@ __global__ void __launch_bounds__(512, 1) gemm_big_kernel(const f16_t* __restric
     const uint32_t a_rd0 = a_row + ((uint32_t)g ^ key) * 16u;          // first k-step of a block
     const uint32_t a_rd1 = a_row + ((uint32_t)(4 + g) ^ key) * 16u;    // second
     const uint32_t w_rd = (uint32_t)W_BASE + (uint32_t)(wn * 4) * 1024u + (uint32_t)lane * 16u;
-    // one k-step on the MFMAs: activation buffer ABUF, its half HALF, weight stage WST
-#define MN_BIG_STEP(ABUF, HALF, WST)                                                                        \
+    // One k-step.  Its weight fragments and first activation fragment are already in registers (read
+    // right after the barrier that published them, in the middle of the previous k-step), so the MFMAs
+    // start at once while the other activation fragments stream in; half way through, every LDS read of
+    // this k-step has returned, the loads of the next one are waited for, the barrier is taken and the
+    // next k-step's first operands are read: the LDS latency hides behind the second half of the MFMAs.
+    //   ABUF/HALF/WST: activation buffer, its half, weight stage of this k-step; N*: of the next one;
+    //   WAIT: loads that may still be in flight when the next k-step's data must have landed
+    f16x8 wf[4], af0;
+#define MN_BIG_READ_FIRST(ABUF, HALF, WST)                                                                  \
   {                                                                                                         \
-    const unsigned char* sa_ = smem + (ABUF) * A_TILE + ((HALF) ? a_rd1 : a_rd0);                           \
     const unsigned char* sw_ = smem + w_rd + (WST) * BIG_W_BYTES;                                           \
-    f16x8 wf[4], af[AT];                                                                                    \
     _Pragma("unroll") for (int b = 0; b < 4; ++b) wf[b] = *reinterpret_cast<const f16x8*>(sw_ + b * 1024);  \
-    _Pragma("unroll") for (int a = 0; a < AT; ++a) af[a] = *reinterpret_cast<const f16x8*>(sa_ + a * 2048); \
-    _Pragma("unroll") for (int a = 0; a < AT; ++a)                                                          \
+    af0 = *reinterpret_cast<const f16x8*>(smem + (ABUF) * A_TILE + ((HALF) ? a_rd1 : a_rd0));               \
+  }
+#define MN_BIG_STEP(ABUF, HALF, NABUF, NHALF, NWST, WAIT)                                                   \
+  {                                                                                                         \
+    constexpr int H_ = AT / 2;                                                                              \
+    const unsigned char* sa_ = smem + (ABUF) * A_TILE + ((HALF) ? a_rd1 : a_rd0);                           \
+    f16x8 af[AT];                                                                                           \
+    _Pragma("unroll") for (int a = 1; a < AT; ++a) af[a] = *reinterpret_cast<const f16x8*>(sa_ + a * 2048); \
+    _Pragma("unroll") for (int b = 0; b < 4; ++b)                                                           \
+      acc[0][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[b], af0, acc[0][b], 0, 0, 0);                   \
+    _Pragma("unroll") for (int a = 1; a < H_; ++a)                                                          \
       _Pragma("unroll") for (int b = 0; b < 4; ++b)                                                         \
         acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[b], af[a], acc[a][b], 0, 0, 0);               \
+    f16x8 wk_[4];                                                                                           \
+    _Pragma("unroll") for (int b = 0; b < 4; ++b) wk_[b] = wf[b];                                           \
+    __builtin_amdgcn_sched_barrier(0);                                                                      \
+    wait_vm<(WAIT)>();                                                                                      \
+    __syncthreads();                                                                                        \
+    MN_BIG_READ_FIRST(NABUF, NHALF, NWST)                                                                   \
+    __builtin_amdgcn_sched_barrier(0);                                                                      \
+    _Pragma("unroll") for (int a = H_; a < AT; ++a)                                                         \
+      _Pragma("unroll") for (int b = 0; b < 4; ++b)                                                         \
+        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wk_[b], af[a], acc[a][b], 0, 0, 0);              \
   }
     // issue order (per wave): A(0) W(0) W(1) W(2) | even k-step st: A(st/2+1) W(st+3) | odd: W(st+3) | ...
     MN_BIG_DMA_A(0)
@@ -380,22 +404,22 @@ __global__ void __launch_bounds__(512, 1) gemm_big_kernel(const f16_t* __restric
     MN_BIG_DMA_W(2)
     wait_vm<2 * UW>();  // A(0), W(0) landed; W(1), W(2) may be in flight
     __syncthreads();
+    MN_BIG_READ_FIRST(0, 0, 0)
     for (int st = 0; st < n_stage; st += 2) {
       const int jb = st >> 1;
       // even k-step: the other activation buffer was last read before the previous barrier
       MN_BIG_DMA_A(jb + 1)
       MN_BIG_DMA_W(st + 3)
-      MN_BIG_STEP(jb & 1, 0, st & 3)
-      wait_vm<UA + 2 * UW>();  // W(st+1) landed; W(st+2), A(jb+1), W(st+3) may be in flight
-      __syncthreads();
+      // W(st+1) must have landed; W(st+2), A(jb+1), W(st+3) may be in flight
+      MN_BIG_STEP(jb & 1, 0, jb & 1, 1, (st + 1) & 3, UA + 2 * UW)
       // odd k-step
       MN_BIG_DMA_W(st + 4)
-      MN_BIG_STEP(jb & 1, 1, (st + 1) & 3)
-      wait_vm<2 * UW>();       // W(st+2) and A(jb+1) landed; W(st+3), W(st+4) may be in flight
-      __syncthreads();
+      // W(st+2) and A(jb+1) must have landed; W(st+3), W(st+4) may be in flight
+      MN_BIG_STEP(jb & 1, 1, (jb + 1) & 1, 0, (st + 2) & 3, 2 * UW)
     }
     wait_vm<0>();  // the repeats past the end must land before the LDS is given back
 #undef MN_BIG_STEP
+#undef MN_BIG_READ_FIRST
   }
 #undef MN_BIG_DMA_A
 #undef MN_BIG_DMA_W
