@@ -181,10 +181,17 @@ __global__ void __launch_bounds__(NORM_THREADS) norm_kernel(NormArgs a) {
       } else {
         r = *reinterpret_cast<const float4*>(xr + e);
         if (a.partials) {
-          // fixed summation order: residual, then partial 0, 1, ..., then the bias
-          for (int s = 0; s < a.n_partials; ++s) {
-            const float4 p = *reinterpret_cast<const float4*>(a.partials + ((size_t)s * a.M + m) * d + e);
-            r.x += p.x; r.y += p.y; r.z += p.z; r.w += p.w;
+          // fixed summation order: residual, then partial 0, 1, ..., then the bias.  The partials are
+          // fetched eight at a time before any is added (indices past the end repeat the last one and are
+          // not added): one memory round trip per batch instead of one per partial
+          for (int s0 = 0; s0 < a.n_partials; s0 += 8) {
+            float4 p[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+              p[j] = *reinterpret_cast<const float4*>(a.partials + ((size_t)min(s0 + j, a.n_partials - 1) * a.M + m) * d + e);
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+              if (s0 + j < a.n_partials) { r.x += p[j].x; r.y += p[j].y; r.z += p[j].z; r.w += p[j].w; }
           }
         }
         if (a.bias) {
@@ -251,10 +258,18 @@ __global__ void rope_append_kernel(RopeAppendArgs a) {
   const int ncols = (a.H + 2 * a.Hkv) * hd;
   const int c0 = head * hd + t, c1 = c0 + half;
   float v0 = 0.f, v1 = 0.f;
-  for (int s = 0; s < a.n_partials; ++s) {
-    const float* p = a.qkv + ((size_t)s * a.M + m) * ncols;
-    v0 += p[c0];
-    v1 += p[c1];
+  // partials fetched eight at a time before any is added (see norm_kernel); the order of the sum is fixed
+  for (int s0 = 0; s0 < a.n_partials; s0 += 8) {
+    float p0[8], p1[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float* p = a.qkv + ((size_t)min(s0 + j, a.n_partials - 1) * a.M + m) * ncols;
+      p0[j] = p[c0];
+      p1[j] = p[c1];
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (s0 + j < a.n_partials) { v0 += p0[j]; v1 += p1[j]; }
   }
   if (a.bias) { v0 += a.bias[c0]; v1 += a.bias[c1]; }
   const bool is_v = head >= a.H + a.Hkv;
