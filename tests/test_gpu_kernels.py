@@ -105,7 +105,12 @@ def test_accept_commit_bit_exact(hb, B, k_max):
 # ---------------------------------------------------------------------------- GEMM
 @pytest.mark.parametrize("M,N,K,split", [(5, 256, 256, 1), (40, 5120, 5120, 0), (144, 8192, 8192, 0), (144, 1000, 1024, 4),
                                          (17, 50272, 512, 1), (144, 10240, 8192, 2), (200, 3072, 2048, 0),
-                                         (608, 2048, 8192, 0), (1, 64, 128, 1), (144, 8192, 28672, 0), (144, 640, 8192, 16)])
+                                         (608, 2048, 8192, 0), (1, 64, 128, 1), (144, 8192, 28672, 0), (144, 640, 8192, 16),
+                                         # the many-rows kernel: one row past the streaming kernel's limit, exact and
+                                         # ragged row blocks, a column count short of a 256-column group, one k block,
+                                         # forced splits, vocabulary-sized N
+                                         (145, 384, 256, 0), (320, 10240, 512, 0), (321, 130, 128, 1), (700, 1000, 1024, 3),
+                                         (631, 32000, 512, 2), (1024, 512, 2048, 4)])
 def test_proj_gemm_matches_fp64(hb, M, N, K, split):
     harness, binding = hb
     g = synth.stream(79, M, N, K)
