@@ -297,9 +297,9 @@ __global__ void __launch_bounds__(512, 1) gemm_big_kernel(const f16_t* __restric
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   constexpr int A_TILE = 32 * AT * 128;                  // one 64-k block of activations
   constexpr int W_BASE = 2 * A_TILE;
-  constexpr int UA = (4 * AT) / 8;                       // activation loads per wave and block (8 rows each)
+  constexpr int UA = (4 * AT + 7) / 8;                   // activation loads per wave and block (8 rows each; spare
+                                                         // slots of an odd AT repeat the last chunk)
   constexpr int UW = 2;                                  // weight loads per wave and k-step
-  static_assert((4 * AT) % 8 == 0, "row tiles per wave must be even");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
   const int wm = wave >> 2, wn = wave & 3;
@@ -319,7 +319,7 @@ __global__ void __launch_bounds__(512, 1) gemm_big_kernel(const f16_t* __restric
   const char* w_src[UW];     // weight piece at k-step 0
 #pragma unroll
   for (int j = 0; j < UA; ++j) {
-    const int c = wave * UA + j;                         // 8-row chunk of the tile
+    const int c = min(wave * UA + j, 4 * AT - 1);        // 8-row chunk of the tile
     const int row = m0 + 8 * c + (lane >> 3);
     const int piece = (lane & 7) ^ (4 * (c & 1) + (lane >> 4));  // key = ((row mod 16) / 2)
     a_src[j] = reinterpret_cast<const char*>(A + (size_t)min(row, M - 1) * K + k_begin + 8 * piece);
@@ -336,9 +336,9 @@ __global__ void __launch_bounds__(512, 1) gemm_big_kernel(const f16_t* __restric
 #define MN_BIG_DMA_A(JB)                                                                                    \
   {                                                                                                         \
     const size_t off_ = (size_t)min((JB), last_blk) * (2 * KSTEP * sizeof(f16_t));                          \
-    const uint32_t base_ = lds0 + (uint32_t)((JB) & 1) * A_TILE + (uint32_t)(wave * UA) * 1024u;            \
+    const uint32_t base_ = lds0 + (uint32_t)((JB) & 1) * A_TILE;                                            \
     _Pragma("unroll") for (int j = 0; j < UA; ++j)                                                          \
-      dma16<0>(a_src[j] + off_, __builtin_amdgcn_readfirstlane(base_ + (uint32_t)j * 1024u));               \
+      dma16<0>(a_src[j] + off_, __builtin_amdgcn_readfirstlane(base_ + (uint32_t)min(wave * UA + j, 4 * AT - 1) * 1024u)); \
   }
 #define MN_BIG_DMA_W(ST)                                                                                    \
   {                                                                                                         \
@@ -569,6 +569,14 @@ static GemmTune tune() {
   return t;
 }
 
+static int big_min_m() {  // experiment switch: rows from which the big-tile kernel takes over (0: above 144)
+  static int v = [] {
+    const char* e = getenv("MN_GEMM_BIG_MIN_M");
+    return e ? atoi(e) : 0;
+  }();
+  return v;
+}
+
 // Shape of the grid for one projection: waves per workgroup (each wave owns 32 columns; all waves of a
 // workgroup share the activation tile, so more waves mean less L2 -> LDS traffic per weight byte) and
 // k-splits.  Goal: every CU streams (a CU's share of the HBM rate is bounded by what its waves keep in
@@ -595,13 +603,14 @@ static GemmPlan gemm_plan(int M, int N, int K, int forced_split) {
     return (iters + per - 1) / per;
   };
   GemmPlan best{4, 1};
-  if (M > 144) {  // big-tile kernel: 256-column groups x row blocks, one workgroup per CU
+  if (M > 144 || (big_min_m() > 0 && M >= big_min_m())) {  // big-tile kernel: 256-column groups x row blocks, one workgroup per CU
     const int gx = (slices / 4 + 1) / 2;
     int rb = 1 << 30;
     for (int at : {10, 8, 6}) rb = min(rb, (M + 32 * at - 1) / (32 * at) * at);  // (rows padded least; see big_at)
     int blocks = 1;
     for (int at : {10, 8, 6})
       if ((M + 32 * at - 1) / (32 * at) * at == rb) { blocks = (M + 32 * at - 1) / (32 * at); break; }
+    if (M <= 160) blocks = 1;
     best.nw = 8;
     best.split = splits_for(gx * blocks, tune().target / 2);
     return best;
@@ -654,6 +663,7 @@ static void launch_bf16_mt(const GemmArgs& a, int m_chunks, hipStream_t st) {
 
 // rows per workgroup of the big-tile kernel: the AT (row tiles per wave, two waves deep) that pads M least
 static int big_at(int M) {
+  if (M <= 160) return 5;
   int best = 10, best_rows = 1 << 30;
   for (int at : {10, 8, 6}) {
     const int rb = (M + 32 * at - 1) / (32 * at);
@@ -702,7 +712,7 @@ void launch_gemm(const GemmArgs& a, hipStream_t st) {
   else if (tiles <= 3) launch_bf16_mt<3, 4>(a, 1, st);
   else if (tiles <= 4) launch_bf16_mt<4, 4>(a, 1, st);
   else if (tiles <= 6) launch_bf16_mt<6, 4>(a, 1, st);
-  else if (tiles <= 9) {
+  else if (tiles <= 9 && !(big_min_m() > 0 && a.M >= big_min_m())) {
     switch (gemm_plan(a.M, a.N, a.K, a.split_k).nw) {
       case 8: launch_bf16_mt<9, 8>(a, 1, st); break;
       case 7: launch_bf16_mt<9, 7>(a, 1, st); break;
@@ -720,6 +730,7 @@ void launch_gemm(const GemmArgs& a, hipStream_t st) {
       launch_bf16_mt<8, 4>(a, (tiles + 7) / 8, st);
     } else {
       switch (big_at(a.M)) {
+        case 5: launch_big<5>(a, st); break;
         case 10: launch_big<10>(a, st); break;
         case 8: launch_big<8>(a, st); break;
         default: launch_big<6>(a, st); break;
