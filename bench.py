@@ -283,6 +283,24 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     acr_us = e0.elapsed_time(e1) / 50 * 1e3
+    # the step before the path: n SSMs of the paper's small-model shape drafting k tokens each through the
+    # same library (random weights, synthetic caches of the same contexts); informational
+    draft_ms = None
+    if desc.arch == synth.ARCH_LLAMA and desc.dtype == synth.DT_BF16 and args.layers <= 0:
+        sd = synth.LLAMA_160M
+        s_models = [harness.DeviceModel.random_on_device(sd, wl.seed + 100 + j) for j in range(n)]
+        s_kvs = [harness.DeviceKV.random_on_device(sd, ctx, ks, wl.seed + 200 + j, wl.block_size) for j in range(n)]
+        dsn = harness.DraftSession(s_models, s_kvs, B, k_max, max_ctx)
+        s_ctx0 = [kv.ctx_lens.clone() for kv in s_kvs]
+        dsn.draft(last, k_max)
+        for kv, c0 in zip(s_kvs, s_ctx0):
+            kv.ctx_lens.copy_(c0)
+        torch.cuda.synchronize()
+        t_d = time.perf_counter()
+        dsn.draft(last, k_max)
+        torch.cuda.synchronize()
+        draft_ms = (time.perf_counter() - t_d) * 1e3
+        del dsn, s_models, s_kvs
     sel = binding.mn_selector_create(max(1, k_max), 1, 64, 8, 1, 1)
     t_sel = time.perf_counter()
     for i in range(10000):
@@ -351,7 +369,9 @@ def main():
         "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
         "setup_s": t_setup,
         "after_step": {"acr_update_us": acr_us, "acr": [None if x != x else x for x in acr_buf.cpu().tolist()],
-                       "selector_observe_ns_incl_binding": sel_ns},
+                       "selector_observe_ns_incl_binding": sel_ns,
+                       "ssm_drafting_ms": draft_ms,
+                       "ssm_drafting_note": "n SSMs of Llama-160M shape, k_max tokens each, one after the other on this GPU"},
         "roofline": roofline, "kernel_families": families,
         "ceilings": measure_ceilings(torch, binding, harness), "cpu_baseline": cpu,
     }

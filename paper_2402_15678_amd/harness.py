@@ -247,3 +247,35 @@ class VerifySession:
         self.vote(drafts, spec_len, ssm_w, mode)
         self.forward(last_tok, spec_len, h_spec_len)
         self.accept(spec_len)
+
+
+class DraftSession:
+    """The step before the verification path (paper section 3.1: several SSMs speculate on one request):
+    every SSM is a small decoder of its own (own weights, own paged KV cache) driven through the same
+    library calls as the LLM, one token per call; its greedy tokens fill drafts[b][j][t] on the device,
+    which mn_mv_vote reads directly.  Copying a token column into the drafts array is the only thing done
+    outside the library."""
+
+    def __init__(self, models: Sequence[DeviceModel], kvs: Sequence[DeviceKV], B_: int, k_max: int, max_ctx: int):
+        assert len(models) == len(kvs) and len(models) >= 1
+        self.n, self.B, self.k_max = len(models), B_, k_max
+        self.sessions = [VerifySession(m, kv, B_, 0, 1, max_ctx, max_rows=B_) for m, kv in zip(models, kvs)]
+        dev = _dev()
+        self.drafts = torch.full((B_, self.n, max(1, k_max)), -1, dtype=torch.int32, device=dev)
+        self._zeros = torch.zeros((B_,), dtype=torch.int32, device=dev)
+        self._dummy = torch.zeros((B_, 1), dtype=torch.int32, device=dev)
+
+    def draft(self, last_tok: torch.Tensor, k: int) -> torch.Tensor:
+        """k greedy tokens per sequence from every SSM, starting from the pending token; each SSM's cache
+        advances by k entries (the caller truncates it to the accepted prefix after the verification)."""
+        assert 0 <= k <= self.k_max
+        self.drafts.fill_(-1)
+        zeros = [0] * self.B
+        for j, ses in enumerate(self.sessions):
+            cur = last_tok
+            for t in range(k):
+                ses.forward(cur, self._zeros, zeros, voted=self._dummy)
+                ses.accept(self._zeros, voted=self._dummy)
+                cur = ses.next_last_tok.clone()
+                self.drafts[:, j, t] = cur
+        return self.drafts

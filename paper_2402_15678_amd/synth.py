@@ -87,6 +87,8 @@ OPT_13B = ModelDesc(ARCH_OPT, DT_BF16, 40, 5120, 40, 40, 128, 20480, 50272, 2048
 LLAMA2_70B = ModelDesc(ARCH_LLAMA, DT_BF16, 80, 8192, 64, 8, 128, 28672, 32000, 4096)
 # attention-only workload: one layer of the 70B attention shape, long context
 LLAMA2_70B_ATTN = dataclasses.replace(LLAMA2_70B, n_layers=1, max_pos=8192)
+# the shape of the small speculative models the paper pairs with Llama-2-70B (section 5.1: Llama-160M)
+LLAMA_160M = dataclasses.replace(LLAMA2_70B, n_layers=12, d_model=768, n_heads=12, n_kv_heads=12, head_dim=64, d_ffn=3072)
 
 WORKLOADS: Tuple[Workload, ...] = (
     Workload("opt-tiny-fp32-b1-k4", OPT_TINY, 1, 64, 64, 4, 4, 3, 0.0, seed=1234),
