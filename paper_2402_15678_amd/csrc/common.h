@@ -13,13 +13,14 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// Precision note.  In bf16 models the weights and the KV pages are bf16 in HBM.  Every bf16 value
+// Precision note.  In bf16 models the weights and the KV pages arrive as bf16.  Every bf16 value
 // in the normal fp16 range is exactly representable in fp16 (8 significant bits into 11), so the
-// kernels widen weight and cache fragments to fp16 in registers and run the fp16 MFMA with fp32
-// accumulation, while the activations between kernels (norm output, queries, attention output,
-// FFN activation, softmax probabilities) are kept in fp16: 8x less rounding error per stage than
-// bf16 activations at the same MFMA rate and the same HBM traffic.  bf16 magnitudes below 2^-14
-// lose low bits in the widening (absolute error below 2^-25), which is far below every tolerance.
+// weights are re-encoded as fp16 once, when they are packed, the cache fragments are widened to fp16
+// on their way to the MFMA, and all products run on the fp16 MFMA with fp32 accumulation, while the
+// activations between kernels (norm output, queries, attention output, FFN activation, softmax
+// probabilities) are kept in fp16: 8x less rounding error per stage than bf16 activations at the
+// same MFMA rate and the same HBM traffic.  bf16 magnitudes below 2^-14 lose low bits in the widening
+// (absolute error below 2^-24), which is far below every tolerance.
 
 constexpr int WAVE = 64;
 

@@ -175,8 +175,8 @@ __global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) ge
   {                                                                                                         \
     const int it_ = (IT);                                                                                   \
     const int nxt_ = min(it_ + 1, last);                                                                    \
-    /* pin this iteration's ring slot below the previous barrier: the compiler otherwise hoists the      */ \
-    /* widening above it, where the tile loads are still pending and every wait becomes a full drain     */ \
+    /* pin this iteration's ring slot below the previous barrier: the compiler otherwise hoists its      */ \
+    /* first use above it, where the tile loads are still pending and every wait becomes a full drain    */ \
     _Pragma("unroll") for (int nt = 0; nt < NTW; ++nt)                                                      \
       _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(RING[nt][ks]));              \
     MN_DMA_A(NXT, nxt_)                                                                                     \
