@@ -178,3 +178,46 @@ def test_measuring_sticks_run_and_report_plausible_rates(env):
     torch.cuda.synchronize()
     tflops = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
     assert 300.0 < tflops < 2600.0, tflops
+
+
+def test_largest_batch_many_rows(env):
+    """MN_MAX_BATCH sequences in one step (thousands of rows: the many-rows GEMM, attention over thousands of
+    short sequences); a sample of sequences is checked against the oracle, which treats them one by one."""
+    harness, binding, W, model = env
+    B = 4096
+    g = synth.stream(8, 1)
+    ctx = g.integers(1, 41, size=B).astype(np.int32)
+    ks = g.integers(0, 3, size=B).astype(np.int32)
+    kvh = synth.make_paged_kv(DESC, ctx, ks, 11)
+    kvd = harness.DeviceKV.from_host(DESC, kvh)
+    M = int((ks + 1).sum())
+    ses = harness.VerifySession(model, kvd, B, 2, 3, int((ctx + ks + 1).max()), max_rows=M, want_logits=True)
+    last = g.integers(0, DESC.vocab, size=B).astype(np.int32)
+    drafts = g.integers(0, DESC.vocab, size=(B, 3, 2)).astype(np.int32)
+    t = [_i32(last), _i32(drafts), _i32(ks), torch.ones(3, device="cuda:0")]
+    ses.step(t[0], t[1], t[2], ks.tolist(), t[3])
+    torch.cuda.synchronize()
+    assert ses.dev_status.item() == 0
+    pick = np.unique(np.concatenate([[0, B - 1], g.integers(0, B, size=10)]))
+    caches = util.oracle_caches(DESC, _subset_kv(kvh, pick))
+    want = orc.verify_step(DESC, W, caches, last[pick], drafts[pick], ks[pick], np.ones(3, np.float32))
+    row0 = np.concatenate([[0], np.cumsum(ks + 1)])
+    logits = ses.logits.cpu().numpy()
+    voted = ses.voted.cpu().numpy()
+    for i, b in enumerate(pick):
+        assert np.array_equal(voted[b, :ks[b]], want["voted"][i, :ks[b]])
+        got = logits[row0[b]:row0[b + 1]]
+        assert np.abs(got - want["logits"][i]).max() < 3e-2
+        if orc.top1_margin(want["logits"][i]).min() >= 6e-2:
+            assert ses.accepted_len[b].item() == want["accepted_len"][i]
+            assert kvd.ctx_lens[b].item() == want["ctx_lens"][i]
+    # every sequence advanced by its accepted length + 1
+    adv = kvd.ctx_lens.cpu().numpy() - ctx
+    assert np.array_equal(adv, ses.accepted_len.cpu().numpy() + 1)
+    assert (ses.n_out.cpu().numpy() == adv).all()
+
+
+def _subset_kv(kvh, seqs):
+    """A PagedKV image restricted to some sequences (same pages, only their block-table rows)."""
+    import dataclasses
+    return dataclasses.replace(kvh, block_tables=kvh.block_tables[seqs], ctx_lens=np.asarray(kvh.ctx_lens)[seqs])
