@@ -424,6 +424,13 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
       g.a = h; g.w = c->w1[l]; g.swiglu_act = act; g.M = M; g.N = w1r; g.K = d.d_model; g.split_k = 1; g.dtype = d.dtype;
       Tap t(&c->prof, MN_PROF_GEMM, st);
       launch_gemm(g, st);
+    } else if (!llama && d.dtype == MN_DT_BF16 && gemm_pick_split(M, w1r, d.d_model, d.dtype) == 1) {
+      // one split: bias + ReLU applied in the kernel's epilogue, no partial sums and no activation kernel
+      GemmArgs g{};
+      g.a = h; g.w = c->w1[l]; g.relu_act = act; g.bias = (const float*)c->b1[l]; g.M = M; g.N = w1r; g.K = d.d_model;
+      g.split_k = 1; g.dtype = d.dtype;
+      Tap t(&c->prof, MN_PROF_GEMM, st);
+      launch_gemm(g, st);
     } else {
       s = gemm_pick_split(M, w1r, d.d_model, d.dtype);
       gemm(h, c->w1[l], part, w1r, d.d_model, s);

@@ -57,7 +57,8 @@ __device__ __forceinline__ int lds_slot(int row, int chunk) { return row * LDS_R
 // EPI_SWIGLU (Llama first FFN projection, one split): the matrix was packed with gate and up rows
 // interleaved per 16-column tile, so a wave's two tiles are gate and up of the same 16 FFN
 // columns; it stores silu(gate) * up as fp16 [M][F] and nothing else.
-enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1 };
+// EPI_RELU (OPT first FFN projection, one split): stores max(sum + bias, 0) as fp16 [M][N].
+enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_RELU = 2 };
 
 template <int MT, int NTW, int EPI, int NW, int RD>
 __global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) gemm_w16_kernel(const f16_t* __restrict__ A, const bf16_t* __restrict__ W,
@@ -237,6 +238,29 @@ __global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) ge
 #pragma unroll
         for (int i = 0; i < 4; ++i) r[i] = gt[i] / (1.f + __expf(-gt[i])) * up[i];
         *reinterpret_cast<uint2*>(act + (size_t)m * F + f) = make_uint2(pack2h(r[0], r[1]), pack2h(r[2], r[3]));
+      }
+    }
+  } else if constexpr (EPI == EPI_RELU) {
+    f16_t* act = reinterpret_cast<f16_t*>(out_);
+#pragma unroll
+    for (int nt = 0; nt < NTW; ++nt) {
+      const int n = n_wg + (w4 * NTW + nt) * 16 + g * 4;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const int m = m0 + mt * 16 + l16;
+        if (m >= M || n >= N) continue;
+        f32x4 v = acc[nt][mt];
+        float r[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = fmaxf(v[i] + ((bias && n + i < N) ? bias[n + i] : 0.f), 0.f);
+        f16_t* p = act + (size_t)m * N + n;
+        if (n + 3 < N && (N & 3) == 0) {
+          *reinterpret_cast<uint2*>(p) = make_uint2(pack2h(r[0], r[1]), pack2h(r[2], r[3]));
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (n + i < N) p[i] = (f16_t)r[i];
+        }
       }
     }
   } else {
@@ -443,6 +467,29 @@ __global__ void __launch_bounds__(512, 1) gemm_big_kernel(const f16_t* __restric
         *reinterpret_cast<uint2*>(act + (size_t)m * F + f) = make_uint2(pack2h(r[0], r[1]), pack2h(r[2], r[3]));
       }
     }
+  } else if constexpr (EPI == EPI_RELU) {
+    f16_t* act = reinterpret_cast<f16_t*>(out_);
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const int n = n_wg + (wn * 4 + b) * 16 + g * 4;
+#pragma unroll
+      for (int a = 0; a < AT; ++a) {
+        const int m = m0 + (wm * AT + a) * 16 + l16;
+        if (m >= M || n >= N) continue;
+        const f32x4 v = acc[a][b];
+        float r[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = fmaxf(v[i] + ((bias && n + i < N) ? bias[n + i] : 0.f), 0.f);
+        f16_t* p = act + (size_t)m * N + n;
+        if (n + 3 < N && (N & 3) == 0) {
+          *reinterpret_cast<uint2*>(p) = make_uint2(pack2h(r[0], r[1]), pack2h(r[2], r[3]));
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (n + i < N) p[i] = (f16_t)r[i];
+        }
+      }
+    }
   } else {
     float* o = reinterpret_cast<float*>(out_) + (size_t)split * M * N;
 #pragma unroll
@@ -594,9 +641,9 @@ static GemmPlan gemm_plan(int M, int N, int K, int forced_split) {
   const int slices = ((N + NWG - 1) / NWG) * 4;  // 32-column wave slices of the padded matrix
   const int iters = K / KB;
   if (forced_split < 1 && tune().split >= 1) forced_split = tune().split;
-  auto splits_for = [&](int gx, int slots) {
+  auto splits_for = [&](int gx, int slots, int min_iters = 16) {
     int s = forced_split >= 1 ? forced_split : slots / gx;
-    if (forced_split < 1 && s > iters / 16) s = iters / 16;
+    if (forced_split < 1 && s > iters / min_iters) s = iters / min_iters;
     if (s > MN_MAX_SPLIT_K) s = MN_MAX_SPLIT_K;
     if (s < 1) s = 1;
     const int per = (iters + s - 1) / s;  // drop splits that would get no iteration
@@ -615,8 +662,11 @@ static GemmPlan gemm_plan(int M, int N, int K, int forced_split) {
     best.split = splits_for(gx * blocks, tune().target / 2);
     return best;
   }
-  if (M <= 96) {  // up to six row tiles: 4-wave workgroups, two per CU
-    best.split = splits_for((slices + 3) / 4, tune().target);
+  if (M <= 96) {
+    // up to six row tiles: 4-wave workgroups.  Few rows make an iteration cheap, so a split may be as short
+    // as 8 iterations, and one workgroup per CU is enough (measured at 40 rows: the 5120 x 5120 matrix
+    // gains 30 % from 5 splits over 2, the 20480-column one loses with any split)
+    best.split = splits_for((slices + 3) / 4, tune().target / 2, 8);
     return best;
   }
   int best_cus = 0, best_waves = 0;
@@ -657,6 +707,8 @@ static void launch_bf16_mt(const GemmArgs& a, int m_chunks, hipStream_t st) {
   const bf16_t* W = reinterpret_cast<const bf16_t*>(a.w);
   if (a.swiglu_act)
     gemm_w16_kernel<MT, NTW, EPI_SWIGLU, NW, RD><<<grid, NW * 64, 0, st>>>(A, W, a.swiglu_act, nullptr, a.M, a.N, a.K, per * KB, m_chunks, gx, a.split_k);
+  else if (a.relu_act)
+    gemm_w16_kernel<MT, NTW, EPI_RELU, NW, RD><<<grid, NW * 64, 0, st>>>(A, W, a.relu_act, a.bias, a.M, a.N, a.K, per * KB, m_chunks, gx, a.split_k);
   else
     gemm_w16_kernel<MT, NTW, EPI_PARTIAL, NW, RD><<<grid, NW * 64, 0, st>>>(A, W, a.out, a.bias, a.M, a.N, a.K, per * KB, m_chunks, gx, a.split_k);
 }
@@ -689,10 +741,13 @@ static void launch_big(const GemmArgs& a, hipStream_t st) {
   if (!attr_set) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_big_kernel<AT, EPI_PARTIAL>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_big_kernel<AT, EPI_SWIGLU>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_big_kernel<AT, EPI_RELU>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     attr_set = true;
   }
   if (a.swiglu_act)
     gemm_big_kernel<AT, EPI_SWIGLU><<<grid, 512, smem, st>>>(A, W, a.swiglu_act, nullptr, a.M, a.N, a.K, per * KB, rb, gx, a.split_k);
+  else if (a.relu_act)
+    gemm_big_kernel<AT, EPI_RELU><<<grid, 512, smem, st>>>(A, W, a.relu_act, a.bias, a.M, a.N, a.K, per * KB, rb, gx, a.split_k);
   else
     gemm_big_kernel<AT, EPI_PARTIAL><<<grid, 512, smem, st>>>(A, W, a.out, a.bias, a.M, a.N, a.K, per * KB, rb, gx, a.split_k);
 }

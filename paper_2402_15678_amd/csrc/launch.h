@@ -76,6 +76,7 @@ struct GemmArgs {
   const void* w;  // fp32 models: [N][K] row-major; bf16 models: the packed layout of gemm.hip
   float* out;     // [S][M][N] fp32 partial sums (S = split_k); bias added to split 0 when given
   void* swiglu_act;  // non-null: fused SwiGLU epilogue, fp16 [M][N/2] (bf16 models, split_k == 1, interleaved packing)
+  void* relu_act;    // non-null: fused bias + ReLU epilogue, fp16 [M][N] (bf16 models, split_k == 1)
   const float* bias;
   int M, N, K, split_k, dtype;
 };
