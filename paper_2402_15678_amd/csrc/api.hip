@@ -151,7 +151,7 @@ extern "C" void mn_destroy(mn_ctx* ctx) { delete ctx; }
 static size_t al(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
-  size_t row_seq, row_j, row_pos, row_tok, seq_row0, seq_ctx, seq_ok, rope_cos, rope_sin;
+  size_t row_seq, row_j, row_pos, row_tok, seq_row0, seq_ctx, seq_ok, attn_tps, rope_cos, rope_sin;
   size_t x, h, q, knew, vnew, attn, act, partials, logits, attn_scratch, total;
   size_t partials_bytes, attn_scratch_bytes;
 };
@@ -164,6 +164,7 @@ static Layout make_layout(const mn_model_desc& d, int B, int M, int max_ctx) {
   auto take = [&](size_t bytes) { size_t o = at; at += al(bytes); return o; };
   L.row_seq = take(Mr * 4); L.row_j = take(Mr * 4); L.row_pos = take(Mr * 4); L.row_tok = take(Mr * 4);
   L.seq_row0 = take(((size_t)B + 1) * 4); L.seq_ctx = take((size_t)B * 4 + 4); L.seq_ok = take((size_t)B * 4 + 4);
+  L.attn_tps = take(4);
   L.rope_cos = take(Mr * (d.head_dim / 2) * 4); L.rope_sin = take(Mr * (d.head_dim / 2) * 4);
   L.x = take(Mr * d.d_model * 4);
   L.h = take(Mr * d.d_model * es);
@@ -298,6 +299,7 @@ static RowInfo row_info(const Ws& w) {
   r.seq_row0 = w.at<int32_t>(w.L.seq_row0);
   r.seq_ctx = w.at<int32_t>(w.L.seq_ctx);
   r.seq_ok = w.at<int32_t>(w.L.seq_ok);
+  r.attn_tps = w.at<int32_t>(w.L.attn_tps);
   return r;
 }
 
@@ -318,6 +320,17 @@ static void run_prepare(mn_ctx* c, const Ws& w, const int32_t* last_tok, const i
   p.row_seq = w.at<int32_t>(w.L.row_seq); p.row_j = w.at<int32_t>(w.L.row_j);
   p.row_pos = w.at<int32_t>(w.L.row_pos); p.row_tok = w.at<int32_t>(w.L.row_tok);
   p.seq_row0 = w.at<int32_t>(w.L.seq_row0); p.seq_ctx = w.at<int32_t>(w.L.seq_ctx); p.seq_ok = w.at<int32_t>(w.L.seq_ok);
+  p.attn_tps = w.at<int32_t>(w.L.attn_tps);
+  p.kv_heads = c->d.n_kv_heads;
+  p.q_per_kv = c->d.n_heads / c->d.n_kv_heads;
+  // 1.5 workgroups per CU: measured flat between 1 and 2 per CU, slower beyond (every further split of a
+  // sequence writes and re-reads one more fp32 partial of its rows)
+  static const int attn_wgs = [] {
+    const char* e = getenv("MN_ATTN_WGS");  // experiment switch
+    const int v = e ? atoi(e) : 0;
+    return v > 0 ? v : 384;
+  }();
+  p.attn_wgs = attn_wgs;
   p.rope_cos = w.at<float>(w.L.rope_cos); p.rope_sin = w.at<float>(w.L.rope_sin);
   p.dev_status = dev_status;
   Tap t(&c->prof, MN_PROF_PREPARE, st);

@@ -120,7 +120,7 @@ __global__ void __launch_bounds__(GEN_THREADS) attn_generic_kernel(AttnArgs a) {
 // ------------------------------------------------------------------------------------------
 // MFMA kernel (bf16 pages, fp16 queries, head_dim 128, block 16)
 // ------------------------------------------------------------------------------------------
-// Workgroup (4 waves) = one (KV split, KV head, sequence).  The R = G*q_b query rows that share the
+// Workgroup (4 waves) = one (KV head, sequence, KV split).  The R = G*q_b query rows that share the
 // KV head are cut into 16-row column tiles; wave w owns tiles w, w+4, (w+8) and keeps their query
 // fragments (pre-multiplied by log2(e)/sqrt(hd)) in registers.
 //
@@ -201,6 +201,11 @@ __device__ __forceinline__ f16x8 softmax_tile(const f32x4& S0, const f32x4& S1, 
 
 template <int N> struct IntC { static constexpr int value = N; };
 
+// KV splits of a sequence with n_tiles key tiles when a workgroup should take about tps of them
+__device__ __forceinline__ int seq_splits(int n_tiles, int tps, int n_splits_max) {
+  return max(1, min(n_splits_max, (n_tiles + tps - 1) / max(tps, 1)));
+}
+
 // Partials: o_part [split][M][H][HD] fp32 (unnormalised), ml_part [split][M][H][2] = (max in log2 units, sum)
 template <int CTW>
 __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_splits, int n_rg, float* __restrict__ o_part,
@@ -210,7 +215,10 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_spl
   int32_t* s_bidx = reinterpret_cast<int32_t*>(smem + NS * TILE_BYTES);  // physical block of every block of the split
   // row group rg: column tiles [4*CTW*rg, 4*CTW*(rg+1)) of the stack; sequences with more than 64*CTW
   // stacked rows get a workgroup per group (each streams the keys again), the others leave at once
-  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z / n_rg, rg = blockIdx.z % n_rg;
+  // grid (KV head, sequence x row group, split): workgroup ids are dealt round-robin over the 8 XCDs, so with
+  // the KV head as the fastest index the work spreads evenly whatever splits and row groups turn out empty
+  // (with the split fastest, a batch that uses 2 of 16 possible splits would run on 2 of the 8 XCDs)
+  const int kvh = blockIdx.x, b = blockIdx.y / n_rg, rg = blockIdx.y % n_rg, split = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
   const int G = a.H / a.Hkv;
@@ -225,8 +233,12 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_spl
   if (tile0 >= NT16) return;              // (whole workgroup)
   const int nkeys = ok ? ctx + qb : 0;
   const int n_tiles = (nkeys + KT - 1) / KT;
-  const int t_begin = (int)(((long)n_tiles * split) / n_splits);
-  const int t_end = (int)(((long)n_tiles * (split + 1)) / n_splits);
+  // this sequence's own number of KV splits (the grid holds the largest any sequence may get): about
+  // attn_tps key tiles per workgroup, so the long sequences of a ragged batch are cut finer than the short ones
+  const int my_splits = seq_splits(n_tiles, a.rows.attn_tps[0], n_splits);
+  if (split >= my_splits) return;         // (whole workgroup)
+  const int t_begin = (int)(((long)n_tiles * split) / my_splits);
+  const int t_end = (int)(((long)n_tiles * (split + 1)) / my_splits);
   const int n_my = max(0, t_end - t_begin);
   const int nct = ok ? min(CTW, max(0, (NT16 - tile0 - wave + 3) >> 2)) : 0;  // real column tiles of this wave
 
@@ -451,7 +463,7 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_spl
     const float l = L[ct][0];
     const int j = r / G, gi = r % G;
     const int m = row0 + j, h = kvh * G + gi;
-    if (n_splits == 1) {
+    if (my_splits == 1) {
       const float inv = (ok && l > 0.f) ? 1.f / l : 0.f;
       f16_t* o = reinterpret_cast<f16_t*>(a.out) + ((size_t)m * a.H + h) * HD + 4 * g;
 #pragma unroll
@@ -475,11 +487,19 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_spl
   }
 }
 
-// One wave per (row, head): merge the split partials, normalise, store fp16.
+// One wave per (row, head): merge the split partials, normalise, store fp16.  Rows of sequences that ran as
+// one split were written in final form by the attention kernel and are left alone.
 __global__ void __launch_bounds__(256) attn_merge_kernel(const float* __restrict__ o_part, const float* __restrict__ ml_part,
-                                                         int n_splits, int M, int H, f16_t* __restrict__ out) {
+                                                         int n_splits_max, int M, int H, RowInfo rows,
+                                                         f16_t* __restrict__ out) {
   const int wid = (blockIdx.x * 256 + threadIdx.x) >> 6, lane = threadIdx.x & 63;
   if (wid >= M * H) return;
+  const int m = wid / H;
+  const int b = rows.row_seq[m];
+  const int qb = rows.seq_row0[b + 1] - rows.seq_row0[b];
+  const int nkeys = rows.seq_ok[b] ? rows.seq_ctx[b] + qb : 0;
+  const int n_splits = seq_splits((nkeys + KT - 1) / KT, rows.attn_tps[0], n_splits_max);
+  if (n_splits == 1) return;
   float gm = -INFINITY;
   for (int s = 0; s < n_splits; ++s) gm = fmaxf(gm, ml_part[((size_t)s * M * H + wid) * 2]);
   const float ms = (gm == -INFINITY) ? 0.f : gm;
@@ -499,26 +519,17 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(const float* __restrict
 // ------------------------------------------------------------------------------------------
 // launch
 // ------------------------------------------------------------------------------------------
-static int attn_target_wgs() {
-  static int t = [] {
-    const char* e = getenv("MN_ATTN_TARGET_WGS");
-    return e ? atoi(e) : 512;  // two workgroups per CU
-  }();
-  return t;
-}
-
+// Largest number of KV splits any sequence of the batch may get (the grid's x extent; every sequence then
+// takes what its own length asks for, see seq_splits): one per 16 key tiles of the longest context.
 static int pick_splits(int B, int Hkv, int max_ctx) {
   static int forced = [] {
     const char* e = getenv("MN_ATTN_SPLITS");
     return e ? atoi(e) : 0;
   }();
+  (void)B;
+  (void)Hkv;
   const int tiles = (max_ctx + KT - 1) / KT;
-  int s = forced > 0 ? forced : (attn_target_wgs() + B * Hkv - 1) / (B * Hkv);
-  // at least sixteen key tiles per split (measured: below that the prologue of a workgroup, three tiles
-  // of lead-in and the query fragments, and the larger partial sums cost more than the extra
-  // workgroups hide)
-  const int cap = tiles / 16;
-  if (s > cap) s = cap;
+  int s = forced > 0 ? forced : tiles / 16;
   if (s > 16) s = 16;
   if (s < 1) s = 1;
   return s;
@@ -563,14 +574,14 @@ void launch_attention(const AttnArgs& a, hipStream_t st) {
       attr_set = true;
     }
     if (nt16_max <= 4) {
-      attn_mfma_kernel<1><<<dim3(n_splits, a.Hkv, a.B), 256, smem, st>>>(a, n_splits, 1, o_part, ml_part);
+      attn_mfma_kernel<1><<<dim3(a.Hkv, a.B, n_splits), 256, smem, st>>>(a, n_splits, 1, o_part, ml_part);
     } else {
       const int n_rg = (nt16_max + 4 * MAX_CT - 1) / (4 * MAX_CT);
-      attn_mfma_kernel<2><<<dim3(n_splits, a.Hkv, a.B * n_rg), 256, smem, st>>>(a, n_splits, n_rg, o_part, ml_part);
+      attn_mfma_kernel<2><<<dim3(a.Hkv, a.B * n_rg, n_splits), 256, smem, st>>>(a, n_splits, n_rg, o_part, ml_part);
     }
     if (n_splits > 1) {
       const int waves = a.M * a.H;
-      attn_merge_kernel<<<(waves + 3) / 4, 256, 0, st>>>(o_part, ml_part, n_splits, a.M, a.H, reinterpret_cast<f16_t*>(a.out));
+      attn_merge_kernel<<<(waves + 3) / 4, 256, 0, st>>>(o_part, ml_part, n_splits, a.M, a.H, a.rows, reinterpret_cast<f16_t*>(a.out));
     }
     return;
   }

@@ -114,6 +114,7 @@ struct RowInfo {
   const int32_t* seq_row0;  // [B+1] first row of sequence b
   const int32_t* seq_ctx;   // [B] ctx_b as read at the start of the step (0 for disabled sequences)
   const int32_t* seq_ok;    // [B] 1 = enabled
+  const int32_t* attn_tps;  // [1] key tiles (32 keys) one attention workgroup should take: sets the KV splits per sequence
 };
 
 struct KvView {

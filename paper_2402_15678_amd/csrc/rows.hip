@@ -15,8 +15,9 @@ __global__ void __launch_bounds__(256) prepare_kernel(PrepArgs a) {
   __shared__ int32_t s_ok[MN_MAX_BATCH];
   __shared__ int32_t s_nb[MN_MAX_BATCH];  // blocks each sequence needs mapped (0: nothing to check)
   __shared__ int s_bad;
+  __shared__ unsigned long long s_tiles;
   const int tid = threadIdx.x;
-  if (tid == 0) s_bad = 0;
+  if (tid == 0) { s_bad = 0; s_tiles = 0ull; }
   __syncthreads();
   // pass 1: per-sequence validation
   for (int b = tid; b < a.B; b += blockDim.x) {
@@ -77,6 +78,7 @@ __global__ void __launch_bounds__(256) prepare_kernel(PrepArgs a) {
   const bool bad = s_bad != 0;
   // a device spec_len that disagrees with the launch geometry disables the whole batch
   if (bad) {
+    if (tid == 0 && a.attn_tps) a.attn_tps[0] = 1 << 20;
     for (int b = tid; b <= a.B; b += blockDim.x) a.seq_row0[b] = 0;
     for (int b = tid; b < a.B; b += blockDim.x) { a.seq_ctx[b] = 0; a.seq_ok[b] = 0; }
     for (int m = tid; m < a.M; m += blockDim.x) { a.row_seq[m] = 0; a.row_j[m] = 0; a.row_pos[m] = -1; a.row_tok[m] = 0; }
@@ -95,6 +97,19 @@ __global__ void __launch_bounds__(256) prepare_kernel(PrepArgs a) {
       a.row_pos[r0 + j] = ok ? ctx + j : -1;
       a.row_tok[r0 + j] = (ok && a.last_tok) ? ((j == 0) ? a.last_tok[b] : a.voted[(size_t)b * a.k_max + j - 1]) : 0;
     }
+    // key tiles of 32, once per group of 128 (query position x head) rows: the work of the sequence in units of
+    // one workgroup's tile (integer sum: order-free)
+    if (ok && q > 0)
+      atomicAdd(&s_tiles, (unsigned long long)((ctx + q + 31) >> 5) * (unsigned long long)((q * max(a.q_per_kv, 1) + 127) >> 7));
+  }
+  __syncthreads();
+  // Balance of the attention grid: a workgroup should take about (all key tiles x KV heads) / (the number of
+  // workgroups aimed for) tiles, at least 16 (below that the lead-in of a workgroup and the partial sums cost more than
+  // the parallelism wins).  Long sequences of a ragged batch are then cut into more splits than short ones.
+  if (tid == 0 && a.attn_tps) {
+    const unsigned long long w = (unsigned long long)max(a.attn_wgs, 1);
+    const unsigned long long per = (s_tiles * (unsigned long long)max(a.kv_heads, 1) + w - 1) / w;
+    a.attn_tps[0] = (int)min(max(per, 16ull), (unsigned long long)(1 << 20));
   }
 }
 
