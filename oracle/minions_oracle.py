@@ -23,6 +23,10 @@ What it computes, with the passage of the paper each part follows:
                      verification rule of section 2.1: a draft token is kept iff it equals the
                      LLM's argmax, the first mismatch discards the rest, and one more token
                      comes from the LLM's own distribution (correction or bonus token).
+* ``accept_stochastic``  the general verification rule of section 2.1 (keep a token outright when the
+                     SSM's probability does not exceed the LLM's, otherwise reject it with probability
+                     1 - o/q and draw a replacement from the renormalised positive part of o - q), with
+                     its random numbers from a counter-based generator (``philox4x32``).
 * ``commit``         drop the cache entries of the rejected tokens (section 4): the context
                      grows by the accepted prefix plus the pending token.
 * ``acr_update``     speculation quality metric (equation ACR) and the multiplicative weight
@@ -378,6 +382,98 @@ def verify_step(desc, W, caches: Sequence[SeqCache], last_tok: Sequence[int], dr
     return {"voted": voted, "voted_ssm": ssm, "logits": logits, "greedy": greedy, "accepted_len": acc,
             "out_tokens": out, "n_out": n_out, "next_last_tok": nxt, "ctx_lens": new_ctx,
             "blocks_in_use": blocks}
+
+
+# ---------------------------------------------------------------------------
+# stochastic verification (section 2.1, the general rule of which `accept` is the greedy case)
+# ---------------------------------------------------------------------------
+
+_M32 = 0xFFFFFFFF
+
+
+def philox4x32(counter: Sequence[int], key: Sequence[int], rounds: int = 10) -> Tuple[int, int, int, int]:
+    """Philox-4x32 counter-based generator (Salmon, Moraes, Dror, Shaw, "Parallel random numbers: as
+    easy as 1, 2, 3", SC 2011): a 128-bit counter and a 64-bit key give four 32-bit words.  Each round
+    multiplies words 0 and 2 by two fixed odd constants, swaps the halves of the products into the
+    other lanes and mixes in the key, which advances by the golden-ratio / sqrt(3) constants."""
+    c0, c1, c2, c3 = (int(c) & _M32 for c in counter)
+    k0, k1 = (int(k) & _M32 for k in key)
+    for _ in range(rounds):
+        p0 = 0xD2511F53 * c0
+        p1 = 0xCD9E8D57 * c2
+        c0, c1, c2, c3 = ((p1 >> 32) ^ c1 ^ k0) & _M32, p1 & _M32, ((p0 >> 32) ^ c3 ^ k1) & _M32, p0 & _M32
+        k0 = (k0 + 0x9E3779B9) & _M32
+        k1 = (k1 + 0xBB67AE85) & _M32
+    return c0, c1, c2, c3
+
+
+def unit_double(hi: int, lo: int) -> float:
+    """53 random bits -> a double in [0, 1): the top 27 bits of `hi` and the top 26 bits of `lo`."""
+    return float(((int(hi) >> 5) << 26) + (int(lo) >> 6)) / float(1 << 53)
+
+
+def verify_uniforms(seed: int, step: int, b: int, j: int) -> Tuple[float, float]:
+    """The two uniform numbers position j of sequence b consumes in step `step`: the first decides
+    acceptance, the second picks the replacement (or bonus) token.  Key = seed, counter = (b, j, step)."""
+    w = philox4x32((b, j, step & _M32, (step >> 32) & _M32), (seed & _M32, (seed >> 32) & _M32))
+    return unit_double(w[0], w[1]), unit_double(w[2], w[3])
+
+
+def llm_probs(logits_row: np.ndarray, temperature: float) -> np.ndarray:
+    """o(x): softmax of the LLM's scores at one position, at the given temperature, in fp64."""
+    z = (_f64(logits_row) - float(np.max(logits_row))) / float(temperature)
+    e = np.exp(z)
+    return e / e.sum()
+
+
+def sample_cdf(mass: np.ndarray, u: float) -> Tuple[int, float]:
+    """Inverse-CDF sample in token order: the first token whose running sum of `mass` exceeds u times the
+    total.  Also returns how far (relative to the total) the target is from the nearest running sum on
+    either side of the chosen token, so that a test can tell a decision that hangs on the last bits."""
+    cum = np.cumsum(_f64(mass))
+    total = float(cum[-1])
+    target = u * total
+    v = int(np.searchsorted(cum, target, side="right"))
+    if v >= len(cum):                       # rounding pushed the target to the total: last token with mass
+        v = int(np.nonzero(mass > 0)[0][-1])
+    below = float(cum[v - 1]) if v > 0 else -np.inf
+    gap = min(abs(float(cum[v]) - target), abs(target - below)) / total
+    return v, gap
+
+
+def accept_stochastic(voted: Sequence[int], logits: np.ndarray, draft_probs: np.ndarray, k: int,
+                      temperature: float, seed: int, step: int, b: int):
+    """Verification of one sequence's k speculated tokens (section 2.1).  logits [k+1][V] are the LLM's
+    scores of the k+1 positions, draft_probs [k][V] the drafting SSM's distributions q_i.  Token x_i is
+    kept when q_i(x_i) <= o_i(x_i); otherwise it is rejected with probability 1 - o_i(x_i)/q_i(x_i), and
+    then a replacement is drawn from max(0, o_i - q_i) renormalised and everything after it is dropped.
+    When all k survive, one more token is drawn from o_{k+1}.
+    Returns (accepted length a, the a+1 emitted tokens, smallest relative distance of any decision taken
+    from its threshold)."""
+    out: List[int] = []
+    margin = np.inf
+    for i in range(k):
+        x = int(voted[i])
+        o = llm_probs(logits[i], temperature)
+        q = _f64(draft_probs[i])
+        u_acc, u_res = verify_uniforms(seed, step, b, i)
+        if q[x] <= o[x]:
+            out.append(x)
+            continue
+        ratio = o[x] / q[x]
+        margin = min(margin, abs(u_acc - ratio))
+        if u_acc < ratio:                   # rejected with probability 1 - o/q
+            out.append(x)
+            continue
+        residual = np.maximum(0.0, o - q)
+        tok, gap = sample_cdf(residual, u_res)
+        margin = min(margin, gap)
+        out.append(tok)
+        return i, out, margin
+    _, u_res = verify_uniforms(seed, step, b, k)
+    tok, gap = sample_cdf(llm_probs(logits[k], temperature), u_res)
+    out.append(tok)
+    return k, out, min(margin, gap)
 
 
 # ---------------------------------------------------------------------------
