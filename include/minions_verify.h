@@ -211,6 +211,37 @@ mn_status mn_accept_and_commit(mn_ctx *ctx, const int32_t *voted, const int32_t 
                                int32_t *n_out, int32_t *next_last_tok, int32_t *blocks_in_use,
                                int32_t *dev_status, void *stream);
 
+/* Stochastic verification (section 2.1, the general rule; the greedy tokens of mn_verify_forward are its
+ * temperature -> 0 case).  With o_j = softmax(logits row of position j / temperature) and q_j the
+ * drafting SSM's distribution at that position, the speculated token x = voted[b][j] survives when
+ * q_j(x) <= o_j(x), and otherwise with probability o_j(x) / q_j(x); where it does not survive, a
+ * replacement is drawn from max(0, o_j - q_j) renormalised (from o_j itself should that be zero
+ * everywhere); at position k_b, after the last speculated token, a token is drawn from o_{k_b}.
+ * The result is written in the layout of `greedy`: sampled[b][j] = voted[b][j] where the token
+ * survived, the drawn token elsewhere, -1 beyond k_b.  A replacement never equals the token it
+ * replaces, so mn_accept_and_commit(voted, sampled, ...) then yields exactly the rule's output: the
+ * survivors before the first rejection plus the replacement (or the bonus token), and the cache commit.
+ * Every position is decided independently of the others (entries after the first rejection are
+ * computed and then ignored by the acceptance).
+ *   logits      dev [M][vocab] fp32, rows packed as by mn_verify_forward (sequence b's k_b + 1 rows
+ *               follow those of sequence b - 1); M = sum_b (spec_len[b] + 1)
+ *   voted       dev [B][k_max]            draft_probs dev [B][k_max][vocab] fp32: q_j of the SSM whose
+ *   spec_len    dev [B]                   draft was voted (used as given, not renormalised)
+ *   greedy      dev [B][k_max+1] from mn_verify_forward: a sequence with greedy[b][0] == -1 (a no-op
+ *               there) gets sampled[b][*] = -1 and stays a no-op in mn_accept_and_commit
+ *   sampled     dev [B][k_max+1] (out)
+ * Arithmetic is fp64.  Random numbers: Philox-4x32-10 with key = seed and counter = (b, j, step); the
+ * first two output words give the 53-bit uniform number of the survival test (top 27 bits of word 0,
+ * top 26 of word 1), the last two that of the draw, which takes the first token, in token order, whose
+ * running sum of mass exceeds u times the total.  The same (seed, step, b, j) always gives the same
+ * numbers: the caller advances `step` once per verification step.
+ * Errors: temperature must be positive and finite; vocab <= 2^21; k_max <= 4096.  Rows that do not add
+ * up to M set MN_DEV_SPEC_LEN in *dev_status and give -1.  ctx may be NULL. */
+mn_status mn_verify_sample(mn_ctx *ctx, const float *logits, const int32_t *voted, const float *draft_probs,
+                           const int32_t *spec_len, const int32_t *greedy, int B, int k_max, int M, int vocab,
+                           double temperature, uint64_t seed, uint64_t step, int32_t *sampled, int32_t *dev_status,
+                           void *stream);
+
 /* ---- after the step: closing the loop (sections 3.2 and 3.3) --------------------------------- */
 
 /* Speculation quality metric and SSM weight update (section 3.2, equation ACR).  For every SSM i,

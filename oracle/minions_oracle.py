@@ -466,6 +466,8 @@ def accept_stochastic(voted: Sequence[int], logits: np.ndarray, draft_probs: np.
             out.append(x)
             continue
         residual = np.maximum(0.0, o - q)
+        if not residual.sum() > 0.0:        # q covers o everywhere (possible only for a q that sums above 1)
+            residual = o
         tok, gap = sample_cdf(residual, u_res)
         margin = min(margin, gap)
         out.append(tok)

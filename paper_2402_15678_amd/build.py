@@ -10,7 +10,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libminions_verify.so")
-SOURCES = ("api.hip", "vote_accept.hip", "rows.hip", "gemm.hip", "attention.hip", "probe.hip", "selector.cpp")
+SOURCES = ("api.hip", "vote_accept.hip", "rows.hip", "gemm.hip", "attention.hip", "stochastic.hip", "probe.hip", "selector.cpp")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-variable",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -256,6 +256,25 @@ extern "C" mn_status mn_acr_update(mn_ctx* ctx, const int32_t* voted_ssm, const 
   return hip_check(ctx, "mn_acr_update");
 }
 
+extern "C" mn_status mn_verify_sample(mn_ctx* ctx, const float* logits, const int32_t* voted, const float* draft_probs,
+                                      const int32_t* spec_len, const int32_t* greedy, int B, int k_max, int M, int vocab,
+                                      double temperature, uint64_t seed, uint64_t step, int32_t* sampled,
+                                      int32_t* dev_status, void* stream) {
+  if (B < 0 || B > MN_MAX_BATCH) return fail(ctx, MN_EINVAL, "mn_verify_sample: B = %d", B);
+  if (k_max < 0 || k_max > 4096) return fail(ctx, MN_EINVAL, "mn_verify_sample: k_max = %d", k_max);
+  if (M < 0 || (long)M > (long)B * (k_max + 1)) return fail(ctx, MN_EINVAL, "mn_verify_sample: M = %d rows for B = %d, k_max = %d", M, B, k_max);
+  if (vocab < 1 || vocab > verify_sample_max_vocab()) return fail(ctx, MN_EUNSUPPORTED, "mn_verify_sample: vocab = %d", vocab);
+  if (!(temperature > 0.0) || !(temperature < INFINITY)) return fail(ctx, MN_EINVAL, "mn_verify_sample: temperature must be positive and finite");
+  if (B > 0 && (!logits || !spec_len || !greedy || !sampled)) return fail(ctx, MN_ENULL, "mn_verify_sample: a required pointer is NULL");
+  if (B > 0 && k_max > 0 && (!voted || !draft_probs)) return fail(ctx, MN_ENULL, "mn_verify_sample: voted or draft_probs is NULL");
+  {
+    Tap t(ctx ? &ctx->prof : nullptr, MN_PROF_ACCEPT, (hipStream_t)stream);
+    launch_verify_sample(logits, voted, draft_probs, spec_len, greedy, B, k_max, M, vocab, temperature, seed, step, sampled,
+                         dev_status, (hipStream_t)stream);
+  }
+  return hip_check(ctx, "mn_verify_sample");
+}
+
 // ---- shared checks --------------------------------------------------------------------------------
 static mn_status check_kv(mn_ctx* c, const mn_kv* kv, int max_ctx, const char* who) {
   if (!kv) return fail(c, MN_ENULL, "%s: kv is NULL", who);

@@ -16,6 +16,12 @@ void launch_accept_commit(const int32_t* voted, const int32_t* greedy, const int
                           int32_t* out_tokens, int32_t* n_out, int32_t* next_last_tok, int32_t* blocks_in_use,
                           int32_t* dev_status, hipStream_t st);
 
+// ---- stochastic.hip ----
+void launch_verify_sample(const float* logits, const int32_t* voted, const float* draft_probs, const int32_t* spec_len,
+                          const int32_t* greedy, int B, int k_max, int M, int V, double temperature, uint64_t seed,
+                          uint64_t step, int32_t* sampled, int32_t* dev_status, hipStream_t st);
+int verify_sample_max_vocab();
+
 // ---- rows.hip ----
 struct PrepArgs {
   const int32_t *last_tok, *voted, *spec_len, *ctx_lens, *block_tables;

@@ -228,9 +228,24 @@ class VerifySession:
                             self.greedy.data_ptr(), self.logits.data_ptr() if self.logits is not None else None,
                             self.workspace.data_ptr(), self.ws_bytes, self.dev_status.data_ptr(), stream_ptr())
 
-    def accept(self, spec_len: torch.Tensor, voted: Optional[torch.Tensor] = None) -> None:
+    def sample(self, spec_len: torch.Tensor, M: int, draft_probs: torch.Tensor, temperature: float, seed: int,
+               step: int, voted: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """Stochastic verification on the logits of the last forward: fills and returns `sampled`, which
+        accept(..., tokens=sampled) takes in place of the greedy tokens."""
+        assert self.logits is not None, "the session was built without a logits buffer"
         v = self.voted if voted is None else voted
-        B.mn_accept_and_commit(self.model.ctx, v.data_ptr(), self.greedy.data_ptr(), spec_len.data_ptr(), self.B,
+        if not hasattr(self, "sampled"):
+            self.sampled = torch.full_like(self.greedy, -7)
+        B.mn_verify_sample(self.model.ctx, self.logits.data_ptr(), v.data_ptr(), draft_probs.data_ptr(),
+                           spec_len.data_ptr(), self.greedy.data_ptr(), self.B, self.k_max, M, self.model.desc.vocab,
+                           temperature, seed, step, self.sampled.data_ptr(), self.dev_status.data_ptr(), stream_ptr())
+        return self.sampled
+
+    def accept(self, spec_len: torch.Tensor, voted: Optional[torch.Tensor] = None,
+               tokens: Optional[torch.Tensor] = None) -> None:
+        v = self.voted if voted is None else voted
+        g = self.greedy if tokens is None else tokens
+        B.mn_accept_and_commit(self.model.ctx, v.data_ptr(), g.data_ptr(), spec_len.data_ptr(), self.B,
                                self.k_max, self.kv.c, self.accepted_len.data_ptr(), self.out_tokens.data_ptr(),
                                self.n_out.data_ptr(), self.next_last_tok.data_ptr(), self.blocks_in_use.data_ptr(),
                                self.dev_status.data_ptr(), stream_ptr())
