@@ -283,6 +283,32 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     acr_us = e0.elapsed_time(e1) / 50 * 1e3
+    # the general (stochastic) verification rule on this step's own scores: q = softmax(scores + N(0,1)) stands
+    # in for the SSM's distributions (harness arithmetic); device time of mn_verify_sample per call; informational
+    ses.logits = torch.empty((M, desc.vocab), dtype=torch.float32, device=dev)
+    kvd.ctx_lens.copy_(ctx0)
+    ses.forward(last, spec, h_spec)
+    gq = torch.Generator(device=dev).manual_seed(wl.seed)
+    q_probs = torch.zeros((B, max(1, k_max), desc.vocab), dtype=torch.float32, device=dev)
+    row = 0
+    for b in range(B):
+        kb = int(ks[b])
+        if kb:
+            z = ses.logits[row:row + kb] + torch.randn((kb, desc.vocab), generator=gq, device=dev)
+            q_probs[b, :kb] = torch.softmax(z, dim=-1)
+        row += kb + 1
+    ses.sample(spec, M, q_probs, 1.0, wl.seed, 0)
+    e0.record()
+    for i in range(20):
+        ses.sample(spec, M, q_probs, 1.0, wl.seed, i + 1)
+    e1.record()
+    torch.cuda.synchronize()
+    sample_us = e0.elapsed_time(e1) / 20 * 1e3
+    sample_survivors = int((ses.sampled[:, :max(1, k_max)] == ses.voted)[torch.arange(max(1, k_max), device=dev)[None, :]
+                                                                        < spec[:, None]].sum().item())
+    kvd.ctx_lens.copy_(ctx0)
+    ses.logits = None
+    del q_probs
     # the step before the path: n SSMs of the paper's small-model shape drafting k tokens each through the
     # same library (random weights, synthetic caches of the same contexts); informational
     draft_ms = None
@@ -368,6 +394,9 @@ def main():
         "acceptance_rate": float(acc.sum()) / max(1, int(ks.sum())),
         "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
         "setup_s": t_setup,
+        "stochastic_rule": {"verify_sample_us": sample_us, "temperature": 1.0, "positions": M,
+                            "speculated_tokens_surviving": sample_survivors, "speculated_tokens": int(ks.sum()),
+                            "note": "mn_verify_sample on this step's scores; q = softmax(scores + N(0,1))"},
         "after_step": {"acr_update_us": acr_us, "acr": [None if x != x else x for x in acr_buf.cpu().tolist()],
                        "selector_observe_ns_incl_binding": sel_ns,
                        "ssm_drafting_ms": draft_ms,

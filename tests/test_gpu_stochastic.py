@@ -169,3 +169,70 @@ def test_emitted_token_distribution(hb):
         counts += np.bincount(res[2][:, 0], minlength=V)
     N = B * steps
     assert np.abs(counts / N - o).max() < 4.0 * np.sqrt(0.25 / N)
+
+
+def test_tiny_model_forward_sample_accept_end_to_end(hb):
+    """The whole stochastic step on the small fp32 model: prompts prefilled through the library, speculated
+    tokens drawn from distributions near the LLM's, forward -> mn_verify_sample -> accept + commit against the
+    oracle's own forward and rule.  The two forwards agree to 1e-4 on the scores; at the low temperature used
+    here (the model's scores are nearly flat, so T = 0.03 is what makes its distribution peaked enough for a
+    draw to have a clear answer) that is up to 2 * 1e-4 / T = 7e-3 relative on a probability, so a sequence is
+    compared only when every decision the oracle took cleared its threshold by 1e-2 (the others are counted and
+    must be few)."""
+    harness, binding = hb
+    wl = synth.WORKLOADS[0]
+    desc = wl.desc
+    W = synth.make_weights(desc, wl.seed)
+    model = harness.DeviceModel.from_host(desc, W)
+    g = synth.stream(4102, 0)
+    B, k, T, noise = 16, 4, 0.03, 0.02
+    lens = [int(x) for x in g.integers(5, 24, size=B)]
+    prompts = [g.integers(0, desc.vocab, size=n).astype(np.int32) for n in lens]
+    kvh = synth.make_paged_kv(desc, [0] * B, [max(lens) + k + 1] * B, wl.seed, scatter=True, fill=True)
+    kvd = harness.DeviceKV.from_host(desc, kvh)
+    # ---- prefill: ctx = 0, the prompt's tokens as one causal block ----
+    pmax = max(lens) - 1
+    pre = harness.VerifySession(model, kvd, B, pmax, 1, max(lens))
+    pv = np.full((B, pmax), -1, np.int32)
+    for b, p in enumerate(prompts):
+        pv[b, :len(p) - 1] = p[1:]
+    t_last, t_k, t_v = _dev([p[0] for p in prompts]), _dev([n - 1 for n in lens]), _dev(pv)
+    pre.forward(t_last, t_k, [n - 1 for n in lens], voted=t_v)
+    torch.cuda.synchronize()
+    assert pre.dev_status.item() == 0
+    kvd.ctx_lens.copy_(_dev(lens))
+    caches = [orc.SeqCache(desc.n_layers, desc.n_kv_heads, desc.head_dim) for _ in range(B)]
+    pre_logits = orc.decoder_step(desc, W, [p.tolist() for p in prompts], caches)
+    last = [int(np.argmax(l[-1])) for l in pre_logits]
+    # ---- speculation: token j drawn from q_j = softmax((LLM scores of the prefix + noise) / T) ----
+    voted = np.zeros((B, k), np.int32)
+    q = np.zeros((B, k, desc.vocab), np.float32)
+    for b in range(B):
+        toks = prompts[b].tolist() + [last[b]]
+        for j in range(k):
+            z = orc.decoder_full(desc, W, toks)[-1] + noise * g.normal(0.0, 1.0, desc.vocab)
+            p = _softmax64(z / T)
+            q[b, j] = p.astype(np.float32)
+            voted[b, j] = int(g.choice(desc.vocab, p=p))
+            toks.append(int(voted[b, j]))
+    # ---- the step on the device ----
+    ses = harness.VerifySession(model, kvd, B, k, 1, max(lens) + k + 1, want_logits=True)
+    t_last, t_k, t_v, t_q = _dev(last), _dev([k] * B), _dev(voted), _dev(q, torch.float32)
+    ses.forward(t_last, t_k, [k] * B, voted=t_v)
+    sampled = ses.sample(t_k, B * (k + 1), t_q, T, seed=31, step=2, voted=t_v)
+    ses.accept(t_k, voted=t_v, tokens=sampled)
+    torch.cuda.synchronize()
+    assert ses.dev_status.item() == 0
+    # ---- the step on the oracle ----
+    want_logits = orc.decoder_step(desc, W, [[last[b]] + voted[b].tolist() for b in range(B)], caches)
+    got_logits = ses.logits.cpu().numpy().reshape(B, k + 1, desc.vocab)
+    acc, out, ctx1 = ses.accepted_len.cpu().numpy(), ses.out_tokens.cpu().numpy(), kvd.ctx_lens.cpu().numpy()
+    compared = 0
+    for b in range(B):
+        assert np.abs(got_logits[b] - want_logits[b]).max() < 1e-4
+        a, toks, margin = orc.accept_stochastic(voted[b], want_logits[b], q[b], k, T, 31, 2, b)
+        if margin < 1e-2:
+            continue
+        compared += 1
+        assert acc[b] == a and out[b, :a + 1].tolist() == toks and ctx1[b] == lens[b] + a + 1
+    assert compared >= B - 4
