@@ -2,7 +2,7 @@
 // extended to more than one input token per sequence once a cache exists).  Query row j of
 // sequence b sees the cached keys [0, ctx_b) and the new keys 0..j of its own sequence.
 //
-// Two kernels:
+// Three kernels:
 //  * attn_mfma_kernel  bf16 pages / fp16 queries, head_dim 128, 16-token blocks.  The G*q_b query rows that share one
 //    KV head (grouped-query attention stacks the group's heads on top of the speculated tokens)
 //    are the column index of every MFMA, so each K/V byte is read once per KV head.  Key tiles go
@@ -10,6 +10,8 @@
 //    four waves: the page layouts put 8 consecutive contraction elements in 16 bytes for both
 //    products (head-dim chunks for K, tokens for V).  The KV range of a sequence is split across
 //    workgroups; partial (max, sum, output) triples are merged by attn_merge_kernel.
+//  * attn_fewrow_kernel  bf16 pages / fp16 queries, head_dim 64, at most 4 stacked query rows per KV head
+//    (a small drafting model decoding token by token): wide loads, plain FMA.
 //  * attn_generic_kernel  any storage type / head_dim / block size; plain FMA, one (row, head)
 //    per workgroup.  Used by the fp32 model and as the fallback.
 #include "launch.h"
@@ -517,6 +519,200 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(const float* __restrict
 }
 
 // ------------------------------------------------------------------------------------------
+// few-row kernel (bf16 pages, fp16 queries, head_dim 64, 16-token blocks, at most 4 stacked rows per KV head)
+// ------------------------------------------------------------------------------------------
+// The shape of a small model decoding one token per sequence (the SSMs that draft for the vote): one or
+// a few query rows against the whole context.  There is nothing for a matrix instruction to share, the
+// job is to keep the K/V pages streaming with wide loads.  Workgroup = one (KV head, sequence), 8 or 16 waves;
+// a wave takes the key range in steps of four blocks (64 keys):
+//  * K: lane (token t = lane % 16, group g = lane / 16) loads head-dim chunks g and g + 4 of token t of
+//    each of the four blocks (16 bytes each, a quarter wave reads 256 contiguous bytes), multiplies
+//    them with its part of q and adds up over the four groups with two cross-lane steps; group g then
+//    keeps the score of block g: one key per lane;
+//  * softmax: running maximum per wave (log2 units), per-lane partial sums of the probabilities;
+//  * V: lane = head dimension; the 64 probabilities go through LDS (read back as broadcasts) and meet
+//    the 16 tokens x 4 blocks of that dimension (32 contiguous bytes per block).
+// This step's own keys (side buffers) are added by wave 0 one by one; the waves' (max, sum, output)
+// are merged through LDS.
+constexpr int FR_HD = 64;
+
+__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+template <int RR, int FR_NW>  // rows held, waves per workgroup
+__global__ void __launch_bounds__(FR_NW * 64) attn_fewrow_kernel(AttnArgs a) {
+  __shared__ __attribute__((aligned(16))) float s_p[FR_NW][RR][64];
+  __shared__ float s_o[FR_NW][RR][64];
+  __shared__ float s_m[FR_NW][RR], s_l[FR_NW][RR];
+  const int kvh = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int t = lane & 15, g = lane >> 4;
+  const int G = a.H / a.Hkv;
+  const int row0 = a.rows.seq_row0[b];
+  const int qb = a.rows.seq_row0[b + 1] - row0;
+  if (qb <= 0) return;                       // (whole workgroup)
+  const int R = min(G * qb, RR);             // stacked rows r = j*G + gi (the host launches RR >= G * max_q)
+  f16_t* out = reinterpret_cast<f16_t*>(a.out);
+  if (!a.rows.seq_ok[b]) {                   // disabled sequence: zeros (whole workgroup)
+    if (wave < R) out[((size_t)(row0 + wave / G) * a.H + kvh * G + wave % G) * FR_HD + lane] = (f16_t)0.f;
+    return;
+  }
+  const int ctx = a.rows.seq_ctx[b];
+  const f16_t* Q = reinterpret_cast<const f16_t*>(a.q);
+  const f16_t* Kn = reinterpret_cast<const f16_t*>(a.knew);
+  const f16_t* Vn = reinterpret_cast<const f16_t*>(a.vnew);
+  const int n_pk = Kn ? ctx : ctx + qb;      // keys that live in the pages
+  const float sscale = rsqrtf((float)FR_HD) * LOG2E;
+
+  float qf[RR][16];   // q of row r, head-dim chunks g and g + 4 (the lane's share of a dot product)
+  float qe[RR];       // q of row r, head dimension `lane`
+  float m[RR], l[RR], acc[RR];
+  int lim[RR];        // keys [0, lim) of the pages are visible to row r
+#pragma unroll
+  for (int r = 0; r < RR; ++r) {
+    m[r] = -INFINITY;
+    l[r] = 0.f;
+    acc[r] = 0.f;
+    qe[r] = 0.f;
+    lim[r] = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) qf[r][i] = 0.f;
+    if (r < R) {
+      const f16_t* qp = Q + ((size_t)(row0 + r / G) * a.H + kvh * G + r % G) * FR_HD;
+      const f16x8 p0 = *reinterpret_cast<const f16x8*>(qp + 8 * g);
+      const f16x8 p1 = *reinterpret_cast<const f16x8*>(qp + 8 * (g + 4));
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        qf[r][i] = (float)p0[i] * sscale;
+        qf[r][8 + i] = (float)p1[i] * sscale;
+      }
+      qe[r] = (float)qp[lane] * sscale;
+      lim[r] = min(n_pk, ctx + r / G + 1);
+    }
+  }
+
+  const int32_t* bt = a.kv.block_tables + (size_t)b * a.kv.max_blocks_per_seq;
+  const int last_blk = max(0, (n_pk - 1) / BS);
+  const uint32_t blk_last = (uint32_t)max(a.kv.num_blocks - 1, 0);
+  const size_t head_stride = (size_t)FR_HD * BS * sizeof(bf16_t);  // one (block, KV head) of K or of V
+  const char* Kb = reinterpret_cast<const char*>(a.kv.k) + (size_t)kvh * head_stride + (size_t)(g * BS + t) * 16;
+  const char* Vb = reinterpret_cast<const char*>(a.kv.v) + (size_t)kvh * head_stride + (size_t)lane * (BS * sizeof(bf16_t));
+  const int n_steps = (n_pk + 63) >> 6;
+  for (int s = wave; s < n_steps; s += FR_NW) {
+    uint4 kp[4][2], vp[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t blk = min((uint32_t)bt[min(4 * s + i, last_blk)], blk_last);
+      const size_t off = (size_t)blk * a.Hkv * head_stride;
+      kp[i][0] = *reinterpret_cast<const uint4*>(Kb + off);
+      kp[i][1] = *reinterpret_cast<const uint4*>(Kb + off + 4 * BS * 16);
+      vp[i][0] = *reinterpret_cast<const uint4*>(Vb + off);
+      vp[i][1] = *reinterpret_cast<const uint4*>(Vb + off + 16);
+    }
+    const int key = (4 * s + g) * BS + t;    // the key whose score this lane keeps
+#pragma unroll
+    for (int r = 0; r < RR; ++r) {
+      float sv = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float d = 0.f;
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          const uint4 w = kp[i][c];
+          const float* qq = &qf[r][8 * c];
+          d = fmaf(qq[0], bf_lo(w.x), d); d = fmaf(qq[1], bf_hi(w.x), d);
+          d = fmaf(qq[2], bf_lo(w.y), d); d = fmaf(qq[3], bf_hi(w.y), d);
+          d = fmaf(qq[4], bf_lo(w.z), d); d = fmaf(qq[5], bf_hi(w.z), d);
+          d = fmaf(qq[6], bf_lo(w.w), d); d = fmaf(qq[7], bf_hi(w.w), d);
+        }
+        d += __shfl_xor(d, 16);
+        d += __shfl_xor(d, 32);
+        if (g == i) sv = d;
+      }
+      if (key >= lim[r]) sv = -INFINITY;
+      const float new_m = fmaxf(m[r], wave_max(sv));
+      const float alpha = (m[r] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m[r] - new_m);
+      const float p = (sv == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sv - new_m);
+      m[r] = new_m;
+      l[r] = l[r] * alpha + p;
+      acc[r] *= alpha;
+      s_p[wave][r][lane] = p;
+    }
+    // (the wave reads back what it has just written: LDS operations of one wave stay in order)
+#pragma unroll
+    for (int r = 0; r < RR; ++r) {
+      float o = acc[r];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float4* pp = reinterpret_cast<const float4*>(&s_p[wave][r][16 * i]);
+        const float4 p0 = pp[0], p1 = pp[1], p2 = pp[2], p3 = pp[3];
+        const uint4 v0 = vp[i][0], v1 = vp[i][1];
+        o = fmaf(p0.x, bf_lo(v0.x), o); o = fmaf(p0.y, bf_hi(v0.x), o);
+        o = fmaf(p0.z, bf_lo(v0.y), o); o = fmaf(p0.w, bf_hi(v0.y), o);
+        o = fmaf(p1.x, bf_lo(v0.z), o); o = fmaf(p1.y, bf_hi(v0.z), o);
+        o = fmaf(p1.z, bf_lo(v0.w), o); o = fmaf(p1.w, bf_hi(v0.w), o);
+        o = fmaf(p2.x, bf_lo(v1.x), o); o = fmaf(p2.y, bf_hi(v1.x), o);
+        o = fmaf(p2.z, bf_lo(v1.y), o); o = fmaf(p2.w, bf_hi(v1.y), o);
+        o = fmaf(p3.x, bf_lo(v1.z), o); o = fmaf(p3.y, bf_hi(v1.z), o);
+        o = fmaf(p3.z, bf_lo(v1.w), o); o = fmaf(p3.w, bf_hi(v1.w), o);
+      }
+      acc[r] = o;
+    }
+  }
+
+  // this step's own keys: row (j, gi) sees the new keys 0..j
+  if (Kn && wave == 0) {
+    for (int jn = 0; jn < qb; ++jn) {
+      const size_t src = ((size_t)(row0 + jn) * a.Hkv + kvh) * FR_HD + lane;
+      const float kk = (float)Kn[src], vv = (float)Vn[src];
+#pragma unroll
+      for (int r = 0; r < RR; ++r) {
+        if (r < R && jn <= r / G) {          // (uniform over the wave)
+          const float sv = wave_sum(qe[r] * kk);
+          const float new_m = fmaxf(m[r], sv);
+          const float alpha = (m[r] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m[r] - new_m);
+          const float p = __builtin_amdgcn_exp2f(sv - new_m);
+          m[r] = new_m;
+          l[r] = l[r] * alpha + (lane == 0 ? p : 0.f);
+          acc[r] = acc[r] * alpha + p * vv;
+        }
+      }
+    }
+  }
+
+#pragma unroll
+  for (int r = 0; r < RR; ++r) {
+    const float lt = wave_sum(l[r]);
+    s_o[wave][r][lane] = acc[r];
+    if (lane == 0) {
+      s_m[wave][r] = m[r];
+      s_l[wave][r] = lt;
+    }
+  }
+  __syncthreads();
+  {
+    const int r = wave;                      // wave r merges row r (R <= 4 <= FR_NW)
+    if (r < R) {
+      float gm = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < FR_NW; ++w) gm = fmaxf(gm, s_m[w][r]);
+      float lt = 0.f, o = 0.f;
+#pragma unroll
+      for (int w = 0; w < FR_NW; ++w) {
+        const float f = (s_m[w][r] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(s_m[w][r] - gm);
+        lt += f * s_l[w][r];
+        o += f * s_o[w][r][lane];
+      }
+      out[((size_t)(row0 + r / G) * a.H + kvh * G + r % G) * FR_HD + lane] = (f16_t)(lt > 0.f ? o / lt : 0.f);
+    }
+  }
+}
+
+static bool fewrow_supported(const AttnArgs& a, int G) {
+  return a.dtype == MN_DT_BF16 && a.hd == FR_HD && a.kv.block_size == BS && a.Hkv > 0 && a.H % a.Hkv == 0 &&
+         G * a.max_q <= 4;
+}
+
+// ------------------------------------------------------------------------------------------
 // launch
 // ------------------------------------------------------------------------------------------
 // Largest number of KV splits any sequence of the batch may get (the grid's x extent; every sequence then
@@ -583,6 +779,19 @@ void launch_attention(const AttnArgs& a, hipStream_t st) {
       const int waves = a.M * a.H;
       attn_merge_kernel<<<(waves + 3) / 4, 256, 0, st>>>(o_part, ml_part, n_splits, a.M, a.H, a.rows, reinterpret_cast<f16_t*>(a.out));
     }
+    return;
+  }
+  static const int generic_only = [] {
+    const char* e = getenv("MN_ATTN_GENERIC");
+    return e ? atoi(e) : 0;
+  }();
+  if (!generic_only && fewrow_supported(a, G)) {
+    const dim3 fg(a.Hkv, a.B);
+    const int rr = G * a.max_q;
+    // a single row leaves registers for 16 waves (one step of 64 keys each at 1024 keys of context)
+    if (rr <= 1) attn_fewrow_kernel<1, 16><<<fg, 1024, 0, st>>>(a);
+    else if (rr <= 2) attn_fewrow_kernel<2, 8><<<fg, 512, 0, st>>>(a);
+    else attn_fewrow_kernel<4, 8><<<fg, 512, 0, st>>>(a);
     return;
   }
   dim3 grid(a.H, a.M);

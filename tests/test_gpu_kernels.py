@@ -143,6 +143,12 @@ def test_proj_gemm_matches_fp64(hb, M, N, K, split):
     ("gqa-ragged", synth.LLAMA2_70B.with_layers(1), [256, 2047, 513, 15, 16, 1, 300], [1, 16, 7, 0, 3, 16, 12]),
     ("mha-opt13b", synth.OPT_13B.with_layers(1), [512, 100, 31], [4, 4, 0]),
     ("fp32-generic", synth.OPT_TINY.with_layers(1), [64, 0, 300], [4, 63, 2]),
+    # head_dim 64, few rows per KV head: the drafting models' decode shape and its neighbours
+    ("fewrow-mha-decode", synth.LLAMA_160M.with_layers(1), [1024, 1000, 37, 0, 63, 64, 65, 2047], [0] * 8),
+    ("fewrow-mha-k3", synth.LLAMA_160M.with_layers(1), [300, 17, 0, 640], [3, 1, 2, 0]),
+    ("fewrow-gqa2", synth.ModelDesc(synth.ARCH_LLAMA, synth.DT_BF16, 1, 512, 8, 4, 64, 1024, 64, 4096), [129, 5, 0, 1500], [1, 0, 1, 1]),
+    ("fewrow-gqa4", synth.ModelDesc(synth.ARCH_LLAMA, synth.DT_BF16, 1, 512, 8, 2, 64, 1024, 64, 4096), [200, 16, 1], [0, 0, 0]),
+    ("hd64-many-rows-generic", synth.LLAMA_160M.with_layers(1), [100, 40], [7, 4]),
 ])
 def test_attention_matches_oracle(hb, name, desc, ctx_lens, spec_lens):
     harness, binding = hb

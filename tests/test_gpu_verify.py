@@ -194,3 +194,13 @@ def test_llama70b_width_ragged_paged(hb):
     ks = [1, 16, 5, 9, 16, 2, 7, 12, 3, 1, 10, 4]
     err, dec = _reduced_case(hb, wl, 1, 12, 3, ctx_override=ctx, k_override=ks)
     print("llama70b-width ragged max |dlogit| = %.2e, decisive %d/12" % (err, dec))
+
+
+def test_llama160m_width_few_rows(hb):
+    # the drafting models' shape (head_dim 64, bf16 storage) with 1 to 4 scored positions per sequence: the
+    # few-row attention kernel with this step's own keys coming from the side buffers; 2 of 12 layers
+    wl = synth.Workload("llama160m-bf16-few-rows", synth.LLAMA_160M, 10, 0, 0, 0, 3, 3, 0.3, seed=1240)
+    ctx = [512, 1, 63, 64, 65, 1000, 16, 129, 300, 47]
+    ks = [0, 3, 1, 2, 0, 3, 3, 0, 1, 2]
+    err, dec = _reduced_case(hb, wl, 2, 10, 4, ctx_override=ctx, k_override=ks)
+    print("llama160m-width few rows max |dlogit| = %.2e, decisive %d/10" % (err, dec))
