@@ -234,13 +234,31 @@ mn_status mn_accept_and_commit(mn_ctx *ctx, const int32_t *voted, const int32_t 
  * first two output words give the 53-bit uniform number of the survival test (top 27 bits of word 0,
  * top 26 of word 1), the last two that of the draw, which takes the first token, in token order, whose
  * running sum of mass exceeds u times the total.  The same (seed, step, b, j) always gives the same
- * numbers: the caller advances `step` once per verification step.
- * Errors: temperature must be positive and finite; vocab <= 2^21; k_max <= 4096.  Rows that do not add
+ * numbers: the caller advances `step` once per verification step.  The top byte of the counter's last
+ * word (above the 56 bits of `step`) is 0 here and 1 + i for drafting SSM i (mn_draft_sample), so one seed
+ * serves all of them without shared numbers.
+ * Errors: temperature must be positive and finite; step < 2^56; vocab <= 2^21; k_max <= 4096.  Rows that do not add
  * up to M set MN_DEV_SPEC_LEN in *dev_status and give -1.  ctx may be NULL. */
 mn_status mn_verify_sample(mn_ctx *ctx, const float *logits, const int32_t *voted, const float *draft_probs,
                            const int32_t *spec_len, const int32_t *greedy, int B, int k_max, int M, int vocab,
                            double temperature, uint64_t seed, uint64_t step, int32_t *sampled, int32_t *dev_status,
                            void *stream);
+
+/* The drafting side of the stochastic rule (section 2.1: the SSM predicts its tokens from its own
+ * distribution q).  For each sequence b, q_b = softmax(logits[b] / temperature) is rounded to fp32 and,
+ * when probs is given, written to probs[b * probs_stride + v]; the token is drawn from exactly those
+ * fp32 values (inverse CDF in token order, as in mn_verify_sample) and written to
+ * tokens[b * token_stride].  The strides (in elements) let the caller aim both at their final place:
+ * tokens at drafts[b][ssm][t] of mn_mv_vote's input (stride n * k_max), probs at row [b][t] of a
+ * [B][k_max][vocab] array (stride k_max * vocab) that mn_verify_sample reads for the SSM whose draft wins
+ * the vote.
+ *   logits dev [B][vocab] fp32: one row per sequence (an SSM's mn_verify_forward with spec_len = 0)
+ * Random numbers: Philox-4x32-10, key = seed, counter = (b, t, step, consumer 1 + ssm); words 2, 3 give
+ * the uniform number of the draw.  0 <= ssm < MN_MAX_DRAFTS, t >= 0, step < 2^56, temperature positive
+ * and finite, vocab <= 2^21, token_stride >= 1, probs_stride >= vocab.  ctx may be NULL. */
+mn_status mn_draft_sample(mn_ctx *ctx, const float *logits, int B, int vocab, double temperature, uint64_t seed,
+                          uint64_t step, int ssm, int t, int32_t *tokens, long token_stride, float *probs,
+                          long probs_stride, void *stream);
 
 /* ---- after the step: closing the loop (sections 3.2 and 3.3) --------------------------------- */
 

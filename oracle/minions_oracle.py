@@ -412,10 +412,13 @@ def unit_double(hi: int, lo: int) -> float:
     return float(((int(hi) >> 5) << 26) + (int(lo) >> 6)) / float(1 << 53)
 
 
-def verify_uniforms(seed: int, step: int, b: int, j: int) -> Tuple[float, float]:
+def verify_uniforms(seed: int, step: int, b: int, j: int, consumer: int = 0) -> Tuple[float, float]:
     """The two uniform numbers position j of sequence b consumes in step `step`: the first decides
-    acceptance, the second picks the replacement (or bonus) token.  Key = seed, counter = (b, j, step)."""
-    w = philox4x32((b, j, step & _M32, (step >> 32) & _M32), (seed & _M32, (seed >> 32) & _M32))
+    acceptance, the second picks the replacement (or bonus) token.  Key = seed, counter = (b, j, step);
+    the top byte of the counter's last word names the consumer (0 = the verifier, 1 + i = drafting SSM i),
+    so that under one seed no two of them see the same numbers; steps stay below 2^56."""
+    assert 0 <= step < (1 << 56) and 0 <= consumer < 256
+    w = philox4x32((b, j, step & _M32, ((step >> 32) & 0xFFFFFF) | (consumer << 24)), (seed & _M32, (seed >> 32) & _M32))
     return unit_double(w[0], w[1]), unit_double(w[2], w[3])
 
 
@@ -439,6 +442,17 @@ def sample_cdf(mass: np.ndarray, u: float) -> Tuple[int, float]:
     below = float(cum[v - 1]) if v > 0 else -np.inf
     gap = min(abs(float(cum[v]) - target), abs(target - below)) / total
     return v, gap
+
+
+def draft_sample(logits_row: np.ndarray, temperature: float, seed: int, step: int, ssm: int, b: int, t: int):
+    """A drafting SSM's next token (section 2.1: the SSM predicts its tokens from its own distribution q):
+    q = softmax(scores / T) rounded to fp32, which is what the verifier will be handed, and a token drawn
+    from exactly those values by the inverse CDF in token order.  Returns (token, q as fp32, relative
+    distance of the draw from the nearest boundary)."""
+    q32 = llm_probs(logits_row, temperature).astype(np.float32)
+    _, u = verify_uniforms(seed, step, b, t, consumer=1 + ssm)
+    tok, gap = sample_cdf(q32.astype(np.float64), u)
+    return tok, q32, gap
 
 
 def accept_stochastic(voted: Sequence[int], logits: np.ndarray, draft_probs: np.ndarray, k: int,

@@ -23,7 +23,7 @@ MN_MAX_DRAFTS, MN_MAX_BATCH, MN_MAX_SPLIT_K = 64, 4096, 16
 EXPORTS = ("mn_create", "mn_destroy", "mn_last_error", "mn_status_str", "mn_workspace_bytes", "mn_mv_vote",
            "mn_verify_forward", "mn_accept_and_commit", "mn_proj_gemm", "mn_attention", "mn_profile_enable",
            "mn_profile_collect", "mn_packed_weight_bytes", "mn_pack_weight", "mn_acr_update",
-           "mn_verify_sample",
+           "mn_verify_sample", "mn_draft_sample",
            "mn_selector_create", "mn_selector_destroy", "mn_selector_observe", "mn_selector_current",
            "mn_selector_adjustments", "mn_probe_stream_read", "mn_probe_mfma")
 PROF_KINDS = ("prepare", "norm", "gemm", "rope_append", "attention", "act", "argmax", "vote", "accept")
@@ -83,6 +83,9 @@ def _load() -> C.CDLL:
     lib.mn_verify_sample.restype = i32
     lib.mn_verify_sample.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, C.c_double, C.c_uint64, C.c_uint64,
                                      vp, vp, vp]
+    lib.mn_draft_sample.restype = i32
+    lib.mn_draft_sample.argtypes = [vp, vp, i32, i32, C.c_double, C.c_uint64, C.c_uint64, i32, i32, vp, C.c_long, vp,
+                                    C.c_long, vp]
     lib.mn_acr_update.restype = i32
     lib.mn_acr_update.argtypes = [vp, vp, vp, vp, vp, i32, i32, C.c_double, C.c_double, C.c_float, C.c_float, vp, vp, vp]
     lib.mn_selector_create.restype = i32
@@ -198,6 +201,12 @@ def mn_verify_sample(ctx, logits, voted, draft_probs, spec_len, greedy, B, k_max
                      sampled, dev_status=None, stream=None) -> None:
     _check(lib.mn_verify_sample(ctx, logits, voted, draft_probs, spec_len, greedy, B, k_max, M, vocab, temperature,
                                 seed, step, sampled, dev_status, stream), ctx)
+
+
+def mn_draft_sample(ctx, logits, B, vocab, temperature, seed, step, ssm, t, tokens, token_stride, probs=None,
+                    probs_stride=0, stream=None) -> None:
+    _check(lib.mn_draft_sample(ctx, logits, B, vocab, temperature, seed, step, ssm, t, tokens, token_stride, probs,
+                               probs_stride, stream), ctx)
 
 
 def mn_acr_update(ctx, voted_ssm, accepted_len, spec_len, n_out, B, n, reward_threshold, punish_threshold,

@@ -265,6 +265,7 @@ extern "C" mn_status mn_verify_sample(mn_ctx* ctx, const float* logits, const in
   if (M < 0 || (long)M > (long)B * (k_max + 1)) return fail(ctx, MN_EINVAL, "mn_verify_sample: M = %d rows for B = %d, k_max = %d", M, B, k_max);
   if (vocab < 1 || vocab > verify_sample_max_vocab()) return fail(ctx, MN_EUNSUPPORTED, "mn_verify_sample: vocab = %d", vocab);
   if (!(temperature > 0.0) || !(temperature < INFINITY)) return fail(ctx, MN_EINVAL, "mn_verify_sample: temperature must be positive and finite");
+  if (step >> 56) return fail(ctx, MN_EINVAL, "mn_verify_sample: step must be below 2^56");
   if (B > 0 && (!logits || !spec_len || !greedy || !sampled)) return fail(ctx, MN_ENULL, "mn_verify_sample: a required pointer is NULL");
   if (B > 0 && k_max > 0 && (!voted || !draft_probs)) return fail(ctx, MN_ENULL, "mn_verify_sample: voted or draft_probs is NULL");
   {
@@ -273,6 +274,25 @@ extern "C" mn_status mn_verify_sample(mn_ctx* ctx, const float* logits, const in
                          dev_status, (hipStream_t)stream);
   }
   return hip_check(ctx, "mn_verify_sample");
+}
+
+extern "C" mn_status mn_draft_sample(mn_ctx* ctx, const float* logits, int B, int vocab, double temperature, uint64_t seed,
+                                     uint64_t step, int ssm, int t, int32_t* tokens, long token_stride, float* probs,
+                                     long probs_stride, void* stream) {
+  if (B < 0 || B > MN_MAX_BATCH) return fail(ctx, MN_EINVAL, "mn_draft_sample: B = %d", B);
+  if (vocab < 1 || vocab > verify_sample_max_vocab()) return fail(ctx, MN_EUNSUPPORTED, "mn_draft_sample: vocab = %d", vocab);
+  if (!(temperature > 0.0) || !(temperature < INFINITY)) return fail(ctx, MN_EINVAL, "mn_draft_sample: temperature must be positive and finite");
+  if (step >> 56) return fail(ctx, MN_EINVAL, "mn_draft_sample: step must be below 2^56");
+  if (ssm < 0 || ssm >= MN_MAX_DRAFTS) return fail(ctx, MN_EINVAL, "mn_draft_sample: ssm = %d", ssm);
+  if (t < 0) return fail(ctx, MN_EINVAL, "mn_draft_sample: t = %d", t);
+  if (token_stride < 1 || (probs && probs_stride < vocab)) return fail(ctx, MN_EINVAL, "mn_draft_sample: strides");
+  if (B > 0 && (!logits || !tokens)) return fail(ctx, MN_ENULL, "mn_draft_sample: a required pointer is NULL");
+  {
+    Tap tp(ctx ? &ctx->prof : nullptr, MN_PROF_VOTE, (hipStream_t)stream);
+    launch_draft_sample(logits, B, vocab, temperature, seed, step, ssm, t, tokens, token_stride, probs, probs_stride,
+                        (hipStream_t)stream);
+  }
+  return hip_check(ctx, "mn_draft_sample");
 }
 
 // ---- shared checks --------------------------------------------------------------------------------

@@ -20,6 +20,8 @@ void launch_accept_commit(const int32_t* voted, const int32_t* greedy, const int
 void launch_verify_sample(const float* logits, const int32_t* voted, const float* draft_probs, const int32_t* spec_len,
                           const int32_t* greedy, int B, int k_max, int M, int V, double temperature, uint64_t seed,
                           uint64_t step, int32_t* sampled, int32_t* dev_status, hipStream_t st);
+void launch_draft_sample(const float* logits, int B, int V, double temperature, uint64_t seed, uint64_t step, int ssm,
+                         int t_pos, int32_t* tokens, long token_stride, float* probs, long probs_stride, hipStream_t st);
 int verify_sample_max_vocab();
 
 // ---- rows.hip ----

@@ -11,7 +11,10 @@
 // number with a ratio or a running sum known to about 1e-14 relative, so it is reproducible by any
 // other fp64 evaluation of the same definition except on a set of measure ~1e-14.
 // Random numbers: Philox-4x32 with 10 rounds (Salmon et al., SC 2011), key = seed, counter =
-// (sequence, position, step): a position's numbers do not depend on the batch it is scored in.
+// (sequence, position, step + consumer tag): a position's numbers do not depend on the batch it is scored in.
+//
+// The same file holds the drafting side of the rule: draft_sample_kernel draws an SSM's next token from
+// its own q = softmax(scores / T) and writes q out for the verifier.
 #include "launch.h"
 #include "../../include/minions_verify.h"
 
@@ -52,23 +55,130 @@ __device__ __forceinline__ double block_sum_ordered(double v, double* s_buf, int
   return s_buf[SV_THREADS];
 }
 
-// One workgroup per (position j, sequence b).  Tokens are walked in tiles of 1024: thread t of the
-// workgroup holds tokens tile*1024 + 4t .. 4t+3 (coalesced 16-byte pieces), so a prefix over (tile,
-// thread, element) is a prefix in token order.
+struct DrawShared {
+  double buf[SV_THREADS + 1];
+  double tile[SV_MAX_TILES];  // mass of every tile
+  double target[2];           // target inside the chosen tile, total mass
+  int pick[2];                // chosen tile, chosen token
+};
+
+// Inverse-CDF draw over the vocabulary: the first token, in token order, whose running sum of mass(v)
+// exceeds u times the total; -1 when the total is not positive.  Tokens are walked in tiles of 1024:
+// thread t of the workgroup holds tokens tile*1024 + 4t .. 4t+3 (coalesced 16-byte pieces), so a prefix
+// over (tile, thread, element) is a prefix in token order.  The per-tile masses are summed first, one
+// thread finds the tile that holds the target, and that tile alone is scanned.  Every thread of the
+// workgroup calls it; the result is uniform.  mass(v) must return the same value every time it is asked.
+template <typename F>
+__device__ int cdf_draw(F mass, int V, double u, DrawShared& sh, int tid) {
+  const int n_tiles = (V + SV_TILE - 1) / SV_TILE;
+  for (int t = 0; t < n_tiles; ++t) {
+    double m = 0.0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int v = t * SV_TILE + 4 * tid + e;
+      if (v < V) m += mass(v);
+    }
+    const double ts = block_sum_ordered(m, sh.buf, tid);
+    if (tid == 0) sh.tile[t] = ts;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    double total = 0.0;
+    for (int t = 0; t < n_tiles; ++t) total += sh.tile[t];
+    const double target = u * total;
+    double before = 0.0;
+    int t = 0;
+    while (t < n_tiles - 1 && before + sh.tile[t] <= target) before += sh.tile[t++];
+    sh.target[0] = target - before;
+    sh.target[1] = total;
+    sh.pick[0] = t;
+    sh.pick[1] = 0x7fffffff;
+  }
+  __syncthreads();
+  if (!(sh.target[1] > 0.0)) return -1;  // (whole workgroup)
+  const int tile = sh.pick[0];
+  const double target = sh.target[0];
+  double m4[4], mine = 0.0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int v = tile * SV_TILE + 4 * tid + e;
+    m4[e] = v < V ? mass(v) : 0.0;
+    mine += m4[e];
+  }
+  sh.buf[tid] = mine;
+  __syncthreads();
+  double cum = 0.0;
+  for (int i = 0; i < tid; ++i) cum += sh.buf[i];  // thread order = token order
+  int hit = 0x7fffffff, last_pos = -1;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    cum += m4[e];
+    const int v = tile * SV_TILE + 4 * tid + e;
+    if (m4[e] > 0.0) {
+      last_pos = v;
+      if (cum > target && hit == 0x7fffffff) hit = v;
+    }
+  }
+  if (hit != 0x7fffffff) atomicMin(&sh.pick[1], hit);
+  __syncthreads();
+  if (sh.pick[1] == 0x7fffffff) {  // rounding left the target at the tile's end: its last token with mass (whole workgroup)
+    __syncthreads();
+    if (tid == 0) sh.pick[1] = -1;
+    __syncthreads();
+    if (last_pos >= 0) atomicMax(&sh.pick[1], last_pos);
+    __syncthreads();
+  }
+  return sh.pick[1];
+}
+
+// Largest score of a row and Z = sum_v exp((l_v - max) / T), both uniform over the workgroup.
+__device__ __forceinline__ void row_max_and_z(const float* __restrict__ L, int V, double temperature, float* s_max,
+                                              double* s_buf, int tid, double& dmx, double& Z) {
+  float mx = -INFINITY;
+  for (int v = tid; v < V; v += SV_THREADS) mx = fmaxf(mx, L[v]);
+  s_max[tid] = mx;
+  __syncthreads();
+  for (int s = SV_THREADS / 2; s > 0; s >>= 1) {
+    if (tid < s) s_max[tid] = fmaxf(s_max[tid], s_max[tid + s]);
+    __syncthreads();
+  }
+  dmx = (double)s_max[0];
+  double zp = 0.0;
+  const int n_tiles = (V + SV_TILE - 1) / SV_TILE;
+  for (int t = 0; t < n_tiles; ++t) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int v = t * SV_TILE + 4 * tid + e;
+      if (v < V) zp += exp(((double)L[v] - dmx) / temperature);
+    }
+  }
+  Z = block_sum_ordered(zp, s_buf, tid);
+}
+
+// The top byte of the counter's last word names the consumer of the numbers, so that the verifier
+// (0) and the drafting SSMs (1 + index) never share a stream under one seed; steps are below 2^56.
+__device__ __forceinline__ void position_uniforms(uint32_t b, uint32_t j, uint32_t step_lo, uint32_t step_hi,
+                                                  uint32_t consumer, uint32_t seed_lo, uint32_t seed_hi, double& u0,
+                                                  double& u1) {
+  uint32_t w[4] = {b, j, step_lo, (step_hi & 0x00ffffffu) | (consumer << 24)};
+  philox4x32_10(w, seed_lo, seed_hi);
+  u0 = unit_double(w[0], w[1]);
+  u1 = unit_double(w[2], w[3]);
+}
+
+// One workgroup per (position j, sequence b).
 __global__ void __launch_bounds__(SV_THREADS) verify_sample_kernel(
     const float* __restrict__ logits, const int32_t* __restrict__ voted, const float* __restrict__ draft_probs,
     const int32_t* __restrict__ spec_len, const int32_t* __restrict__ greedy, int B, int k_max, int M, int V,
     double temperature, uint32_t seed_lo, uint32_t seed_hi, uint32_t step_lo, uint32_t step_hi,
     int32_t* __restrict__ sampled, int32_t* dev_status) {
-  __shared__ double s_buf[SV_THREADS + 1];
-  __shared__ double s_tile[SV_MAX_TILES];  // residual mass of every tile
+  __shared__ DrawShared sh;
   __shared__ float s_max[SV_THREADS];
-  __shared__ int s_int[4];                 // rows before this sequence, bad flag, chosen tile, chosen token
-  __shared__ double s_target[2];           // target inside the chosen tile, total
+  __shared__ int s_int[2];  // rows before this sequence, bad flag
   const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   int32_t* out = sampled + (size_t)b * (k_max + 1) + j;
 
-  if (tid < 4) s_int[tid] = 0;
+  if (tid < 2) s_int[tid] = 0;
   __syncthreads();
   {  // rows of the sequences before b (integer sum: order-free)
     int part = 0, bad = 0;
@@ -92,36 +202,14 @@ __global__ void __launch_bounds__(SV_THREADS) verify_sample_kernel(
     return;
   }
   const float* L = logits + (size_t)row * V;
-  const int n_tiles = (V + SV_TILE - 1) / SV_TILE;
-
-  // ---- largest score of the row ----
-  float mx = -INFINITY;
-  for (int v = tid; v < V; v += SV_THREADS) mx = fmaxf(mx, L[v]);
-  s_max[tid] = mx;
-  __syncthreads();
-  for (int s = SV_THREADS / 2; s > 0; s >>= 1) {
-    if (tid < s) s_max[tid] = fmaxf(s_max[tid], s_max[tid + s]);
-    __syncthreads();
-  }
-  const double dmx = (double)s_max[0];
-
-  // ---- Z = sum_v exp((l_v - max) / T) ----
-  double zp = 0.0;
-  for (int t = 0; t < n_tiles; ++t) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int v = t * SV_TILE + 4 * tid + e;
-      if (v < V) zp += exp(((double)L[v] - dmx) / temperature);
-    }
-  }
-  const double Z = block_sum_ordered(zp, s_buf, tid);
+  double dmx, Z;
+  row_max_and_z(L, V, temperature, s_max, sh.buf, tid, dmx, Z);
+  double u_acc, u_res;
+  position_uniforms((uint32_t)b, (uint32_t)j, step_lo, step_hi, 0u, seed_lo, seed_hi, u_acc, u_res);
 
   // ---- does the speculated token survive? ----
   bool keep = false;
   int x = -1;
-  uint32_t w[4] = {(uint32_t)b, (uint32_t)j, step_lo, step_hi};
-  philox4x32_10(w, seed_lo, seed_hi);
-  const double u_acc = unit_double(w[0], w[1]), u_res = unit_double(w[2], w[3]);
   const float* Q = nullptr;
   if (j < k_b) {
     x = voted[(size_t)b * k_max + j];
@@ -136,81 +224,38 @@ __global__ void __launch_bounds__(SV_THREADS) verify_sample_kernel(
     if (tid == 0) *out = x;
     return;
   }
+  // ---- a token from max(0, o - q); without q (position k_b), or when nothing of o lies above q, from o ----
+  int tok = -1;
+  if (Q) tok = cdf_draw([&](int v) { return fmax(0.0, exp(((double)L[v] - dmx) / temperature) / Z - (double)Q[v]); }, V,
+                        u_res, sh, tid);
+  if (tok < 0) tok = cdf_draw([&](int v) { return exp(((double)L[v] - dmx) / temperature) / Z; }, V, u_res, sh, tid);
+  if (tid == 0) *out = tok;
+}
 
-  // ---- mass of max(0, o - q) per tile; without q (position k_b), or when nothing of o lies above q,
-  //      the mass is o itself ----
-  const float* Qr = Q;  // what is subtracted from o (nothing when null)
-  for (;;) {
-    for (int t = 0; t < n_tiles; ++t) {
-      double m = 0.0;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int v = t * SV_TILE + 4 * tid + e;
-        if (v < V) {
-          const double o = exp(((double)L[v] - dmx) / temperature) / Z;
-          m += Qr ? fmax(0.0, o - (double)Qr[v]) : o;
-        }
-      }
-      const double ts = block_sum_ordered(m, s_buf, tid);
-      if (tid == 0) s_tile[t] = ts;
-    }
-    __syncthreads();
-    if (tid == 0) {
-      double total = 0.0;
-      for (int t = 0; t < n_tiles; ++t) total += s_tile[t];
-      s_target[1] = total;
-      const double target = u_res * total;
-      double before = 0.0;
-      int t = 0;
-      while (t < n_tiles - 1 && before + s_tile[t] <= target) before += s_tile[t++];
-      s_int[2] = t;
-      s_target[0] = target - before;
-    }
-    __syncthreads();
-    if (s_target[1] > 0.0 || !Qr) break;  // (whole workgroup)
-    Qr = nullptr;
+// One workgroup per sequence: token ~ q = softmax(scores / T) of a drafting SSM, and q itself in fp32.
+// The draw is taken from the fp32 values that are written out, so what the verifier is later told is
+// exactly the distribution the token came from.
+__global__ void __launch_bounds__(SV_THREADS) draft_sample_kernel(const float* __restrict__ logits, int V,
+                                                                  double temperature, uint32_t seed_lo, uint32_t seed_hi,
+                                                                  uint32_t step_lo, uint32_t step_hi, uint32_t consumer,
+                                                                  uint32_t t_pos, int32_t* __restrict__ tokens,
+                                                                  long token_stride, float* __restrict__ probs,
+                                                                  long probs_stride) {
+  __shared__ DrawShared sh;
+  __shared__ float s_max[SV_THREADS];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const float* L = logits + (size_t)b * V;
+  double dmx, Z;
+  row_max_and_z(L, V, temperature, s_max, sh.buf, tid, dmx, Z);
+  double u_unused, u;
+  position_uniforms((uint32_t)b, t_pos, step_lo, step_hi, consumer, seed_lo, seed_hi, u_unused, u);
+  auto q32 = [&](int v) { return (float)(exp(((double)L[v] - dmx) / temperature) / Z); };
+  if (probs) {
+    float* P = probs + (size_t)b * probs_stride;
+    for (int v = tid; v < V; v += SV_THREADS) P[v] = q32(v);
   }
-  const int tile = s_int[2];
-  const double target = s_target[0];
-
-  // ---- inside the chosen tile: the first token whose running sum exceeds the target ----
-  double m4[4], mine = 0.0;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const int v = tile * SV_TILE + 4 * tid + e;
-    m4[e] = 0.0;
-    if (v < V) {
-      const double o = exp(((double)L[v] - dmx) / temperature) / Z;
-      m4[e] = Qr ? fmax(0.0, o - (double)Qr[v]) : o;
-    }
-    mine += m4[e];
-  }
-  __syncthreads();
-  s_buf[tid] = mine;
-  if (tid == 0) s_int[3] = 0x7fffffff;
-  __syncthreads();
-  double cum = 0.0;
-  for (int i = 0; i < tid; ++i) cum += s_buf[i];  // thread order = token order
-  int hit = 0x7fffffff, last_pos = -1;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    cum += m4[e];
-    const int v = tile * SV_TILE + 4 * tid + e;
-    if (m4[e] > 0.0) {
-      last_pos = v;
-      if (cum > target && hit == 0x7fffffff) hit = v;
-    }
-  }
-  if (hit != 0x7fffffff) atomicMin(&s_int[3], hit);
-  __syncthreads();
-  if (s_int[3] == 0x7fffffff) {  // rounding left the target at the tile's end: its last token with mass
-    __syncthreads();
-    if (tid == 0) s_int[3] = -1;
-    __syncthreads();
-    if (last_pos >= 0) atomicMax(&s_int[3], last_pos);
-    __syncthreads();
-  }
-  if (tid == 0) *out = s_int[3];
+  const int tok = cdf_draw([&](int v) { return (double)q32(v); }, V, u, sh, tid);
+  if (tid == 0) tokens[(size_t)b * token_stride] = tok;
 }
 
 void launch_verify_sample(const float* logits, const int32_t* voted, const float* draft_probs, const int32_t* spec_len,
@@ -220,6 +265,14 @@ void launch_verify_sample(const float* logits, const int32_t* voted, const float
   verify_sample_kernel<<<dim3(k_max + 1, B), SV_THREADS, 0, st>>>(
       logits, voted, draft_probs, spec_len, greedy, B, k_max, M, V, temperature, (uint32_t)seed, (uint32_t)(seed >> 32),
       (uint32_t)step, (uint32_t)(step >> 32), sampled, dev_status);
+}
+
+void launch_draft_sample(const float* logits, int B, int V, double temperature, uint64_t seed, uint64_t step, int ssm,
+                         int t_pos, int32_t* tokens, long token_stride, float* probs, long probs_stride, hipStream_t st) {
+  if (B <= 0) return;
+  draft_sample_kernel<<<B, SV_THREADS, 0, st>>>(logits, V, temperature, (uint32_t)seed, (uint32_t)(seed >> 32),
+                                                (uint32_t)step, (uint32_t)(step >> 32), (uint32_t)(1 + ssm),
+                                                (uint32_t)t_pos, tokens, token_stride, probs, probs_stride);
 }
 
 int verify_sample_max_vocab() { return SV_TILE * SV_MAX_TILES; }

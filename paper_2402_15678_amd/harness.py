@@ -271,11 +271,17 @@ class DraftSession:
     which mn_mv_vote reads directly.  Copying a token column into the drafts array is the only thing done
     outside the library."""
 
-    def __init__(self, models: Sequence[DeviceModel], kvs: Sequence[DeviceKV], B_: int, k_max: int, max_ctx: int):
+    def __init__(self, models: Sequence[DeviceModel], kvs: Sequence[DeviceKV], B_: int, k_max: int, max_ctx: int,
+                 sampling: bool = False):
         assert len(models) == len(kvs) and len(models) >= 1
         self.n, self.B, self.k_max = len(models), B_, k_max
-        self.sessions = [VerifySession(m, kv, B_, 0, 1, max_ctx, max_rows=B_) for m, kv in zip(models, kvs)]
+        self.sessions = [VerifySession(m, kv, B_, 0, 1, max_ctx, max_rows=B_, want_logits=sampling)
+                         for m, kv in zip(models, kvs)]
         dev = _dev()
+        self.vocab = models[0].desc.vocab
+        # q of every drafted token, per SSM: [n][B][k_max][vocab] fp32 (only when the SSMs sample)
+        self.draft_probs = (torch.zeros((self.n, B_, max(1, k_max), self.vocab), dtype=torch.float32, device=dev)
+                            if sampling else None)
         self.drafts = torch.full((B_, self.n, max(1, k_max)), -1, dtype=torch.int32, device=dev)
         self._zeros = torch.zeros((B_,), dtype=torch.int32, device=dev)
         self._dummy = torch.zeros((B_, 1), dtype=torch.int32, device=dev)
@@ -294,3 +300,28 @@ class DraftSession:
                 cur = ses.next_last_tok.clone()
                 self.drafts[:, j, t] = cur
         return self.drafts
+
+    def draft_sampled(self, last_tok: torch.Tensor, k: int, temperature: float, seed: int, step: int) -> torch.Tensor:
+        """k tokens per sequence from every SSM, each drawn from the SSM's own q = softmax(scores / T)
+        (mn_draft_sample writes the token straight into drafts[b][j][t] and q into draft_probs[j][b][t]);
+        the SSM's cache advances as in draft()."""
+        assert self.draft_probs is not None, "the session was built without sampling"
+        assert 0 <= k <= self.k_max
+        self.drafts.fill_(-1)
+        zeros = [0] * self.B
+        kk = max(1, self.k_max)
+        for j, ses in enumerate(self.sessions):
+            cur = last_tok
+            for t in range(k):
+                ses.forward(cur, self._zeros, zeros, voted=self._dummy)
+                ses.accept(self._zeros, voted=self._dummy)            # the cache keeps the token just scored
+                B.mn_draft_sample(ses.model.ctx, ses.logits.data_ptr(), self.B, self.vocab, temperature, seed, step, j, t,
+                                  self.drafts[0, j, t:].data_ptr(), self.n * kk,
+                                  self.draft_probs[j, 0, t].data_ptr(), kk * self.vocab, stream_ptr())
+                cur = self.drafts[:, j, t].contiguous()
+        return self.drafts
+
+    def voted_probs(self, voted_ssm: torch.Tensor) -> torch.Tensor:
+        """q of the SSM whose draft won the vote, per sequence: [B][k_max][vocab] (a gather, no arithmetic)."""
+        idx = voted_ssm.long().clamp_(min=0)
+        return self.draft_probs[idx, torch.arange(self.B, device=idx.device)].contiguous()

@@ -236,3 +236,97 @@ def test_tiny_model_forward_sample_accept_end_to_end(hb):
         compared += 1
         assert acc[b] == a and out[b, :a + 1].tolist() == toks and ctx1[b] == lens[b] + a + 1
     assert compared >= B - 4
+
+
+@pytest.mark.parametrize("B,V,T,spread", [(1, 7, 1.0, 1.0), (16, 1003, 0.7, 2.0), (16, 32000, 1.0, 2.0), (5, 50272, 0.3, 1.0),
+                                          (300, 4096, 1.5, 3.0)])
+def test_draft_sample_matches_oracle(hb, B, V, T, spread):
+    """mn_draft_sample on seeded scores: q within an fp32 ulp of the oracle's, and the token equal wherever the
+    oracle's draw cleared its boundaries by more than an fp32 rounding of q could move them."""
+    harness, binding = hb
+    g = synth.stream(4103, B, V)
+    logits = g.normal(0.0, spread, (B, V)).astype(np.float32)
+    n, k_max, ssm, t = 3, 5, 2, 4
+    drafts = torch.full((B, n, k_max), -5, dtype=torch.int32, device="cuda:0")
+    probs = torch.full((B, k_max, V), -1.0, dtype=torch.float32, device="cuda:0")
+    log_d = _dev(logits, torch.float32)
+    binding.mn_draft_sample(None, log_d.data_ptr(), B, V, T, 77, 12, ssm, t, drafts[0, ssm, t:].data_ptr(), n * k_max,
+                            probs[0, t].data_ptr(), k_max * V, harness.stream_ptr())
+    torch.cuda.synchronize()
+    got_tok, got_q = drafts.cpu().numpy(), probs.cpu().numpy()
+    assert (np.delete(got_tok.reshape(B, -1), ssm * k_max + t, axis=1) == -5).all()      # only its own slot is written
+    assert (got_q[:, :t] == -1.0).all()
+    skipped = 0
+    for b in range(B):
+        tok, q32, gap = orc.draft_sample(logits[b], T, 77, 12, ssm, b, t)
+        assert np.allclose(got_q[b, t], q32, rtol=3e-7, atol=1e-45)
+        assert abs(float(got_q[b, t].astype(np.float64).sum()) - 1.0) < 1e-5
+        if gap < 1e-6:
+            skipped += 1
+            continue
+        assert got_tok[b, ssm, t] == tok, (b, got_tok[b, ssm, t], tok)
+    assert skipped <= max(1, B // 50)
+
+
+def test_sampled_drafting_loop_on_the_device(hb):
+    """SSMs that sample, the vote, the LLM's stochastic verification and the commit, end to end on the device.
+    Checked as properties (the parity of every stage has its own test): the drafts come with the distributions
+    they were drawn from, the SSM caches advance, the same (seed, step) reproduces the drafts and another step
+    does not, and the outcome is a prefix of the voted draft plus one token."""
+    harness, binding = hb
+    V, B, k, n = 512, 6, 4, 3
+    llm_desc = synth.ModelDesc(synth.ARCH_OPT, synth.DT_F32, 2, 128, 4, 4, 32, 256, V, 256)
+    ssm_descs = [synth.ModelDesc(synth.ARCH_OPT, synth.DT_F32, 1, 64, 2, 2, 32, 128, V, 256),
+                 synth.ModelDesc(synth.ARCH_LLAMA, synth.DT_F32, 1, 64, 4, 2, 16, 128, V, 256),
+                 synth.ModelDesc(synth.ARCH_OPT, synth.DT_F32, 2, 64, 2, 2, 32, 64, V, 256)]
+    ctx = np.array([40, 17, 64, 1, 33, 90], np.int32)
+    ks = np.full(B, k, np.int32)
+    last = synth.stream(4104, 0).integers(0, V, size=B).astype(np.int32)
+    max_ctx = int((ctx + k + 1).max())
+
+    def build(desc, seed):
+        kvh = synth.make_paged_kv(desc, ctx, ks, seed, scatter=True)
+        return harness.DeviceModel.from_host(desc, synth.make_weights(desc, seed)), harness.DeviceKV.from_host(desc, kvh)
+
+    llm_m, llm_kv = build(llm_desc, 910)
+    ssm = [build(d, 911 + i) for i, d in enumerate(ssm_descs)]
+    ds = harness.DraftSession([s[0] for s in ssm], [s[1] for s in ssm], B, k, max_ctx, sampling=True)
+    t_last, t_k = _dev(last), _dev(ks)
+    T = 0.05                                     # the small models' scores are nearly flat
+    d1 = ds.draft_sampled(t_last, k, T, seed=5, step=1).clone()
+    q1 = ds.draft_probs.clone()
+    torch.cuda.synchronize()
+    for s in ssm:
+        assert s[1].ctx_lens.cpu().tolist() == (ctx + k).tolist()
+        s[1].ctx_lens.copy_(_dev(ctx))
+    d1h, q1h = d1.cpu().numpy(), q1.cpu().numpy()
+    assert ((d1h >= 0) & (d1h < V)).all()
+    assert np.allclose(q1h.sum(axis=-1), 1.0, atol=1e-5)
+    for j in range(n):
+        for b in range(B):
+            assert (q1h[j, b, np.arange(k), d1h[b, j]] > 0).all()          # a drawn token has mass
+    d2 = ds.draft_sampled(t_last, k, T, seed=5, step=1).clone()
+    for s in ssm:
+        s[1].ctx_lens.copy_(_dev(ctx))
+    d3 = ds.draft_sampled(t_last, k, T, seed=5, step=2).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(d1, d2) and not torch.equal(d1, d3)
+    # ---- vote, verify, sample, accept on the LLM with the winners' distributions ----
+    ses = harness.VerifySession(llm_m, llm_kv, B, k, n, max_ctx, want_logits=True)
+    w = torch.ones(n, device="cuda:0")
+    ses.vote(d1, t_k, w)
+    ses.forward(t_last, t_k, ks.tolist())
+    ds.draft_probs.copy_(q1)
+    qv = ds.voted_probs(ses.voted_ssm)
+    sampled = ses.sample(t_k, B * (k + 1), qv, T, seed=5, step=1)
+    ses.accept(t_k, tokens=sampled)
+    torch.cuda.synchronize()
+    assert ses.dev_status.item() == 0
+    voted, ssm_idx = ses.voted.cpu().numpy(), ses.voted_ssm.cpu().numpy()
+    acc, out, n_out = ses.accepted_len.cpu().numpy(), ses.out_tokens.cpu().numpy(), ses.n_out.cpu().numpy()
+    for b in range(B):
+        assert np.array_equal(voted[b], d1h[b, ssm_idx[b]])               # the vote returns one SSM's whole draft
+        a = int(acc[b])
+        assert 0 <= a <= k and n_out[b] == a + 1 and out[b, :a].tolist() == voted[b, :a].tolist()
+        assert 0 <= out[b, a] < V and (a == k or out[b, a] != voted[b, a])
+    assert llm_kv.ctx_lens.cpu().tolist() == (ctx + acc + 1).tolist()

@@ -119,3 +119,23 @@ def test_rejection_probability_is_one_minus_ratio():
     # a token the LLM gives at least the SSM's probability is never rejected
     for t in range(200):
         assert orc.accept_stochastic([1], logits, q, 1, 1.0, seed=4, step=t, b=1)[0] == 1
+
+
+def test_draft_sample_distribution_and_streams():
+    """An SSM's draws follow its own q; SSMs and the verifier use different numbers under one seed."""
+    rng = np.random.default_rng(21)
+    V, T, N = 6, 0.7, 20000
+    z = rng.normal(0.0, 1.2, V)
+    q = orc.llm_probs(z, T)
+    counts = np.zeros(V)
+    for step in range(N):
+        tok, q32, _ = orc.draft_sample(z, T, seed=5, step=step, ssm=2, b=1, t=3)
+        counts[tok] += 1
+    assert q32.dtype == np.float32 and np.abs(q32 - q).max() < 1e-7
+    assert np.abs(counts / N - q).max() < 4.0 * np.sqrt(0.25 / N)
+    us = {orc.verify_uniforms(5, 9, 1, 3, consumer=c) for c in range(0, 6)}
+    assert len(us) == 6
+    assert orc.verify_uniforms(5, 9, 1, 3) == orc.verify_uniforms(5, 9, 1, 3, consumer=0)
+    # a draw on a one-hot distribution is that token whatever the number
+    hot = np.full(V, -1e4); hot[4] = 0.0
+    assert all(orc.draft_sample(hot, 1.0, 1, s_, 0, 0, 0)[0] == 4 for s_ in range(50))
