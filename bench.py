@@ -34,6 +34,8 @@ def parse_args():
     ap.add_argument("--workload", type=int, default=2, help="index into the workload list (default: 70B b16 k8)")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the real depth); for experiments")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="also replay the step from a captured graph and report its time beside the eager one")
     ap.add_argument("--profile-steps", type=int, default=3, help="extra steps run with the timing taps on")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, for scaling rocprofv3 byte counters)")
@@ -271,6 +273,28 @@ def main():
     per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     acc = ses.accepted_len.cpu().numpy()
 
+    # the same step captured once and replayed (the library only launches kernels on the caller's stream, so a
+    # serving loop may do this): informational, the headline stays the eager launch sequence
+    graph_ms = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(gr, stream=side):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(2):
+            gr.replay()
+        torch.cuda.synchronize()
+        tg = time.perf_counter()
+        for _ in range(args.steps):
+            gr.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - tg) / args.steps * 1e3
+        assert ses.dev_status.item() == 0 and np.array_equal(ses.accepted_len.cpu().numpy(), acc)
+        del gr
+
     # the two rows that close the loop after the step (not part of the timed step): the SSM weight update
     # on the device and the host-side speculation length selector
     acr_buf = torch.zeros((n,), dtype=torch.float64, device=dev)
@@ -393,7 +417,7 @@ def main():
         "accepted_tokens_per_sec": float((acc + 1).sum()) / (ms_per_step * 1e-3),
         "acceptance_rate": float(acc.sum()) / max(1, int(ks.sum())),
         "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
-        "setup_s": t_setup,
+        "setup_s": t_setup, "ms_per_step_graph_replay": graph_ms,
         "stochastic_rule": {"verify_sample_us": sample_us, "temperature": 1.0, "positions": M,
                             "speculated_tokens_surviving": sample_survivors, "speculated_tokens": int(ks.sum()),
                             "note": "mn_verify_sample on this step's scores; q = softmax(scores + N(0,1))"},

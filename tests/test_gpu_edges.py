@@ -84,6 +84,45 @@ def test_bit_reproducible_run_to_run(env):
         assert torch.equal(a, b)                                              # no float atomics: identical bits
 
 
+def test_step_replays_from_a_captured_graph(env):
+    """The whole step (vote -> forward -> accept + commit) issues only kernel launches on the caller's stream, so
+    a caller may capture it once and replay it.  Three replays, with eager work and synchronisations in between,
+    each against the eager result bit for bit (logits, tokens, cache pages, committed contexts)."""
+    harness, binding, W, model = env
+    ctx, ks = np.array([100, 33, 257, 0], np.int32), np.array([4, 7, 2, 5], np.int32)
+    g = synth.stream(6, 2)
+    last, drafts = _i32(g.integers(0, DESC.vocab, size=4)), _i32(g.integers(0, DESC.vocab, size=(4, 3, 7)))
+    spec, w = _i32(ks), torch.ones(3, device="cuda:0")
+    ctx0 = _i32(ctx)
+    kvh, kvd, ses = _setup(harness, model, ctx, ks)
+    ses.step(last, drafts, spec, ks.tolist(), w)                             # eager: the reference, and the warm-up
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (ses.logits, ses.greedy, ses.out_tokens, ses.accepted_len, kvd.k_pages[1], kvd.v_pages[0],
+                                kvd.ctx_lens)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        kvd.ctx_lens.copy_(ctx0)
+        with torch.cuda.graph(graph, stream=side):
+            ses.step(last, drafts, spec, ks.tolist(), w)
+    torch.cuda.current_stream().wait_stream(side)
+    for r in range(3):
+        kvd.ctx_lens.copy_(ctx0)
+        for t in (ses.logits, ses.greedy, ses.out_tokens, ses.accepted_len):
+            t.fill_(-3)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (ses.logits, ses.greedy, ses.out_tokens, ses.accepted_len, kvd.k_pages[1], kvd.v_pages[0], kvd.ctx_lens)
+        for a, b in zip(got, want):
+            assert torch.equal(a, b), r
+        assert ses.dev_status.item() == 0
+        # eager work of the program between the replays
+        kvd.ctx_lens.copy_(ctx0)
+        ses.step(last, drafts, spec, ks.tolist(), w)
+        torch.cuda.synchronize()
+
+
 def test_one_pass_equals_sequential_decodes_on_the_device(env):
     harness, binding, W, model = env
     ctx, k = np.array([50, 16, 129], np.int32), 5
