@@ -268,6 +268,7 @@ extern "C" mn_status mn_verify_sample(mn_ctx* ctx, const float* logits, const in
   if (step >> 56) return fail(ctx, MN_EINVAL, "mn_verify_sample: step must be below 2^56");
   if (B > 0 && (!logits || !spec_len || !greedy || !sampled)) return fail(ctx, MN_ENULL, "mn_verify_sample: a required pointer is NULL");
   if (B > 0 && k_max > 0 && (!voted || !draft_probs)) return fail(ctx, MN_ENULL, "mn_verify_sample: voted or draft_probs is NULL");
+  if (B == 0) return MN_OK;
   {
     Tap t(ctx ? &ctx->prof : nullptr, MN_PROF_ACCEPT, (hipStream_t)stream);
     launch_verify_sample(logits, voted, draft_probs, spec_len, greedy, B, k_max, M, vocab, temperature, seed, step, sampled,
@@ -287,6 +288,7 @@ extern "C" mn_status mn_draft_sample(mn_ctx* ctx, const float* logits, int B, in
   if (t < 0) return fail(ctx, MN_EINVAL, "mn_draft_sample: t = %d", t);
   if (token_stride < 1 || (probs && probs_stride < vocab)) return fail(ctx, MN_EINVAL, "mn_draft_sample: strides");
   if (B > 0 && (!logits || !tokens)) return fail(ctx, MN_ENULL, "mn_draft_sample: a required pointer is NULL");
+  if (B == 0) return MN_OK;
   {
     Tap tp(ctx ? &ctx->prof : nullptr, MN_PROF_VOTE, (hipStream_t)stream);
     launch_draft_sample(logits, B, vocab, temperature, seed, step, ssm, t, tokens, token_stride, probs, probs_stride,

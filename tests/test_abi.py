@@ -120,3 +120,31 @@ def test_step_calls_reject_bad_arguments_before_launch(binding):
         with pytest.raises(binding.MinionsError):
             binding.mn_probe_mfma(iters)
     binding.mn_destroy(ctx)
+
+
+def test_stochastic_entries_reject_bad_arguments_before_launch(binding):
+    p = 0x1000
+    vs = lambda **kw: binding.mn_verify_sample(None, kw.get("logits", p), p, p, p, p, kw.get("B", 2), kw.get("k_max", 3),
+                                               kw.get("M", 8), kw.get("vocab", 100), kw.get("T", 1.0), 1,
+                                               kw.get("step", 0), kw.get("sampled", p))
+    for kw, status in [(dict(B=-1), binding.MN_EINVAL), (dict(B=5000), binding.MN_EINVAL), (dict(k_max=-1), binding.MN_EINVAL),
+                       (dict(M=9), binding.MN_EINVAL), (dict(vocab=0), binding.MN_EUNSUPPORTED),
+                       (dict(vocab=(1 << 21) + 1), binding.MN_EUNSUPPORTED), (dict(T=0.0), binding.MN_EINVAL),
+                       (dict(T=float("inf")), binding.MN_EINVAL), (dict(T=float("nan")), binding.MN_EINVAL),
+                       (dict(step=1 << 56), binding.MN_EINVAL), (dict(logits=None), binding.MN_ENULL),
+                       (dict(sampled=None), binding.MN_ENULL)]:
+        with pytest.raises(binding.MinionsError) as e:
+            vs(**kw)
+        assert e.value.status == status, kw
+    binding.mn_verify_sample(None, None, None, None, None, None, 0, 3, 0, 100, 1.0, 1, 0, None)     # B = 0: no launch
+    ds = lambda **kw: binding.mn_draft_sample(None, kw.get("logits", p), kw.get("B", 2), kw.get("vocab", 100),
+                                              kw.get("T", 1.0), 1, kw.get("step", 0), kw.get("ssm", 0), kw.get("t", 0),
+                                              kw.get("tokens", p), kw.get("ts", 1), kw.get("probs", None), kw.get("ps", 0))
+    for kw, status in [(dict(B=-1), binding.MN_EINVAL), (dict(vocab=0), binding.MN_EUNSUPPORTED), (dict(T=-1.0), binding.MN_EINVAL),
+                       (dict(step=1 << 56), binding.MN_EINVAL), (dict(ssm=-1), binding.MN_EINVAL), (dict(ssm=64), binding.MN_EINVAL),
+                       (dict(t=-1), binding.MN_EINVAL), (dict(ts=0), binding.MN_EINVAL), (dict(probs=p, ps=99), binding.MN_EINVAL),
+                       (dict(logits=None), binding.MN_ENULL), (dict(tokens=None), binding.MN_ENULL)]:
+        with pytest.raises(binding.MinionsError) as e:
+            ds(**kw)
+        assert e.value.status == status, kw
+    binding.mn_draft_sample(None, None, 0, 100, 1.0, 1, 0, 0, 0, None, 1)                             # B = 0: no launch
