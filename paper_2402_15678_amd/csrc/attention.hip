@@ -224,11 +224,15 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_spl
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
   const int G = a.H / a.Hkv;
-  const int row0 = a.rows.seq_row0[b];
-  const int qb = a.rows.seq_row0[b + 1] - row0;
-  if (qb <= 0) return;
+  // everything known about the sequence in one round trip (these few words are cold after the projections
+  // before have streamed through the caches; fetched one after the other they cost a microsecond each)
+  const int row0 = a.rows.seq_row0[b], row1 = a.rows.seq_row0[b + 1];
   const int ok = a.rows.seq_ok[b];
   const int ctx = a.rows.seq_ctx[b];
+  const int tps = a.rows.attn_tps[0];
+  asm volatile("" ::"r"(ok), "r"(ctx), "r"(tps));  // (keeps the compiler from sinking the loads below the exits)
+  const int qb = row1 - row0;
+  if (qb <= 0) return;
   const int R = G * qb;                   // query rows sharing this KV head; row r = j*G + gi
   const int NT16 = (R + 15) >> 4;         // column tiles in use
   const int tile0 = 4 * CTW * rg;         // first column tile of this workgroup
@@ -237,7 +241,7 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_spl
   const int n_tiles = (nkeys + KT - 1) / KT;
   // this sequence's own number of KV splits (the grid holds the largest any sequence may get): about
   // attn_tps key tiles per workgroup, so the long sequences of a ragged batch are cut finer than the short ones
-  const int my_splits = seq_splits(n_tiles, a.rows.attn_tps[0], n_splits);
+  const int my_splits = seq_splits(n_tiles, tps, n_splits);
   if (split >= my_splits) return;         // (whole workgroup)
   const int t_begin = (int)(((long)n_tiles * split) / my_splits);
   const int t_end = (int)(((long)n_tiles * (split + 1)) / my_splits);
