@@ -75,3 +75,65 @@ def test_ssm_drafting_vote_verify_accept_update_on_the_device():
     assert np.array_equal(t_w.cpu().numpy(), want_w)
     m = ~np.isnan(want_acr)
     assert np.array_equal(t_acr.cpu().numpy()[m], want_acr[m])
+
+
+def test_generation_rounds_with_ssm_resync_are_lossless():
+    """Several rounds of draft -> vote -> verify -> commit -> SSM weight update with real (small, random) SSMs:
+    the emitted stream equals the LLM's plain greedy decode (the method is lossless whatever the SSMs say), and
+    in every round each SSM's draft equals that SSM's own greedy continuation of the committed text, which it can
+    only be if its cache was cut back to the committed prefix and refilled with the tokens it had missed."""
+    from paper_2402_15678_amd import harness
+    V = 512
+    llm_desc = synth.ModelDesc(synth.ARCH_OPT, synth.DT_F32, 2, 128, 4, 4, 32, 256, V, 256)
+    ssm_descs = [synth.ModelDesc(synth.ARCH_OPT, synth.DT_F32, 1, 64, 2, 2, 32, 128, V, 256),
+                 synth.ModelDesc(synth.ARCH_LLAMA, synth.DT_F32, 1, 64, 4, 2, 16, 128, V, 256),
+                 synth.ModelDesc(synth.ARCH_OPT, synth.DT_F32, 2, 64, 2, 2, 32, 64, V, 256)]
+    B, k, rounds = 3, 4, 5
+    ctx = np.array([40, 17, 64], np.int32)
+    room = np.full(B, rounds * (k + 1) + k + 2, np.int32)          # blocks for everything the rounds may commit
+    last = synth.stream(4243, 1).integers(0, V, size=B).astype(np.int32)
+
+    def build(desc, seed):
+        W = synth.make_weights(desc, seed)
+        kvh = synth.make_paged_kv(desc, ctx, room, seed, scatter=True)
+        return W, harness.DeviceModel.from_host(desc, W), harness.DeviceKV.from_host(desc, kvh), util.oracle_caches(desc, kvh)
+
+    llm_W, llm_m, llm_kv, llm_caches = build(llm_desc, 920)
+    ssm = [build(d, 921 + i) for i, d in enumerate(ssm_descs)]
+    max_ctx = int((ctx + room + 1).max())
+    w = torch.ones(len(ssm), device="cuda:0")
+    loop = harness.GenerationLoop(llm_m, llm_kv, [s[1] for s in ssm], [s[2] for s in ssm], B, k, max_ctx, _i32(last), w)
+
+    # the oracle's side: the LLM's greedy stream, long enough for the most the rounds can emit
+    T = rounds * (k + 1)
+    stream, margin = util.greedy_continuations(llm_desc, llm_W, llm_caches, last, [T] * B)
+    assert min(margin) > 2e-4
+    emitted = [[] for _ in range(B)]
+    pending = [int(t) for t in last]
+    ssm_caches = [[util.clone_cache(c) for c in s[3]] for s in ssm]            # grow with the committed text
+    total_accepted = 0
+    for r in range(rounds):
+        # what every SSM must draft this round: its greedy continuation after the committed text + pending token
+        want = np.zeros((B, len(ssm), k), np.int32)
+        for j, (desc, s) in enumerate(zip(ssm_descs, ssm)):
+            cont, mg = util.greedy_continuations(desc, s[0], ssm_caches[j], pending, [k - 1] * B)
+            assert min(mg) > 2e-4, (r, j, mg)
+            for b in range(B):
+                want[b, j] = cont[b][:k]
+        toks, acc = loop.round(acr_args=(0.6, 0.3, 1.25, 0.8))
+        torch.cuda.synchronize()
+        assert loop.llm.dev_status.item() == 0
+        assert np.array_equal(loop.drafts.cpu().numpy(), want), r
+        for b in range(B):
+            assert len(toks[b]) == acc[b] + 1
+            n0 = len(emitted[b])
+            assert toks[b] == stream[b][n0:n0 + len(toks[b])], (r, b)          # lossless: the greedy stream itself
+            committed = [pending[b]] + toks[b][:-1]                             # tokens whose cache entries are final
+            for j, (desc, s) in enumerate(zip(ssm_descs, ssm)):
+                orc.decoder_step(desc, s[0], [committed], [ssm_caches[j][b]])
+            emitted[b] += toks[b]
+            pending[b] = toks[b][-1]
+            total_accepted += acc[b]
+        assert llm_kv.ctx_lens.cpu().tolist() == [int(ctx[b]) + len(emitted[b]) for b in range(B)]
+    assert all(len(e) >= rounds for e in emitted)
+    assert (w.cpu().numpy() != 1.0).any() or total_accepted == 0            # the weights moved with the outcome
