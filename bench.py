@@ -336,6 +336,8 @@ def main():
     # the step before the path: n SSMs of the paper's small-model shape drafting k tokens each through the
     # same library (random weights, synthetic caches of the same contexts); informational
     draft_ms = None
+    draft_graph_ms = None
+    draft_seq_ms = None
     if desc.arch == synth.ARCH_LLAMA and desc.dtype == synth.DT_BF16 and args.layers <= 0:
         sd = synth.LLAMA_160M
         s_models = [harness.DeviceModel.random_on_device(sd, wl.seed + 100 + j) for j in range(n)]
@@ -350,6 +352,37 @@ def main():
         dsn.draft(last, k_max)
         torch.cuda.synchronize()
         draft_ms = (time.perf_counter() - t_d) * 1e3
+        for kv, c0 in zip(s_kvs, s_ctx0):
+            kv.ctx_lens.copy_(c0)
+        torch.cuda.synchronize()
+        t_d = time.perf_counter()
+        dsn.draft(last, k_max, concurrent=False)
+        torch.cuda.synchronize()
+        draft_seq_ms = (time.perf_counter() - t_d) * 1e3
+        if args.graph:
+            # the drafting of all SSMs (a few thousand small launches, no host decision in between) as one graph
+            for kv, c0 in zip(s_kvs, s_ctx0):
+                kv.ctx_lens.copy_(c0)
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            gd = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(gd, stream=side):
+                    dsn.draft(last, k_max)
+            torch.cuda.current_stream().wait_stream(side)
+            want_drafts = dsn.drafts.clone()
+            times = []
+            for _ in range(3):
+                for kv, c0 in zip(s_kvs, s_ctx0):
+                    kv.ctx_lens.copy_(c0)
+                torch.cuda.synchronize()
+                t_d = time.perf_counter()
+                gd.replay()
+                torch.cuda.synchronize()
+                times.append((time.perf_counter() - t_d) * 1e3)
+                assert torch.equal(dsn.drafts, want_drafts)
+            draft_graph_ms = min(times)
+            del gd
         del dsn, s_models, s_kvs
     sel = binding.mn_selector_create(max(1, k_max), 1, 64, 8, 1, 1)
     t_sel = time.perf_counter()
@@ -423,8 +456,9 @@ def main():
                             "note": "mn_verify_sample on this step's scores; q = softmax(scores + N(0,1))"},
         "after_step": {"acr_update_us": acr_us, "acr": [None if x != x else x for x in acr_buf.cpu().tolist()],
                        "selector_observe_ns_incl_binding": sel_ns,
-                       "ssm_drafting_ms": draft_ms,
-                       "ssm_drafting_note": "n SSMs of Llama-160M shape, k_max tokens each, one after the other on this GPU"},
+                       "ssm_drafting_ms": draft_ms, "ssm_drafting_ms_one_after_the_other": draft_seq_ms,
+                       "ssm_drafting_ms_graph_replay": draft_graph_ms,
+                       "ssm_drafting_note": "n SSMs of Llama-160M shape, k_max tokens each, on this GPU, one stream per SSM"},
         "roofline": roofline, "kernel_families": families,
         "ceilings": measure_ceilings(torch, binding, harness), "cpu_baseline": cpu,
     }

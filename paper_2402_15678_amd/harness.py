@@ -267,9 +267,9 @@ class VerifySession:
 class DraftSession:
     """The step before the verification path (paper section 3.1: several SSMs speculate on one request):
     every SSM is a small decoder of its own (own weights, own paged KV cache) driven through the same
-    library calls as the LLM, one token per call; its greedy tokens fill drafts[b][j][t] on the device,
-    which mn_mv_vote reads directly.  Copying a token column into the drafts array is the only thing done
-    outside the library."""
+    library calls as the LLM, one token per call, each SSM on a stream of its own; its greedy tokens fill
+    drafts[b][j][t] on the device, which mn_mv_vote reads directly.  Copying a token column into the drafts
+    array is the only thing done outside the library."""
 
     def __init__(self, models: Sequence[DeviceModel], kvs: Sequence[DeviceKV], B_: int, k_max: int, max_ctx: int,
                  sampling: bool = False):
@@ -286,19 +286,43 @@ class DraftSession:
         self._zeros = torch.zeros((B_,), dtype=torch.int32, device=dev)
         self._dummy = torch.zeros((B_, 1), dtype=torch.int32, device=dev)
 
-    def draft(self, last_tok: torch.Tensor, k: int) -> torch.Tensor:
+    def _fork(self):
+        """One stream per SSM (default priority), each starting after the work already queued on the current one."""
+        if not hasattr(self, "_streams"):
+            self._streams = [torch.cuda.Stream() for _ in range(self.n)]
+        main = torch.cuda.current_stream()
+        for st in self._streams:
+            st.wait_stream(main)
+        return main, self._streams
+
+    def draft(self, last_tok: torch.Tensor, k: int, concurrent: bool = True) -> torch.Tensor:
         """k greedy tokens per sequence from every SSM, starting from the pending token; each SSM's cache
-        advances by k entries (the caller truncates it to the accepted prefix after the verification)."""
+        advances by k entries (the caller truncates it to the accepted prefix after the verification).
+        The SSMs do not depend on one another: with `concurrent` each runs on a stream of its own (their small
+        kernels are bound by launch latency, not by the GPU, so side by side they take about the time of one)."""
         assert 0 <= k <= self.k_max
         self.drafts.fill_(-1)
         zeros = [0] * self.B
-        for j, ses in enumerate(self.sessions):
-            cur = last_tok
-            for t in range(k):
-                ses.forward(cur, self._zeros, zeros, voted=self._dummy)
-                ses.accept(self._zeros, voted=self._dummy)
-                cur = ses.next_last_tok.clone()
-                self.drafts[:, j, t] = cur
+        if not concurrent or self.n == 1:
+            for j, ses in enumerate(self.sessions):
+                cur = last_tok
+                for t in range(k):
+                    ses.forward(cur, self._zeros, zeros, voted=self._dummy)
+                    ses.accept(self._zeros, voted=self._dummy)
+                    cur = ses.next_last_tok.clone()
+                    self.drafts[:, j, t] = cur
+            return self.drafts
+        main, streams = self._fork()
+        cur = [last_tok] * self.n
+        for t in range(k):                       # token by token across the SSMs: every queue stays fed
+            for j, ses in enumerate(self.sessions):
+                with torch.cuda.stream(streams[j]):
+                    ses.forward(cur[j], self._zeros, zeros, voted=self._dummy)
+                    ses.accept(self._zeros, voted=self._dummy)
+                    cur[j] = ses.next_last_tok.clone()
+                    self.drafts[:, j, t] = cur[j]
+        for st in streams:
+            main.wait_stream(st)
         return self.drafts
 
     def draft_sampled(self, last_tok: torch.Tensor, k: int, temperature: float, seed: int, step: int) -> torch.Tensor:
@@ -310,15 +334,19 @@ class DraftSession:
         self.drafts.fill_(-1)
         zeros = [0] * self.B
         kk = max(1, self.k_max)
-        for j, ses in enumerate(self.sessions):
-            cur = last_tok
-            for t in range(k):
-                ses.forward(cur, self._zeros, zeros, voted=self._dummy)
-                ses.accept(self._zeros, voted=self._dummy)            # the cache keeps the token just scored
-                B.mn_draft_sample(ses.model.ctx, ses.logits.data_ptr(), self.B, self.vocab, temperature, seed, step, j, t,
-                                  self.drafts[0, j, t:].data_ptr(), self.n * kk,
-                                  self.draft_probs[j, 0, t].data_ptr(), kk * self.vocab, stream_ptr())
-                cur = self.drafts[:, j, t].contiguous()
+        main, streams = self._fork()
+        cur = [last_tok] * self.n
+        for t in range(k):
+            for j, ses in enumerate(self.sessions):
+                with torch.cuda.stream(streams[j]):
+                    ses.forward(cur[j], self._zeros, zeros, voted=self._dummy)
+                    ses.accept(self._zeros, voted=self._dummy)        # the cache keeps the token just scored
+                    B.mn_draft_sample(ses.model.ctx, ses.logits.data_ptr(), self.B, self.vocab, temperature, seed, step,
+                                      j, t, self.drafts[0, j, t:].data_ptr(), self.n * kk,
+                                      self.draft_probs[j, 0, t].data_ptr(), kk * self.vocab, stream_ptr())
+                    cur[j] = self.drafts[:, j, t].contiguous()
+        for st in streams:
+            main.wait_stream(st)
         return self.drafts
 
     def voted_probs(self, voted_ssm: torch.Tensor) -> torch.Tensor:
@@ -367,18 +395,28 @@ class GenerationLoop:
     def draft(self) -> torch.Tensor:
         """k greedy tokens from every SSM; the first forward also feeds the committed tokens the SSM missed."""
         k = self.k
-        for j in range(self.n):
-            f, s = self.first[j], self.single[j]
-            commit = torch.cat([self.ssm_extra[j], self._zeros[:, None]], dim=1).contiguous()
-            f.forward(self.ssm_last[j], self.ssm_nextra[j], self.h_nextra[j], voted=self.ssm_extra[j])
-            f.accept(self.ssm_nextra[j], voted=self.ssm_extra[j], tokens=commit)       # every fed row is kept
-            cur = f.greedy[self._ar, self.ssm_nextra[j].long()].contiguous()           # output of the last row
-            self.drafts[:, j, 0] = cur
-            for t in range(1, k):
-                s.forward(cur, self._zeros, [0] * self.B, voted=self._dummy)
-                s.accept(self._zeros, voted=self._dummy)
-                cur = s.next_last_tok.clone()
-                self.drafts[:, j, t] = cur
+        if not hasattr(self, "_streams"):
+            self._streams = [torch.cuda.Stream() for _ in range(self.n)]      # one per SSM: they are independent
+        main = torch.cuda.current_stream()
+        for st in self._streams:
+            st.wait_stream(main)
+        cur = [None] * self.n
+        for t in range(k):
+            for j in range(self.n):
+                f, s = self.first[j], self.single[j]
+                with torch.cuda.stream(self._streams[j]):
+                    if t == 0:
+                        commit = torch.cat([self.ssm_extra[j], self._zeros[:, None]], dim=1).contiguous()
+                        f.forward(self.ssm_last[j], self.ssm_nextra[j], self.h_nextra[j], voted=self.ssm_extra[j])
+                        f.accept(self.ssm_nextra[j], voted=self.ssm_extra[j], tokens=commit)   # every fed row is kept
+                        cur[j] = f.greedy[self._ar, self.ssm_nextra[j].long()].contiguous()    # output of the last row
+                    else:
+                        s.forward(cur[j], self._zeros, [0] * self.B, voted=self._dummy)
+                        s.accept(self._zeros, voted=self._dummy)
+                        cur[j] = s.next_last_tok.clone()
+                    self.drafts[:, j, t] = cur[j]
+        for st in self._streams:
+            main.wait_stream(st)
         return self.drafts
 
     def round(self, acr_args=None):
