@@ -196,6 +196,44 @@ def test_device_detected_errors_disable_only_the_bad_sequence(env):
     assert (ses4.greedy.cpu().numpy() == -1).all() and torch.equal(kvd4.k_pages[0], before4)
 
 
+def test_few_row_attention_path_disables_only_the_bad_sequence():
+    """The drafting models' shape (head_dim 64, one to four rows per sequence) takes its own attention kernel:
+    a sequence with a damaged block table becomes a no-op there too, the others are unaffected, plain decode
+    (k = 0) and short speculations mix in one batch."""
+    from paper_2402_15678_amd import binding, harness
+    desc = synth.ModelDesc(synth.ARCH_LLAMA, synth.DT_BF16, 2, 256, 4, 4, 64, 512, 1000, 512)
+    model = harness.DeviceModel.from_host(desc, synth.make_weights(desc, 78))
+    ctx, ks = np.array([30, 45, 60, 0, 129], np.int32), np.array([0, 3, 1, 2, 0], np.int32)
+    g = synth.stream(8, 2)
+    last = _i32(g.integers(0, desc.vocab, size=5))
+    voted = _i32(g.integers(0, desc.vocab, size=(5, 3)))
+    spec = _i32(ks)
+
+    def run(damage):
+        kvh = synth.make_paged_kv(desc, ctx, ks, 3)
+        kvd = harness.DeviceKV.from_host(desc, kvh)
+        if damage:
+            bt = kvd.block_tables.clone(); bt[1, 1] = 10 ** 6
+            kvd.block_tables.copy_(bt)
+        ses = harness.VerifySession(model, kvd, 5, 3, 1, int((ctx + ks + 1).max()), max_rows=int((ks + 1).sum()),
+                                    want_logits=True)
+        ses.forward(last, spec, ks.tolist(), voted=voted)
+        ses.accept(spec, voted=voted)
+        torch.cuda.synchronize()
+        return kvh, kvd, ses
+
+    _, kvd0, ref = run(False)
+    assert ref.dev_status.item() == 0 and (ref.greedy.cpu().numpy()[:, 0] >= 0).all()
+    kvh1, kvd1, bad = run(True)
+    assert bad.dev_status.item() & binding.MN_DEV_BLOCK_TABLE
+    got, want = bad.greedy.cpu().numpy(), ref.greedy.cpu().numpy()
+    assert (got[1] == -1).all() and np.array_equal(got[[0, 2, 3, 4]], want[[0, 2, 3, 4]])
+    assert bad.n_out.cpu().tolist()[1] == 0 and kvd1.ctx_lens.cpu().tolist()[1] == 45
+    ok_rows = [0, 5, 6, 7, 8, 9, 10]                       # rows of sequences 0, 2, 3, 4 (sequence 1 owns rows 1-4)
+    assert torch.equal(bad.logits[ok_rows], ref.logits[ok_rows])
+    assert [kvd1.ctx_lens.cpu().tolist()[b] for b in (0, 2, 3, 4)] == [kvd0.ctx_lens.cpu().tolist()[b] for b in (0, 2, 3, 4)]
+
+
 def test_measuring_sticks_run_and_report_plausible_rates(env):
     """The two probes behind the ABI: they launch, finish, and land in the range of a working MI355X
     (loose bounds: they are a ruler for the bench, not a performance test)."""
