@@ -237,6 +237,7 @@ mn_status mn_accept_and_commit(mn_ctx *ctx, const int32_t *voted, const int32_t 
  * numbers: the caller advances `step` once per verification step.  The top byte of the counter's last
  * word (above the 56 bits of `step`) is 0 here and 1 + i for drafting SSM i (mn_draft_sample), so one seed
  * serves all of them without shared numbers.
+ * Scores may be minus infinity (masked tokens: no mass); every row needs a finite maximum.
  * Errors: temperature must be positive and finite; step < 2^56; vocab <= 2^21; k_max <= 4096.  Rows that do not add
  * up to M set MN_DEV_SPEC_LEN in *dev_status and give -1.  ctx may be NULL. */
 mn_status mn_verify_sample(mn_ctx *ctx, const float *logits, const int32_t *voted, const float *draft_probs,

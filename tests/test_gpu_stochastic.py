@@ -118,6 +118,28 @@ def test_sample_then_accept_matches_oracle(hb, B, k_max, V, T, noise):
         _check_against_oracle(res, spec, logits, q, voted, k_max, T, 2024, step, ctx0)
 
 
+def test_masked_vocabulary_entries(hb):
+    """Scores of minus infinity (a masked part of the vocabulary) carry no mass on either side: such a token is
+    never drawn, and a speculated token that the LLM masks is always rejected."""
+    B, k_max, V, T = 12, 4, 1500, 1.0
+    spec, M, logits, q, voted = _case(5, B, k_max, V, T, 1.0)
+    g = synth.stream(4105, 0)
+    masked = g.random((M, V)) < 0.4
+    masked[np.arange(M), np.argmax(logits, axis=1)] = False           # every row keeps a finite maximum
+    logits[masked] = -np.inf
+    ctx0 = np.full(B, 20, np.int32)
+    res = _run_gpu(hb, spec, M, logits, q, voted, k_max, V, T, seed=11, step=3, ctx0=ctx0)
+    _check_against_oracle(res, spec, logits, q, voted, k_max, T, 11, 3, ctx0)
+    out, n_out = res[2], res[3]
+    row = 0
+    for b in range(B):
+        a = int(res[1][b])
+        assert not masked[row + a, out[b, a]]                          # the drawn token is not a masked one
+        for j in range(a):
+            assert not masked[row + j, voted[b, j]]                    # a survivor was not masked by the LLM
+        row += int(spec[b]) + 1
+
+
 def test_low_temperature_equals_greedy_acceptance(hb):
     """One-hot drafts and T -> 0: the output is the longest-prefix acceptance on the argmax tokens."""
     B, k_max, V, T = 32, 6, 777, 1e-3
