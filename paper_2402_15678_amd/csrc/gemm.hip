@@ -666,7 +666,12 @@ static GemmPlan gemm_plan(int M, int N, int K, int forced_split) {
     // up to six row tiles: 4-wave workgroups.  Few rows make an iteration cheap, so a split may be as short
     // as 8 iterations, and one workgroup per CU is enough (measured at 40 rows: the 5120 x 5120 matrix
     // gains 30 % from 5 splits over 2, the 20480-column one loses with any split)
-    best.split = splits_for((slices + 3) / 4, tune().target / 2, 8);
+    const int gx = (slices + 3) / 4;
+    best.split = splits_for(gx, tune().target / 2, 8);
+    // small matrices (the drafting models: a few hundred KB per projection) would leave most of the chip
+    // idle at that rule, and their time is launch and memory latency rather than bandwidth: splits as short
+    // as one iteration, up to about a hundred workgroups
+    if (gx * best.split < 64) best.split = splits_for(gx, 96, 1);
     return best;
   }
   int best_cus = 0, best_waves = 0;

@@ -405,7 +405,29 @@ __global__ void __launch_bounds__(256) argmax_rows_kernel(const float* __restric
   const float* r = logits + (size_t)m * V;
   float bv = -INFINITY;
   int bi = 0x7FFFFFFF;
-  for (int i = tid; i < V; i += blockDim.x) arg_better(bv, bi, r[i], i);
+  if ((V & 3) == 0) {
+    // 16-byte pieces, eight in flight per thread before any is looked at (one piece per round trip is bound
+    // by memory latency); a thread's indices grow, and ties between threads are settled by arg_better
+    const float4* r4 = reinterpret_cast<const float4*>(r);
+    const int n4 = V >> 2;
+    for (int i0 = tid; i0 < n4; i0 += 8 * 256) {
+      float4 p[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) p[u] = r4[min(i0 + u * 256, n4 - 1)];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i4 = i0 + u * 256;
+        if (i4 < n4) {
+          arg_better(bv, bi, p[u].x, 4 * i4);
+          arg_better(bv, bi, p[u].y, 4 * i4 + 1);
+          arg_better(bv, bi, p[u].z, 4 * i4 + 2);
+          arg_better(bv, bi, p[u].w, 4 * i4 + 3);
+        }
+      }
+    }
+  } else {
+    for (int i = tid; i < V; i += blockDim.x) arg_better(bv, bi, r[i], i);
+  }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     const float ov = __shfl_xor(bv, o, 64);
