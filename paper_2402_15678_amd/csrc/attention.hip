@@ -551,16 +551,19 @@ __global__ void __launch_bounds__(FR_NW * 64) attn_fewrow_kernel(AttnArgs a) {
   const int kvh = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int t = lane & 15, g = lane >> 4;
   const int G = a.H / a.Hkv;
-  const int row0 = a.rows.seq_row0[b];
-  const int qb = a.rows.seq_row0[b + 1] - row0;
+  // (the sequence's scalars in one round trip, as in the MFMA kernel)
+  const int row0 = a.rows.seq_row0[b], row1 = a.rows.seq_row0[b + 1];
+  const int seq_ok = a.rows.seq_ok[b];
+  const int ctx = a.rows.seq_ctx[b];
+  asm volatile("" ::"r"(seq_ok), "r"(ctx));
+  const int qb = row1 - row0;
   if (qb <= 0) return;                       // (whole workgroup)
   const int R = min(G * qb, RR);             // stacked rows r = j*G + gi (the host launches RR >= G * max_q)
   f16_t* out = reinterpret_cast<f16_t*>(a.out);
-  if (!a.rows.seq_ok[b]) {                   // disabled sequence: zeros (whole workgroup)
+  if (!seq_ok) {                             // disabled sequence: zeros (whole workgroup)
     if (wave < R) out[((size_t)(row0 + wave / G) * a.H + kvh * G + wave % G) * FR_HD + lane] = (f16_t)0.f;
     return;
   }
-  const int ctx = a.rows.seq_ctx[b];
   const f16_t* Q = reinterpret_cast<const f16_t*>(a.q);
   const f16_t* Kn = reinterpret_cast<const f16_t*>(a.knew);
   const f16_t* Vn = reinterpret_cast<const f16_t*>(a.vnew);
