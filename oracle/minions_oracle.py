@@ -27,6 +27,7 @@ What it computes, with the passage of the paper each part follows:
                      SSM's probability does not exceed the LLM's, otherwise reject it with probability
                      1 - o/q and draw a replacement from the renormalised positive part of o - q), with
                      its random numbers from a counter-based generator (``philox4x32``).
+* ``draft_sample``   the drafting side of that rule: an SSM's token drawn from its own distribution.
 * ``commit``         drop the cache entries of the rejected tokens (section 4): the context
                      grows by the accepted prefix plus the pending token.
 * ``acr_update``     speculation quality metric (equation ACR) and the multiplicative weight
@@ -43,7 +44,10 @@ updated multiplicatively and the order of the sum is part of the contract.
 Pins: tests/test_oracle_*.py (worked example of the paper's figure "majority", brute
 force over an explicit token tree, a PyTorch-CPU fp64 model assembled from library
 routines, closed forms for the norms and the rotary embedding, cached vs cache-less,
-multi-position vs sequential single-position, losslessness vs plain greedy decoding).
+multi-position vs sequential single-position, losslessness vs plain greedy decoding; for the stochastic
+rule: the generator's published known answers, the emitted-token distribution against the LLM's, the
+greedy limit, the rejection probability; for the quality metric and the selector: hand-computed cases and
+a library least-squares fit).  No function here is unpinned.
 """
 from __future__ import annotations
 
