@@ -152,8 +152,8 @@ static size_t al(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
   size_t row_seq, row_j, row_pos, row_tok, seq_row0, seq_ctx, seq_ok, attn_tps, rope_cos, rope_sin;
-  size_t x, h, q, knew, vnew, attn, act, partials, logits, attn_scratch, total;
-  size_t partials_bytes, attn_scratch_bytes;
+  size_t x, h, q, knew, vnew, attn, act, partials, logits, attn_scratch, attn_items, total;
+  size_t partials_bytes, attn_scratch_bytes, attn_items_capacity;
 };
 
 static Layout make_layout(const mn_model_desc& d, int B, int M, int max_ctx) {
@@ -189,6 +189,8 @@ static Layout make_layout(const mn_model_desc& d, int B, int M, int max_ctx) {
   L.logits = take(Mr * d.vocab * 4);
   L.attn_scratch_bytes = attention_scratch_bytes(M, d.n_heads, d.head_dim, max_ctx, d.dtype);
   L.attn_scratch = take(L.attn_scratch_bytes);
+  L.attn_items_capacity = attention_items_capacity(B, M, d.n_heads, d.n_kv_heads);
+  L.attn_items = take(L.attn_items_capacity * 8 * 4);
   L.total = at;
   return L;
 }
@@ -463,6 +465,11 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
     at.B = B; at.M = M; at.H = d.n_heads; at.Hkv = d.n_kv_heads; at.hd = d.head_dim; at.dtype = d.dtype;
     at.max_ctx = max_ctx; at.max_q = max_q;
     at.scratch = w.at<float>(w.L.attn_scratch); at.scratch_bytes = w.L.attn_scratch_bytes;
+    at.items = w.at<int32_t>(w.L.attn_items); at.items_capacity = w.L.attn_items_capacity;
+    if (l == 0) {  // the list of attention workgroups is the same for every layer
+      Tap t(&c->prof, MN_PROF_PREPARE, st);
+      launch_attention_plan(at, st);
+    }
     {
       Tap t(&c->prof, MN_PROF_ATTENTION, st);
       launch_attention(at, st);
@@ -593,6 +600,8 @@ extern "C" mn_status mn_attention(mn_ctx* c, const void* q, const int32_t* spec_
   at.B = B; at.M = M; at.H = d.n_heads; at.Hkv = d.n_kv_heads; at.hd = d.head_dim; at.dtype = d.dtype;
   at.max_ctx = max_ctx; at.max_q = max_q;
   at.scratch = w.at<float>(w.L.attn_scratch); at.scratch_bytes = w.L.attn_scratch_bytes;
+  at.items = w.at<int32_t>(w.L.attn_items); at.items_capacity = w.L.attn_items_capacity;
+  launch_attention_plan(at, st);
   {
     Tap t(&c->prof, MN_PROF_ATTENTION, st);
     launch_attention(at, st);

@@ -122,7 +122,7 @@ __global__ void __launch_bounds__(GEN_THREADS) attn_generic_kernel(AttnArgs a) {
 // ------------------------------------------------------------------------------------------
 // MFMA kernel (bf16 pages, fp16 queries, head_dim 128, block 16)
 // ------------------------------------------------------------------------------------------
-// Workgroup (4 waves) = one (KV head, sequence, KV split).  The R = G*q_b query rows that share the
+// Workgroup (4 waves) = one (KV head, sequence, row group, KV split).  The R = G*q_b query rows that share the
 // KV head are cut into 16-row column tiles; wave w owns tiles w, w+4, (w+8) and keeps their query
 // fragments (pre-multiplied by log2(e)/sqrt(hd)) in registers.
 //
@@ -210,39 +210,35 @@ __device__ __forceinline__ int seq_splits(int n_tiles, int tps, int n_splits_max
 
 // Partials: o_part [split][M][H][HD] fp32 (unnormalised), ml_part [split][M][H][2] = (max in log2 units, sum)
 template <int CTW>
-__global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, int n_splits, int n_rg, float* __restrict__ o_part,
+__global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, float* __restrict__ o_part,
                                                            float* __restrict__ ml_part) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   f16_t* s_kv = reinterpret_cast<f16_t*>(smem);                          // [NS][16 fragments][64 lanes][8]
   int32_t* s_bidx = reinterpret_cast<int32_t*>(smem + NS * TILE_BYTES);  // physical block of every block of the split
-  // row group rg: column tiles [4*CTW*rg, 4*CTW*(rg+1)) of the stack; sequences with more than 64*CTW
-  // stacked rows get a workgroup per group (each streams the keys again), the others leave at once
-  // grid (KV head, sequence x row group, split): workgroup ids are dealt round-robin over the 8 XCDs, so with
-  // the KV head as the fastest index the work spreads evenly whatever splits and row groups turn out empty
-  // (with the split fastest, a batch that uses 2 of 16 possible splits would run on 2 of the 8 XCDs)
-  const int kvh = blockIdx.x, b = blockIdx.y / n_rg, rg = blockIdx.y % n_rg, split = blockIdx.z;
+  // Work list: workgroup (item, KV head) takes record `item` of the list attn_plan_kernel wrote for this step:
+  // {sequence, row group, split, splits of the sequence, first row, rows, enabled, context}.  The list holds
+  // only workgroups that have work, longest first, and the KV head is the fast index: workgroup ids are dealt
+  // round-robin over the 8 XCDs and, inside an XCD, over its CUs, strictly in id order, so work has to be
+  // dense in the id space (with the split as the fast grid index a batch that used 2 of 16 possible splits
+  // ran on 2 of the 8 XCDs; with an often empty second row group next to the sequence index the real
+  // workgroups shared half of the CUs) and long items must not queue behind short ones.
+  // Row group rg: column tiles [4*CTW*rg, 4*CTW*(rg+1)) of the stack; sequences with more than 64*CTW stacked
+  // rows get a workgroup per group (each streams the keys again).
+  const int item = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
+  const int4 rec0 = reinterpret_cast<const int4*>(a.items)[2 * item];
+  const int4 rec1 = reinterpret_cast<const int4*>(a.items)[2 * item + 1];
+  const int b = rec0.x, rg = rec0.y, split = rec0.z, my_splits = rec0.w;
+  if (b < 0) return;                      // past the end of the list (whole workgroup)
+  const int row0 = rec1.x, qb = rec1.y, ok = rec1.z, ctx = rec1.w;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
   const int G = a.H / a.Hkv;
-  // everything known about the sequence in one round trip (these few words are cold after the projections
-  // before have streamed through the caches; fetched one after the other they cost a microsecond each)
-  const int row0 = a.rows.seq_row0[b], row1 = a.rows.seq_row0[b + 1];
-  const int ok = a.rows.seq_ok[b];
-  const int ctx = a.rows.seq_ctx[b];
-  const int tps = a.rows.attn_tps[0];
-  asm volatile("" ::"r"(ok), "r"(ctx), "r"(tps));  // (keeps the compiler from sinking the loads below the exits)
-  const int qb = row1 - row0;
-  if (qb <= 0) return;
   const int R = G * qb;                   // query rows sharing this KV head; row r = j*G + gi
   const int NT16 = (R + 15) >> 4;         // column tiles in use
   const int tile0 = 4 * CTW * rg;         // first column tile of this workgroup
-  if (tile0 >= NT16) return;              // (whole workgroup)
+  if (qb <= 0 || tile0 >= NT16 || split >= my_splits) return;  // (whole workgroup; the list holds no such record)
   const int nkeys = ok ? ctx + qb : 0;
   const int n_tiles = (nkeys + KT - 1) / KT;
-  // this sequence's own number of KV splits (the grid holds the largest any sequence may get): about
-  // attn_tps key tiles per workgroup, so the long sequences of a ragged batch are cut finer than the short ones
-  const int my_splits = seq_splits(n_tiles, tps, n_splits);
-  if (split >= my_splits) return;         // (whole workgroup)
   const int t_begin = (int)(((long)n_tiles * split) / my_splits);
   const int t_end = (int)(((long)n_tiles * (split + 1)) / my_splits);
   const int n_my = max(0, t_end - t_begin);
@@ -722,6 +718,51 @@ static bool fewrow_supported(const AttnArgs& a, int G) {
 // ------------------------------------------------------------------------------------------
 // launch
 // ------------------------------------------------------------------------------------------
+// The list of workgroups of the MFMA kernel for this step (the same for every layer): one record of 8 int32 per
+// (sequence, row group, KV split) that has work: {sequence, row group, split, splits of the sequence, first
+// row, rows, enabled, context}.  Sequences are ordered by descending key tiles per workgroup (ties by index),
+// so the longest workgroups start first and the short ones fill the end of the launch; the records of the
+// grid past the last real one get sequence = -1.  One workgroup; ranking is a comparison of every pair of
+// sequences (B <= 4096, once per step).
+__global__ void __launch_bounds__(1024) attn_plan_kernel(RowInfo rows, int B, int G, int tiles16_per_wg, int n_splits_max,
+                                                         int grid_items, int32_t* __restrict__ items) {
+  __shared__ int s_key[MN_MAX_BATCH], s_cnt[MN_MAX_BATCH], s_spl[MN_MAX_BATCH];
+  __shared__ int s_total;
+  const int tid = threadIdx.x;
+  const int tps = rows.attn_tps[0];
+  for (int b = tid; b < B; b += blockDim.x) {
+    const int q = rows.seq_row0[b + 1] - rows.seq_row0[b];
+    const int n_tiles = rows.seq_ok[b] ? (rows.seq_ctx[b] + q + KT - 1) / KT : 0;
+    const int nt16 = (G * q + 15) >> 4;
+    const int n_rg = q > 0 ? (nt16 + tiles16_per_wg - 1) / tiles16_per_wg : 0;
+    const int spl = seq_splits(n_tiles, tps, n_splits_max);
+    s_spl[b] = spl;
+    s_cnt[b] = n_rg * spl;                       // a disabled sequence keeps one workgroup per row group: it writes zeros
+    s_key[b] = (n_tiles + spl - 1) / spl;
+  }
+  __syncthreads();
+  for (int b = tid; b < B; b += blockDim.x) {
+    const int key = s_key[b], cnt = s_cnt[b], spl = s_spl[b];
+    int off = 0, total = 0;
+    for (int b2 = 0; b2 < B; ++b2) {
+      const int c = s_cnt[b2], k2 = s_key[b2];
+      total += c;
+      if (k2 > key || (k2 == key && b2 < b)) off += c;
+    }
+    if (b == 0) s_total = total;
+    const int row0 = rows.seq_row0[b], q = rows.seq_row0[b + 1] - row0, ok = rows.seq_ok[b], ctx = rows.seq_ctx[b];
+    for (int i = 0; i < cnt; ++i) {
+      if (off + i >= grid_items) break;        // (cannot happen: the grid holds every real record)
+      int4* rec = reinterpret_cast<int4*>(items) + 2 * (size_t)(off + i);
+      rec[0] = make_int4(b, i / spl, i % spl, spl);
+      rec[1] = make_int4(row0, q, ok, ctx);
+    }
+  }
+  __syncthreads();
+  for (int i = s_total + tid; i < grid_items; i += blockDim.x)
+    reinterpret_cast<int4*>(items)[2 * (size_t)i] = make_int4(-1, 0, 0, 1);
+}
+
 // Largest number of KV splits any sequence of the batch may get (the grid's x extent; every sequence then
 // takes what its own length asks for, see seq_splits): one per 16 key tiles of the longest context.
 static int pick_splits(int B, int Hkv, int max_ctx) {
@@ -755,16 +796,48 @@ size_t attention_scratch_bytes(int M, int H, int hd, int max_ctx, int dtype) {
   return (size_t)16 * M * H * (HD + 2) * sizeof(float) + 256;
 }
 
+// Records the work list must hold: a sequence of q rows has at most G q / 64 + 1 row groups (a workgroup covers
+// at least 64 stacked rows) of at most 16 splits each.
+size_t attention_items_capacity(int B, int M, int H, int Hkv) {
+  const size_t G = Hkv > 0 ? (size_t)(H / Hkv) : 1;
+  return 16 * (G * (size_t)(M > 0 ? M : 0) / 64 + (size_t)(B > 0 ? B : 0)) + 16;
+}
+
+// Shape of the MFMA launch, from what the host knows (largest row count of a sequence, longest context).
+struct MfmaShape {
+  int ctw, n_rg, n_splits, grid_items;
+};
+static MfmaShape mfma_shape(const AttnArgs& a) {
+  const int G = a.Hkv > 0 ? a.H / a.Hkv : 1;
+  // the kernel covers 4 * CTW column tiles of 16 stacked query rows per workgroup; longer stacks are cut into
+  // row groups
+  const int nt16_max = (G * a.max_q + 15) / 16;
+  MfmaShape s;
+  s.ctw = nt16_max <= 4 ? 1 : MAX_CT;
+  s.n_rg = (nt16_max + 4 * s.ctw - 1) / (4 * s.ctw);
+  s.n_splits = pick_splits(a.B, a.Hkv, a.max_ctx);
+  const size_t bound = (size_t)a.B * s.n_rg * s.n_splits;
+  s.grid_items = (int)(bound < a.items_capacity ? bound : a.items_capacity);
+  return s;
+}
+static bool mfma_path(const AttnArgs& a) {
+  return attention_mfma_supported(a.H, a.Hkv, a.hd, a.kv.block_size, a.dtype) && a.scratch != nullptr &&
+         a.scratch_bytes >= attention_scratch_bytes(a.M, a.H, a.hd, a.max_ctx, a.dtype) && a.items != nullptr &&
+         a.items_capacity >= attention_items_capacity(a.B, a.M, a.H, a.Hkv);
+}
+
+void launch_attention_plan(const AttnArgs& a, hipStream_t st) {
+  if (a.M <= 0 || a.B <= 0 || !mfma_path(a)) return;
+  const MfmaShape s = mfma_shape(a);
+  attn_plan_kernel<<<1, 1024, 0, st>>>(a.rows, a.B, a.H / a.Hkv, 4 * s.ctw, s.n_splits, s.grid_items, a.items);
+}
+
 void launch_attention(const AttnArgs& a, hipStream_t st) {
   if (a.M <= 0 || a.B <= 0) return;
   const int G = a.Hkv > 0 ? a.H / a.Hkv : 1;
-  // the MFMA kernel covers 4 * MAX_CT column tiles of 16 stacked query rows per workgroup; longer stacks
-  // are cut into row groups
-  const int nt16_max = (G * a.max_q + 15) / 16;
-  const bool mfma = attention_mfma_supported(a.H, a.Hkv, a.hd, a.kv.block_size, a.dtype) && a.scratch != nullptr &&
-                    a.scratch_bytes >= attention_scratch_bytes(a.M, a.H, a.hd, a.max_ctx, a.dtype);
-  if (mfma) {
-    const int n_splits = pick_splits(a.B, a.Hkv, a.max_ctx);
+  if (mfma_path(a)) {
+    const MfmaShape sh = mfma_shape(a);
+    const int n_splits = sh.n_splits;
     float* o_part = a.scratch;
     float* ml_part = a.scratch + (size_t)n_splits * a.M * a.H * HD;
     const int tiles_per_split = ((a.max_ctx + KT - 1) / KT + n_splits - 1) / n_splits + 1;
@@ -776,12 +849,9 @@ void launch_attention(const AttnArgs& a, hipStream_t st) {
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, most);
       attr_set = true;
     }
-    if (nt16_max <= 4) {
-      attn_mfma_kernel<1><<<dim3(a.Hkv, a.B, n_splits), 256, smem, st>>>(a, n_splits, 1, o_part, ml_part);
-    } else {
-      const int n_rg = (nt16_max + 4 * MAX_CT - 1) / (4 * MAX_CT);
-      attn_mfma_kernel<2><<<dim3(a.Hkv, a.B * n_rg, n_splits), 256, smem, st>>>(a, n_splits, n_rg, o_part, ml_part);
-    }
+    const unsigned grid = (unsigned)a.Hkv * (unsigned)sh.grid_items;
+    if (sh.ctw == 1) attn_mfma_kernel<1><<<grid, 256, smem, st>>>(a, o_part, ml_part);
+    else attn_mfma_kernel<2><<<grid, 256, smem, st>>>(a, o_part, ml_part);
     if (n_splits > 1) {
       const int waves = a.M * a.H;
       attn_merge_kernel<<<(waves + 3) / 4, 256, 0, st>>>(o_part, ml_part, n_splits, a.M, a.H, a.rows, reinterpret_cast<f16_t*>(a.out));

@@ -111,9 +111,14 @@ struct AttnArgs {
   int max_q;       // largest number of rows of one sequence (host knowledge)
   float* scratch;  // split-KV partials
   size_t scratch_bytes;
+  int32_t* items;        // work list of the MFMA kernel, 8 int32 per record (see launch_attention_plan), or null
+  size_t items_capacity; // records the buffer holds
 };
 size_t attention_scratch_bytes(int M, int H, int hd, int max_ctx, int dtype);
 bool attention_mfma_supported(int H, int Hkv, int hd, int block_size, int dtype);
+size_t attention_items_capacity(int B, int M, int H, int Hkv);
+// once per step, after the row bookkeeping and before the first launch_attention: the list of workgroups
+void launch_attention_plan(const AttnArgs& a, hipStream_t st);
 void launch_attention(const AttnArgs& a, hipStream_t st);
 
 }  // namespace mn
