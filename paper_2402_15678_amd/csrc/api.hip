@@ -366,12 +366,13 @@ static void run_prepare(mn_ctx* c, const Ws& w, const int32_t* last_tok, const i
   p.attn_tps = w.at<int32_t>(w.L.attn_tps);
   p.kv_heads = c->d.n_kv_heads;
   p.q_per_kv = c->d.n_heads / c->d.n_kv_heads;
-  // 1.5 workgroups per CU: measured flat between 1 and 2 per CU, slower beyond (every further split of a
-  // sequence writes and re-reads one more fp32 partial of its rows)
+  // 1.25 workgroups per CU: measured flat between 1 and 1.3 per CU, slower beyond (every further split of a
+  // sequence writes and re-reads one more fp32 partial of its rows, and workgroups beyond the 512 that are
+  // resident at once start when the first ones end)
   static const int attn_wgs = [] {
     const char* e = getenv("MN_ATTN_WGS");  // experiment switch
     const int v = e ? atoi(e) : 0;
-    return v > 0 ? v : 384;
+    return v > 0 ? v : 320;
   }();
   p.attn_wgs = attn_wgs;
   p.rope_cos = w.at<float>(w.L.rope_cos); p.rope_sin = w.at<float>(w.L.rope_sin);
