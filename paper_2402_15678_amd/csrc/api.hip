@@ -152,7 +152,7 @@ static size_t al(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
   size_t row_seq, row_j, row_pos, row_tok, seq_row0, seq_ctx, seq_ok, attn_tps, rope_cos, rope_sin;
-  size_t x, h, q, knew, vnew, attn, act, partials, logits, attn_scratch, attn_items, total;
+  size_t x, h, q, knew, vnew, attn, act, partials, logits, attn_scratch, attn_items, attn_row_splits, total;
   size_t partials_bytes, attn_scratch_bytes, attn_items_capacity;
 };
 
@@ -191,6 +191,7 @@ static Layout make_layout(const mn_model_desc& d, int B, int M, int max_ctx) {
   L.attn_scratch = take(L.attn_scratch_bytes);
   L.attn_items_capacity = attention_items_capacity(B, M, d.n_heads, d.n_kv_heads);
   L.attn_items = take(L.attn_items_capacity * 8 * 4);
+  L.attn_row_splits = take(Mr * 4);
   L.total = at;
   return L;
 }
@@ -467,6 +468,7 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
     at.max_ctx = max_ctx; at.max_q = max_q;
     at.scratch = w.at<float>(w.L.attn_scratch); at.scratch_bytes = w.L.attn_scratch_bytes;
     at.items = w.at<int32_t>(w.L.attn_items); at.items_capacity = w.L.attn_items_capacity;
+    at.row_splits = w.at<int32_t>(w.L.attn_row_splits);
     if (l == 0) {  // the list of attention workgroups is the same for every layer
       Tap t(&c->prof, MN_PROF_PREPARE, st);
       launch_attention_plan(at, st);
@@ -602,6 +604,7 @@ extern "C" mn_status mn_attention(mn_ctx* c, const void* q, const int32_t* spec_
   at.max_ctx = max_ctx; at.max_q = max_q;
   at.scratch = w.at<float>(w.L.attn_scratch); at.scratch_bytes = w.L.attn_scratch_bytes;
   at.items = w.at<int32_t>(w.L.attn_items); at.items_capacity = w.L.attn_items_capacity;
+  at.row_splits = w.at<int32_t>(w.L.attn_row_splits);
   launch_attention_plan(at, st);
   {
     Tap t(&c->prof, MN_PROF_ATTENTION, st);

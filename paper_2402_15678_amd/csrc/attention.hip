@@ -492,16 +492,14 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, float* __
 // One wave per (row, head): merge the split partials, normalise, store fp16.  Rows of sequences that ran as
 // one split were written in final form by the attention kernel and are left alone.
 __global__ void __launch_bounds__(256) attn_merge_kernel(const float* __restrict__ o_part, const float* __restrict__ ml_part,
-                                                         int n_splits_max, int M, int H, RowInfo rows,
-                                                         f16_t* __restrict__ out) {
+                                                         int n_splits_max, int M, int H,
+                                                         const int32_t* __restrict__ row_splits, f16_t* __restrict__ out) {
   const int wid = (blockIdx.x * 256 + threadIdx.x) >> 6, lane = threadIdx.x & 63;
   if (wid >= M * H) return;
-  const int m = wid / H;
-  const int b = rows.row_seq[m];
-  const int qb = rows.seq_row0[b + 1] - rows.seq_row0[b];
-  const int nkeys = rows.seq_ok[b] ? rows.seq_ctx[b] + qb : 0;
-  const int n_splits = seq_splits((nkeys + KT - 1) / KT, rows.attn_tps[0], n_splits_max);
-  if (n_splits == 1) return;
+  // (one read decides: most rows of a ragged batch have nothing to merge; the bound keeps a damaged entry from
+  // reaching past the partials)
+  const int n_splits = min(row_splits[wid / H], n_splits_max);
+  if (n_splits <= 1) return;
   float gm = -INFINITY;
   for (int s = 0; s < n_splits; ++s) gm = fmaxf(gm, ml_part[((size_t)s * M * H + wid) * 2]);
   const float ms = (gm == -INFINITY) ? 0.f : gm;
@@ -725,11 +723,13 @@ static bool fewrow_supported(const AttnArgs& a, int G) {
 // grid past the last real one get sequence = -1.  One workgroup; ranking is a comparison of every pair of
 // sequences (B <= 4096, once per step).
 __global__ void __launch_bounds__(1024) attn_plan_kernel(RowInfo rows, int B, int G, int tiles16_per_wg, int n_splits_max,
-                                                         int grid_items, int32_t* __restrict__ items) {
+                                                         int grid_items, int32_t* __restrict__ items, int M,
+                                                         int32_t* __restrict__ row_splits) {
   __shared__ int s_key[MN_MAX_BATCH], s_cnt[MN_MAX_BATCH], s_spl[MN_MAX_BATCH];
   __shared__ int s_total;
   const int tid = threadIdx.x;
   const int tps = rows.attn_tps[0];
+  for (int m = tid; m < M; m += blockDim.x) row_splits[m] = 0;   // rows of no sequence (a disabled batch) merge nothing
   for (int b = tid; b < B; b += blockDim.x) {
     const int q = rows.seq_row0[b + 1] - rows.seq_row0[b];
     const int n_tiles = rows.seq_ok[b] ? (rows.seq_ctx[b] + q + KT - 1) / KT : 0;
@@ -751,6 +751,7 @@ __global__ void __launch_bounds__(1024) attn_plan_kernel(RowInfo rows, int B, in
     }
     if (b == 0) s_total = total;
     const int row0 = rows.seq_row0[b], q = rows.seq_row0[b + 1] - row0, ok = rows.seq_ok[b], ctx = rows.seq_ctx[b];
+    for (int j = 0; j < q; ++j) row_splits[row0 + j] = spl;   // for the merge: which rows have partials at all
     for (int i = 0; i < cnt; ++i) {
       if (off + i >= grid_items) break;        // (cannot happen: the grid holds every real record)
       int4* rec = reinterpret_cast<int4*>(items) + 2 * (size_t)(off + i);
@@ -823,13 +824,15 @@ static MfmaShape mfma_shape(const AttnArgs& a) {
 static bool mfma_path(const AttnArgs& a) {
   return attention_mfma_supported(a.H, a.Hkv, a.hd, a.kv.block_size, a.dtype) && a.scratch != nullptr &&
          a.scratch_bytes >= attention_scratch_bytes(a.M, a.H, a.hd, a.max_ctx, a.dtype) && a.items != nullptr &&
+         a.row_splits != nullptr &&
          a.items_capacity >= attention_items_capacity(a.B, a.M, a.H, a.Hkv);
 }
 
 void launch_attention_plan(const AttnArgs& a, hipStream_t st) {
   if (a.M <= 0 || a.B <= 0 || !mfma_path(a)) return;
   const MfmaShape s = mfma_shape(a);
-  attn_plan_kernel<<<1, 1024, 0, st>>>(a.rows, a.B, a.H / a.Hkv, 4 * s.ctw, s.n_splits, s.grid_items, a.items);
+  attn_plan_kernel<<<1, 1024, 0, st>>>(a.rows, a.B, a.H / a.Hkv, 4 * s.ctw, s.n_splits, s.grid_items, a.items, a.M,
+                                       a.row_splits);
 }
 
 void launch_attention(const AttnArgs& a, hipStream_t st) {
@@ -854,7 +857,7 @@ void launch_attention(const AttnArgs& a, hipStream_t st) {
     else attn_mfma_kernel<2><<<grid, 256, smem, st>>>(a, o_part, ml_part);
     if (n_splits > 1) {
       const int waves = a.M * a.H;
-      attn_merge_kernel<<<(waves + 3) / 4, 256, 0, st>>>(o_part, ml_part, n_splits, a.M, a.H, a.rows, reinterpret_cast<f16_t*>(a.out));
+      attn_merge_kernel<<<(waves + 3) / 4, 256, 0, st>>>(o_part, ml_part, n_splits, a.M, a.H, a.row_splits, reinterpret_cast<f16_t*>(a.out));
     }
     return;
   }

@@ -113,6 +113,7 @@ struct AttnArgs {
   size_t scratch_bytes;
   int32_t* items;        // work list of the MFMA kernel, 8 int32 per record (see launch_attention_plan), or null
   size_t items_capacity; // records the buffer holds
+  int32_t* row_splits;   // [M] KV splits of the row's sequence (written by the plan, read by the merge), or null
 };
 size_t attention_scratch_bytes(int M, int H, int hd, int max_ctx, int dtype);
 bool attention_mfma_supported(int H, int Hkv, int hd, int block_size, int dtype);
