@@ -764,15 +764,14 @@ __global__ void __launch_bounds__(1024) attn_plan_kernel(RowInfo rows, int B, in
     reinterpret_cast<int4*>(items)[2 * (size_t)i] = make_int4(-1, 0, 0, 1);
 }
 
-// Largest number of KV splits any sequence of the batch may get (the grid's x extent; every sequence then
-// takes what its own length asks for, see seq_splits): one per 16 key tiles of the longest context.
-static int pick_splits(int B, int Hkv, int max_ctx) {
+// Largest number of KV splits any sequence of the batch may get (it sizes the partials and bounds the work list;
+// every sequence then takes what its own length asks for, see seq_splits): one per 16 key tiles of the longest
+// context.
+static int pick_splits(int max_ctx) {
   static int forced = [] {
-    const char* e = getenv("MN_ATTN_SPLITS");
+    const char* e = getenv("MN_ATTN_SPLITS");  // experiment switch
     return e ? atoi(e) : 0;
   }();
-  (void)B;
-  (void)Hkv;
   const int tiles = (max_ctx + KT - 1) / KT;
   int s = forced > 0 ? forced : tiles / 16;
   if (s > 16) s = 16;
@@ -816,7 +815,7 @@ static MfmaShape mfma_shape(const AttnArgs& a) {
   MfmaShape s;
   s.ctw = nt16_max <= 4 ? 1 : MAX_CT;
   s.n_rg = (nt16_max + 4 * s.ctw - 1) / (4 * s.ctw);
-  s.n_splits = pick_splits(a.B, a.Hkv, a.max_ctx);
+  s.n_splits = pick_splits(a.max_ctx);
   const size_t bound = (size_t)a.B * s.n_rg * s.n_splits;
   s.grid_items = (int)(bound < a.items_capacity ? bound : a.items_capacity);
   return s;
