@@ -42,10 +42,10 @@ def parse_args():
     return ap.parse_args()
 
 
-def measured_traffic(workload_name):
-    """HBM bytes per GEMM launch from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE scaled by a
-    copy kernel of known size), or None when there is no summary for this workload."""
-    path = os.path.join(ROOT, "profiles", "gemm_w16_kernel_%s.hbm_traffic.txt" % workload_name)
+def measured_traffic(workload_name, kernel="gemm_w16_kernel"):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE +
+    WRITE_SIZE scaled by a copy kernel of known size), or None when there is no summary for this workload."""
+    path = os.path.join(ROOT, "profiles", "%s_%s.hbm_traffic.txt" % (kernel, workload_name))
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch"):
@@ -53,6 +53,15 @@ def measured_traffic(workload_name):
     except OSError:
         pass
     return None
+
+
+def calibration_copy(torch, dev):
+    """One 1 GiB device-to-device copy: a kernel that reads and writes a known number of bytes."""
+    src = torch.empty((1 << 30,), dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
 
 
 def cpu_baseline(wl, desc, M, ks, ctx, n_drafts):
@@ -135,8 +144,16 @@ def measure_ceilings(torch, binding, harness):
     e1.record()
     torch.cuda.synchronize()
     mfma = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
-    return {"hbm_stream_read_GBps": hbm, "mfma_f16_dense_TFLOPs": mfma,
-            "note": "measured on this box by mn_probe_stream_read / mn_probe_mfma; the roofline peaks above are the published ones"}
+    binding.mn_probe_mfma_data(2000, st)
+    e0.record()
+    flop = binding.mn_probe_mfma_data(100000, st)
+    e1.record()
+    torch.cuda.synchronize()
+    mfma_data = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    return {"hbm_stream_read_GBps": hbm, "mfma_f16_dense_TFLOPs": mfma, "mfma_f16_dense_TFLOPs_on_data": mfma_data,
+            "note": "measured on this box by mn_probe_stream_read / mn_probe_mfma (constant operands, boost clock) / "
+                    "mn_probe_mfma_data (operands of random sign and mantissa: the clock the chip holds on data); "
+                    "the roofline peaks above are the published ones"}
 
 
 def attention_only(args, wl):
@@ -177,6 +194,8 @@ def attention_only(args, wl):
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) / args.steps * 1e3
     assert status.item() == 0
+    if args.calibrate_copy:
+        calibration_copy(torch, dev)
     binding.mn_profile_enable(model.ctx, True)
     for _ in range(max(1, args.profile_steps)):
         step()
@@ -197,7 +216,8 @@ def attention_only(args, wl):
         "note": "ms_per_step is one mn_attention call (row bookkeeping kernel + attention + merge); the roofline "
                 "covers the attention and merge kernels, timed by the library's event taps",
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_launch": kv_bytes,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(wl.name, "attn_mfma_kernel"),
+                     "algorithmic_bytes_per_launch": kv_bytes,
                      "kernel": "attn_mfma_kernel + attn_merge_kernel", "avg_launch_us": att_ms * 1e3,
                      "mfma_tflops": flops / (att_ms * 1e-3) / 1e12,
                      "mfma_frac": flops / (att_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS},
@@ -425,11 +445,7 @@ def main():
         binding.mn_profile_enable(model.ctx, False)
 
     if args.calibrate_copy:
-        src = torch.empty((1 << 30,), dtype=torch.uint8, device=dev).fill_(1)
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        calibration_copy(torch, dev)
 
     gemm_bytes_step = 2.0 * desc.gemm_params()          # every matrix parameter (2 bytes) is needed once per step
     roofline = None
@@ -440,13 +456,19 @@ def main():
         per_launch_ms = gemm_ms / max(1, gemm_n)
         achieved = gemm_bytes_step * ps / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else 0.0
         flops = 2.0 * M * desc.gemm_params() * ps
+        tflops = flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS,
                     "traffic": measured_traffic(wl.name) if args.layers <= 0 else None,
                     "algorithmic_bytes_per_launch": gemm_bytes_step / max(1, gemm_n // ps), "kernel": "gemm_w16_kernel",
                     "launches_per_step": gemm_n // ps, "avg_launch_us": per_launch_ms * 1e3,
-                    "mfma_tflops": flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0,
-                    "mfma_frac": flops / (gemm_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS if gemm_ms > 0 else 0.0}
+                    "mfma_tflops": tflops, "mfma_frac": tflops / MFMA_PEAK_TFLOPS}
+        if M > MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
+            # more rows than the machine balance (flop per weight byte = M): the projections are bound by the matrix pipe
+            roofline.update({"bound": "mfma", "achieved": tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                             "frac": tflops / MFMA_PEAK_TFLOPS, "traffic": None, "kernel": "gemm_big_kernel",
+                             "algorithmic_flop_per_launch": flops / ps / max(1, gemm_n // ps),
+                             "hbm_GBps": achieved, "hbm_frac": achieved / HBM_PEAK_GBS})
         families = {k: {"ms_per_step": v[0] / ps, "launches_per_step": v[1] // ps} for k, v in prof.items()}
         families["_instrumented_ms_per_step"] = dt_prof / ps * 1e3
         # attention: KV bytes streamed per step

@@ -305,10 +305,15 @@ long mn_selector_adjustments(const mn_selector *sel); /* decisions taken so far;
  * MFMA loop sustain on the chip at hand, to read the roofline fractions against.  The caller times the
  * launches (events on `stream`).
  * mn_probe_stream_read: one pass over buf (dev, 16-byte aligned, >= 1 MiB; bytes / time = read rate).
- * mn_probe_mfma: every SIMD runs iters x 32 independent 16x16x32 fp16 MFMAs on two waves; *flop (HOST,
- * may be NULL) receives the floating-point operations of the launch. */
+ * mn_probe_mfma: every SIMD runs iters x 32 independent 16x16x32 fp16 MFMAs on two waves (1 <= iters <=
+ * 2^22, else MN_EINVAL); *flop (HOST, may be NULL) receives the floating-point operations of the launch.
+ * Every operand element is the constant 0.5: the rate of the matrix pipe at the boost clock.
+ * mn_probe_mfma_data: the same loop on operands of random sign and mantissa (magnitudes in [0.5, 1)):
+ * the rate the chip sustains once the multipliers toggle as they do on data and the power management
+ * has settled the clock; a dense product is to be read against this one. */
 mn_status mn_probe_stream_read(const void *buf, size_t bytes, void *stream);
 mn_status mn_probe_mfma(int iters, double *flop, void *stream);
+mn_status mn_probe_mfma_data(int iters, double *flop, void *stream);
 
 /* ---- component entry points (the kernels mn_verify_forward is made of, at their own shapes) -- */
 

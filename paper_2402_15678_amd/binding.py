@@ -25,7 +25,7 @@ EXPORTS = ("mn_create", "mn_destroy", "mn_last_error", "mn_status_str", "mn_work
            "mn_profile_collect", "mn_packed_weight_bytes", "mn_pack_weight", "mn_acr_update",
            "mn_verify_sample", "mn_draft_sample",
            "mn_selector_create", "mn_selector_destroy", "mn_selector_observe", "mn_selector_current",
-           "mn_selector_adjustments", "mn_probe_stream_read", "mn_probe_mfma")
+           "mn_selector_adjustments", "mn_probe_stream_read", "mn_probe_mfma", "mn_probe_mfma_data")
 PROF_KINDS = ("prepare", "norm", "gemm", "rope_append", "attention", "act", "argmax", "vote", "accept")
 
 
@@ -102,6 +102,8 @@ def _load() -> C.CDLL:
     lib.mn_probe_stream_read.argtypes = [vp, sz, vp]
     lib.mn_probe_mfma.restype = i32
     lib.mn_probe_mfma.argtypes = [i32, C.POINTER(C.c_double), vp]
+    lib.mn_probe_mfma_data.restype = i32
+    lib.mn_probe_mfma_data.argtypes = [i32, C.POINTER(C.c_double), vp]
     lib.mn_profile_enable.restype = i32
     lib.mn_profile_enable.argtypes = [vp, i32]
     lib.mn_profile_collect.restype = i32
@@ -250,4 +252,11 @@ def mn_probe_mfma(iters: int, stream=None) -> float:
     """Launches the MFMA loop; returns the floating-point operations of the launch."""
     flop = C.c_double()
     _check(lib.mn_probe_mfma(iters, C.byref(flop), stream), None)
+    return flop.value
+
+
+def mn_probe_mfma_data(iters: int, stream=None) -> float:
+    """The MFMA loop on operands of random sign and mantissa; returns the floating-point operations of the launch."""
+    flop = C.c_double()
+    _check(lib.mn_probe_mfma_data(iters, C.byref(flop), stream), None)
     return flop.value

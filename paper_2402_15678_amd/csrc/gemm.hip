@@ -301,9 +301,9 @@ __global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) ge
 // 100+ registers, and the counters showed it waiting for memory two thirds of its life.
 // Everything arrives by direct global->LDS loads (no staging registers), one barrier per k-step:
 //  * weights: a k-step is 16 column tiles x 1 KB, contiguous in the packed layout, landing as they are
-//    in a ring of four stages, three k-steps ahead;
+//    in a ring of four stages, two to three k-steps ahead;
 //  * activations: blocks of 64 k (32*AT rows x 128 bytes: whole cache lines; 64-byte row pieces cost the
-//    L2 twice the requests), double-buffered, one block (two k-steps) ahead.  A load instruction brings
+//    L2 twice the requests), double-buffered, one to two k-steps ahead.  A load instruction brings
 //    8 rows; the eight 16-byte pieces of row r are exchanged by XOR with (r/2) mod 8, which makes the
 //    operand reads (16 rows x one piece per quarter wave) as fast as contiguous ones (measured).
 // Loads complete in order, so "at most n outstanding" names exactly which have landed: the waits below
@@ -357,20 +357,43 @@ __global__ void __launch_bounds__(512, 1) gemm_big_kernel(const f16_t* __restric
   }
   const int last_stage = n_stage - 1, last_blk = (n_stage >> 1) - 1;
   // block JB of the split -> activation buffer JB % 2; k-step ST -> weight stage ST % 4 (past the end: repeats)
-#define MN_BIG_DMA_A(JB)                                                                                    \
+#define MN_BIG_DMA_A1(JB, J)                                                                                \
   {                                                                                                         \
-    const size_t off_ = (size_t)min((JB), last_blk) * (2 * KSTEP * sizeof(f16_t));                          \
-    const uint32_t base_ = lds0 + (uint32_t)((JB) & 1) * A_TILE;                                            \
-    _Pragma("unroll") for (int j = 0; j < UA; ++j)                                                          \
-      dma16<0>(a_src[j] + off_, __builtin_amdgcn_readfirstlane(base_ + (uint32_t)min(wave * UA + j, 4 * AT - 1) * 1024u)); \
+    const size_t off_ = (size_t)min((JB), last_blk) * (2 * KSTEP * sizeof(f16_t));                \
+    dma16<0>(a_src[J] + off_, __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)((JB) & 1) * A_TILE +         \
+                                                             (uint32_t)min(wave * UA + (J), 4 * AT - 1) * 1024u)); \
   }
-#define MN_BIG_DMA_W(ST)                                                                                    \
+#define MN_BIG_DMA_W1(ST, J)                                                                                \
   {                                                                                                         \
-    const int st_ = min((ST), last_stage);                                                                  \
+    const int st_ = min((ST), last_stage);                                                        \
     const size_t off_ = ((size_t)(st_ >> 2) * WBLOCK + (size_t)(st_ & 3) * 512) * sizeof(bf16_t);           \
-    const uint32_t base_ = lds0 + W_BASE + (uint32_t)((ST) & (BIG_NST - 1)) * BIG_W_BYTES + (uint32_t)(wave * UW) * 1024u; \
-    _Pragma("unroll") for (int j = 0; j < UW; ++j)                                                          \
-      dma16<0>(w_src[j] + off_, __builtin_amdgcn_readfirstlane(base_ + (uint32_t)j * 1024u));               \
+    dma16<0>(w_src[J] + off_, __builtin_amdgcn_readfirstlane(lds0 + W_BASE + (uint32_t)((ST) & (BIG_NST - 1)) * BIG_W_BYTES + \
+                                                             (uint32_t)(wave * UW + (J)) * 1024u));         \
+  }
+#define MN_BIG_DMA_A(JB) { _Pragma("unroll") for (int j = 0; j < UA; ++j) MN_BIG_DMA_A1(JB, j) }
+#define MN_BIG_DMA_W(ST) { _Pragma("unroll") for (int j = 0; j < UW; ++j) MN_BIG_DMA_W1(ST, j) }
+  // The loads go out one at a time between the MFMA groups, spread over the two k-steps of a block:
+  //   lower half of even k-step st:  pieces C0 .. C0+C1-1 of A(jb+1)
+  //   upper half of even k-step st:  the last C2 pieces of A(jb+1), then W(st+3)
+  //   lower half of odd k-step st+1: W(st+4)
+  //   upper half of odd k-step st+1: pieces 0 .. C0-1 of A(jb+2)
+  // (every target was last read before the barrier the issuing half comes after), so that the eight
+  // waves do not queue at the CU's address unit at the same moment: worth 0-3 % against one burst at
+  // the start of the k-step.
+  constexpr int C0 = (UA + 2) / 3, C1 = (UA - C0 + 1) / 2, C2 = UA - C0 - C1;
+  static_assert(C0 <= 4 && C1 <= 4 && C2 + UW <= 4, "one load per MFMA group");
+#define MN_BIG_DMA_LOW(ODD, JB, ST, G)                                                                      \
+  {                                                                                                         \
+    if (ODD) {                                                                                              \
+      if ((G) < UW) MN_BIG_DMA_W1((ST) + 4, (G) < UW ? (G) : 0)                                             \
+    } else if ((G) < C1) MN_BIG_DMA_A1((JB) + 1, (G) < C1 ? C0 + (G) : 0)                                   \
+  }
+#define MN_BIG_DMA_HIGH(ODD, JB, ST, G)                                                                     \
+  {                                                                                                         \
+    if (ODD) {                                                                                              \
+      if ((G) < C0) MN_BIG_DMA_A1((JB) + 2, (G) < C0 ? (G) : 0)                                             \
+    } else if ((G) < C2) MN_BIG_DMA_A1((JB) + 1, (G) < C2 ? C0 + C1 + (G) : 0)                              \
+    else if ((G) < C2 + UW) MN_BIG_DMA_W1((ST) + 3, ((G) >= C2 && (G) < C2 + UW) ? (G) - C2 : 0)            \
   }
 
   f32x4 acc[AT][4];
@@ -385,68 +408,78 @@ __global__ void __launch_bounds__(512, 1) gemm_big_kernel(const f16_t* __restric
     const uint32_t a_rd0 = a_row + ((uint32_t)g ^ key) * 16u;          // first k-step of a block
     const uint32_t a_rd1 = a_row + ((uint32_t)(4 + g) ^ key) * 16u;    // second
     const uint32_t w_rd = (uint32_t)W_BASE + (uint32_t)(wn * 4) * 1024u + (uint32_t)lane * 16u;
-    // One k-step.  Its weight fragments and first activation fragment are already in registers (read
-    // right after the barrier that published them, in the middle of the previous k-step), so the MFMAs
-    // start at once while the other activation fragments stream in; half way through, every LDS read of
-    // this k-step has returned, the loads of the next one are waited for, the barrier is taken and the
-    // next k-step's first operands are read: the LDS latency hides behind the second half of the MFMAs.
-    //   ABUF/HALF/WST: activation buffer, its half, weight stage of this k-step; N*: of the next one;
-    //   WAIT: loads that may still be in flight when the next k-step's data must have landed
-    f16x8 wf[4], af0;
-#define MN_BIG_READ_FIRST(ABUF, HALF, WST)                                                                  \
+    // One k-step = two halves of 2*AT MFMAs: the lower AT/2 row tiles before the barrier, the upper ones
+    // behind it.  Every operand is asked for half a k-step before its first use, into registers the
+    // previous half has just given up: the upper activation fragments at the start of the k-step (while
+    // the lower half multiplies), the next k-step's lower fragments right behind the barrier that
+    // publishes them, and its weight fragment b as soon as the upper half is through with column tile b
+    // (no copy of the weight fragments is needed to keep them alive across the barrier).
+    //   ABUF/HALF: activation buffer and its half of this k-step; N*: of the next one, NWST its weight
+    //   stage; WAIT: loads that may still be in flight when the next k-step's data must have landed
+    constexpr int H_ = AT / 2;
+    f16x8 wf[4], af[AT];
+#define MN_BIG_READ_LOW(ABUF, HALF)                                                                         \
   {                                                                                                         \
-    const unsigned char* sw_ = smem + w_rd + (WST) * BIG_W_BYTES;                                           \
-    _Pragma("unroll") for (int b = 0; b < 4; ++b) wf[b] = *reinterpret_cast<const f16x8*>(sw_ + b * 1024);  \
-    af0 = *reinterpret_cast<const f16x8*>(smem + (ABUF) * A_TILE + ((HALF) ? a_rd1 : a_rd0));               \
+    const unsigned char* sl_ = smem + (ABUF) * A_TILE + ((HALF) ? a_rd1 : a_rd0);                           \
+    _Pragma("unroll") for (int a = 0; a < H_; ++a) af[a] = *reinterpret_cast<const f16x8*>(sl_ + a * 2048); \
   }
-#define MN_BIG_STEP(ABUF, HALF, NABUF, NHALF, NWST, WAIT)                                                   \
+#define MN_BIG_READ_W(WST, B_) wf[B_] = *reinterpret_cast<const f16x8*>(smem + w_rd + (WST) * BIG_W_BYTES + (B_) * 1024);
+#define MN_BIG_STEP(ABUF, HALF, NABUF, NHALF, NWST, WAIT, ODD, JB, ST)                                                 \
   {                                                                                                         \
-    constexpr int H_ = AT / 2;                                                                              \
     const unsigned char* sa_ = smem + (ABUF) * A_TILE + ((HALF) ? a_rd1 : a_rd0);                           \
-    f16x8 af[AT];                                                                                           \
-    _Pragma("unroll") for (int a = 1; a < AT; ++a) af[a] = *reinterpret_cast<const f16x8*>(sa_ + a * 2048); \
-    _Pragma("unroll") for (int b = 0; b < 4; ++b)                                                           \
-      acc[0][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[b], af0, acc[0][b], 0, 0, 0);                   \
-    _Pragma("unroll") for (int a = 1; a < H_; ++a)                                                          \
-      _Pragma("unroll") for (int b = 0; b < 4; ++b)                                                         \
-        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[b], af[a], acc[a][b], 0, 0, 0);               \
-    f16x8 wk_[4];                                                                                           \
-    _Pragma("unroll") for (int b = 0; b < 4; ++b) wk_[b] = wf[b];                                           \
+    _Pragma("unroll") for (int a = H_; a < AT; ++a) af[a] = *reinterpret_cast<const f16x8*>(sa_ + a * 2048); \
     __builtin_amdgcn_sched_barrier(0);                                                                      \
+    _Pragma("unroll") for (int b = 0; b < 4; ++b) {                                                         \
+      _Pragma("unroll") for (int a = 0; a < H_; ++a)                                                        \
+        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[b], af[a], acc[a][b], 0, 0, 0);               \
+      __builtin_amdgcn_sched_barrier(0);                                                                    \
+      MN_BIG_DMA_LOW(ODD, JB, ST, b)                                                                        \
+      __builtin_amdgcn_sched_barrier(0);                                                                    \
+    }                                                                                                       \
     wait_vm<(WAIT)>();                                                                                      \
     __syncthreads();                                                                                        \
-    MN_BIG_READ_FIRST(NABUF, NHALF, NWST)                                                                   \
+    MN_BIG_READ_LOW(NABUF, NHALF)                                                                           \
     __builtin_amdgcn_sched_barrier(0);                                                                      \
-    _Pragma("unroll") for (int a = H_; a < AT; ++a)                                                         \
-      _Pragma("unroll") for (int b = 0; b < 4; ++b)                                                         \
-        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wk_[b], af[a], acc[a][b], 0, 0, 0);              \
+    _Pragma("unroll") for (int b = 0; b < 4; ++b) {                                                         \
+      _Pragma("unroll") for (int a = H_; a < AT; ++a)                                                       \
+        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[b], af[a], acc[a][b], 0, 0, 0);               \
+      __builtin_amdgcn_sched_barrier(0);                                                                    \
+      MN_BIG_READ_W(NWST, b)                                                                                \
+      MN_BIG_DMA_HIGH(ODD, JB, ST, b)                                                                       \
+      __builtin_amdgcn_sched_barrier(0);                                                                    \
+    }                                                                                                       \
   }
-    // issue order (per wave): A(0) W(0) W(1) W(2) | even k-step st: A(st/2+1) W(st+3) | odd: W(st+3) | ...
+    // issue order (per wave): A(0) W(0) W(1) W(2) A(1)[0..C0) | k-step 0: A(1)[C0..C0+C1) . A(1)[C0+C1..UA) W(3) |
+    // k-step 1: W(4) . A(2)[0..C0) | ...
     MN_BIG_DMA_A(0)
     MN_BIG_DMA_W(0)
     MN_BIG_DMA_W(1)
     MN_BIG_DMA_W(2)
-    wait_vm<2 * UW>();  // A(0), W(0) landed; W(1), W(2) may be in flight
+#pragma unroll
+    for (int j = 0; j < C0; ++j) MN_BIG_DMA_A1(1, j)
+    wait_vm<2 * UW + C0>();  // A(0), W(0) landed
     __syncthreads();
-    MN_BIG_READ_FIRST(0, 0, 0)
+    MN_BIG_READ_LOW(0, 0)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) MN_BIG_READ_W(0, b)
     for (int st = 0; st < n_stage; st += 2) {
       const int jb = st >> 1;
-      // even k-step: the other activation buffer was last read before the previous barrier
-      MN_BIG_DMA_A(jb + 1)
-      MN_BIG_DMA_W(st + 3)
-      // W(st+1) must have landed; W(st+2), A(jb+1), W(st+3) may be in flight
-      MN_BIG_STEP(jb & 1, 0, jb & 1, 1, (st + 1) & 3, UA + 2 * UW)
-      // odd k-step
-      MN_BIG_DMA_W(st + 4)
-      // W(st+2) and A(jb+1) must have landed; W(st+3), W(st+4) may be in flight
-      MN_BIG_STEP(jb & 1, 1, (jb + 1) & 1, 0, (st + 2) & 3, 2 * UW)
+      // even k-step: W(st+1) must have landed; W(st+2) and the first C0+C1 pieces of A(jb+1) may be in flight
+      MN_BIG_STEP(jb & 1, 0, jb & 1, 1, (st + 1) & 3, UW + C0 + C1, 0, jb, st)
+      // odd k-step: W(st+2) and A(jb+1) must have landed; W(st+3), W(st+4) may be in flight
+      MN_BIG_STEP(jb & 1, 1, (jb + 1) & 1, 0, (st + 2) & 3, 2 * UW, 1, jb, st)
     }
     wait_vm<0>();  // the repeats past the end must land before the LDS is given back
 #undef MN_BIG_STEP
-#undef MN_BIG_READ_FIRST
+#undef MN_BIG_READ_W
+#undef MN_BIG_READ_LOW
   }
+#undef MN_BIG_DMA_LOW
+#undef MN_BIG_DMA_HIGH
 #undef MN_BIG_DMA_A
 #undef MN_BIG_DMA_W
+#undef MN_BIG_DMA_A1
+#undef MN_BIG_DMA_W1
 
   // epilogue: lane holds D[n = 16*(wn*4 + b) + 4g + i][m = 16*(wm*AT + a) + l16] of the workgroup tile
   const int n_wg = bx * 256;

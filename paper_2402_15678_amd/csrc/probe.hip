@@ -17,17 +17,33 @@ __global__ void __launch_bounds__(256) probe_stream_kernel(const u32x4* __restri
   if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u && sink) *sink = acc[0];  // (keeps the loads alive)
 }
 
-// eight independent accumulator chains of the 16x16x32 fp16 MFMA per wave, two waves per SIMD
+// eight independent accumulator chains of the 16x16x32 fp16 MFMA per wave, two waves per SIMD.
+// DATA = false: every operand element is the same small constant (few bits toggle: the loop holds the
+// boost clock); DATA = true: four A and four B fragments of random sign and mantissa, magnitudes in
+// [0.5, 1), so the multipliers see what a real product feeds them (the power management then settles at
+// a lower clock: this is the rate a dense product can hope for on this chip).
+template <bool DATA>
 __global__ void __launch_bounds__(512, 1) probe_mfma_kernel(int iters, float* sink) {
   f32x4 acc[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  const float s = 1.f + (float)(threadIdx.x & 7) * 0.125f;
-  const f16x8 a = {(f16_t)s, (f16_t)s, (f16_t)s, (f16_t)s, (f16_t)s, (f16_t)s, (f16_t)s, (f16_t)s};
-  const f16x8 b = {(f16_t)0.5f, (f16_t)0.5f, (f16_t)0.5f, (f16_t)0.5f, (f16_t)0.5f, (f16_t)0.5f, (f16_t)0.5f, (f16_t)0.5f};
+  f16x8 a[4], b[4];
+  uint32_t h = (uint32_t)threadIdx.x * 2654435761u + 12345u;
+#pragma unroll
+  for (int f = 0; f < 8; ++f) {
+    u32x4 bits;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      h = h * 1664525u + 1013904223u;
+      // two halves per word: sign and mantissa from the generator, exponent of 0.5 (or the constant 0.5)
+      bits[e] = DATA ? (((h >> 8) & 0x83ff83ffu) | 0x38003800u) : 0x38003800u;
+    }
+    if (f < 4) a[f] = __builtin_bit_cast(f16x8, bits);
+    else b[f - 4] = __builtin_bit_cast(f16x8, bits);
+  }
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int i = 0; i < 32; ++i) acc[i & 7] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc[i & 7], 0, 0, 0);
+    for (int i = 0; i < 32; ++i) acc[i & 7] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[i & 3], b[(i >> 2) & 3], acc[i & 7], 0, 0, 0);
   }
   float t = 0.f;
 #pragma unroll
@@ -44,12 +60,17 @@ extern "C" mn_status mn_probe_stream_read(const void* buf, size_t bytes, void* s
   return hipGetLastError() == hipSuccess ? MN_OK : MN_EHIP;
 }
 
-extern "C" mn_status mn_probe_mfma(int iters, double* flop, void* stream) {
+static mn_status probe_mfma(bool data, int iters, double* flop, void* stream) {
   if (iters < 1 || iters > (1 << 22)) return MN_EINVAL;
   int dev = 0, cus = 0;
   if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
     return MN_EHIP;
-  mn::probe_mfma_kernel<<<cus, 512, 0, (hipStream_t)stream>>>(iters, nullptr);
+  if (data) mn::probe_mfma_kernel<true><<<cus, 512, 0, (hipStream_t)stream>>>(iters, nullptr);
+  else mn::probe_mfma_kernel<false><<<cus, 512, 0, (hipStream_t)stream>>>(iters, nullptr);
   if (flop) *flop = (double)iters * 32.0 * (2.0 * 16 * 16 * 32) * 8.0 * (double)cus;  // 8 waves per workgroup, one per CU
   return hipGetLastError() == hipSuccess ? MN_OK : MN_EHIP;
 }
+
+extern "C" mn_status mn_probe_mfma(int iters, double* flop, void* stream) { return probe_mfma(false, iters, flop, stream); }
+
+extern "C" mn_status mn_probe_mfma_data(int iters, double* flop, void* stream) { return probe_mfma(true, iters, flop, stream); }

@@ -119,6 +119,8 @@ def test_step_calls_reject_bad_arguments_before_launch(binding):
     for iters in (0, -3, 1 << 23):
         with pytest.raises(binding.MinionsError):
             binding.mn_probe_mfma(iters)
+        with pytest.raises(binding.MinionsError):
+            binding.mn_probe_mfma_data(iters)
     binding.mn_destroy(ctx)
 
 

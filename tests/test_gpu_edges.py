@@ -235,7 +235,7 @@ def test_few_row_attention_path_disables_only_the_bad_sequence():
 
 
 def test_measuring_sticks_run_and_report_plausible_rates(env):
-    """The two probes behind the ABI: they launch, finish, and land in the range of a working MI355X
+    """The probes behind the ABI: they launch, finish, and land in the range of a working MI355X
     (loose bounds: they are a ruler for the bench, not a performance test)."""
     harness, binding = env[0], env[1]
     buf = torch.empty((1 << 28,), dtype=torch.uint8, device="cuda:0").fill_(1)
@@ -255,6 +255,13 @@ def test_measuring_sticks_run_and_report_plausible_rates(env):
     torch.cuda.synchronize()
     tflops = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
     assert 300.0 < tflops < 2600.0, tflops
+    binding.mn_probe_mfma_data(100, harness.stream_ptr())
+    e0.record()
+    flop = binding.mn_probe_mfma_data(4000, harness.stream_ptr())
+    e1.record()
+    torch.cuda.synchronize()
+    on_data = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    assert 300.0 < on_data < 2600.0, on_data
 
 
 def test_largest_batch_many_rows(env):
