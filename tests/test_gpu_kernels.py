@@ -23,15 +23,30 @@ def _dev(a, dt=torch.int32):
 @pytest.mark.parametrize("B,n,k_max,V,mode", [(1, 3, 4, 4096, 0), (16, 4, 8, 5, 0), (64, 5, 16, 3, 0), (64, 5, 16, 3, 1),
                                               (257, 7, 3, 2, 0), (5, 64, 6, 4, 0), (3, 1, 9, 10, 1), (4, 2, 0, 10, 0)])
 def test_vote_bit_exact(hb, B, n, k_max, V, mode):
-    harness, binding = hb
     g = synth.stream(77, B, n, k_max, mode)
+    w = (g.random(n) + 0.25).astype(np.float32)
+    if B % 2 == 0:
+        w = np.ones(n, np.float32)                                    # unit weights: plenty of exact ties
+    _check_vote(hb, g, B, n, k_max, V, mode, w)
+
+
+def test_vote_random_shapes_bit_exact(hb):
+    """Forty drawn shapes (batch, drafts, length, alphabet, mode) with weights from a small set of exactly
+    representable values, so that weighted ties between branches are common."""
+    g = synth.stream(177)
+    for _ in range(40):
+        B, n, k_max = int(g.integers(1, 81)), int(g.integers(1, 9)), int(g.integers(0, 17))
+        V, mode = int(g.integers(2, 7)), int(g.integers(0, 2))
+        w = g.choice(np.asarray([0.5, 1.0, 1.5, 2.0], np.float32), size=n)
+        _check_vote(hb, g, B, n, k_max, V, mode, w)
+
+
+def _check_vote(hb, g, B, n, k_max, V, mode, w):
+    harness, binding = hb
     drafts = g.integers(0, V, size=(B, n, max(1, k_max))).astype(np.int32)[:, :, :k_max]
     drafts = np.ascontiguousarray(drafts)
     spec = g.integers(0, k_max + 1, size=B).astype(np.int32)
     spec[0] = k_max
-    w = (g.random(n) + 0.25).astype(np.float32)
-    if B % 2 == 0:
-        w = np.ones(n, np.float32)                                    # unit weights: plenty of exact ties
     want_v, want_s = orc.vote_batch(drafts.reshape(B, n, k_max), spec, w, mode)
     voted = torch.full((B, max(1, k_max)), -9, dtype=torch.int32, device="cuda:0")
     ssm = torch.full((B,), -9, dtype=torch.int32, device="cuda:0")
