@@ -207,6 +207,25 @@ def test_llama70b_width_full_ragged_batch(hb):
     print("llama70b-width full ragged batch max |dlogit| = %.2e, decisive %d/%d" % (err, dec, wl.batch))
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3, 4, 5, 6])
+def test_small_models_drawn_batches(hb, seed):
+    """Small models of every kind the library runs (Llama-style bf16 with grouped-query heads of 128 and of 64, OPT-style
+    bf16 and fp32), each on a drawn batch: 1-12 sequences, contexts 0-300 (0: prefill), 0-12 speculated tokens."""
+    g = synth.stream(4242, seed)
+    descs = [synth.ModelDesc(synth.ARCH_LLAMA, synth.DT_BF16, 2, 1024, 8, 2, 128, 2048, 1000, 4096),
+             synth.ModelDesc(synth.ARCH_LLAMA, synth.DT_BF16, 2, 512, 8, 4, 64, 1024, 777, 4096),
+             synth.ModelDesc(synth.ARCH_OPT, synth.DT_BF16, 2, 512, 4, 4, 128, 2048, 1000, 2048),
+             synth.OPT_TINY]
+    desc = descs[seed % len(descs)]
+    B = int(g.integers(1, 13))
+    ctx = g.integers(0, 301, size=B)
+    ks = g.integers(0, 13, size=B)
+    ks[int(g.integers(0, B))] = 12
+    wl = synth.Workload("drawn-%d" % seed, desc, B, 0, 300, 0, 12, 3, 0.3, seed=9000 + seed)
+    err, dec = _reduced_case(hb, wl, desc.n_layers, B, 2, ctx_override=ctx.tolist(), k_override=ks.tolist(), min_decisive=0)
+    print("drawn batch %d: B=%d max |dlogit| = %.2e, decisive %d/%d" % (seed, B, err, dec, B))
+
+
 def test_llama160m_width_few_rows(hb):
     # the drafting models' shape (head_dim 64, bf16 storage) with 1 to 4 scored positions per sequence: the
     # few-row attention kernel with this step's own keys coming from the side buffers; 2 of 12 layers
