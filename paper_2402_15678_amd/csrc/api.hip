@@ -376,6 +376,7 @@ static void run_prepare(mn_ctx* c, const Ws& w, const int32_t* last_tok, const i
     return v > 0 ? v : 320;
   }();
   p.attn_wgs = attn_wgs;
+  p.attn_min_tiles = attention_min_tiles();
   p.rope_cos = w.at<float>(w.L.rope_cos); p.rope_sin = w.at<float>(w.L.rope_sin);
   p.dev_status = dev_status;
   Tap t(&c->prof, MN_PROF_PREPARE, st);

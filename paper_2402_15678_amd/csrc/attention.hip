@@ -767,13 +767,22 @@ __global__ void __launch_bounds__(1024) attn_plan_kernel(RowInfo rows, int B, in
 // Largest number of KV splits any sequence of the batch may get (it sizes the partials and bounds the work list;
 // every sequence then takes what its own length asks for, see seq_splits): one per 16 key tiles of the longest
 // context.
+int attention_min_tiles() {
+  static int v = [] {
+    const char* e = getenv("MN_ATTN_MIN_TILES");  // experiment switch
+    const int x = e ? atoi(e) : 0;
+    return x > 0 ? x : 16;
+  }();
+  return v;
+}
+
 static int pick_splits(int max_ctx) {
   static int forced = [] {
     const char* e = getenv("MN_ATTN_SPLITS");  // experiment switch
     return e ? atoi(e) : 0;
   }();
   const int tiles = (max_ctx + KT - 1) / KT;
-  int s = forced > 0 ? forced : tiles / 16;
+  int s = forced > 0 ? forced : tiles / attention_min_tiles();
   if (s > 16) s = 16;
   if (s < 1) s = 1;
   return s;

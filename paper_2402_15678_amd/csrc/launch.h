@@ -35,6 +35,7 @@ struct PrepArgs {
   int kv_heads;                // KV heads of the model (the attention grid has one workgroup row per KV head)
   int q_per_kv;                // query heads per KV head (a workgroup covers 128 rows of query position x head)
   int attn_wgs;                // number of attention workgroups to aim for
+  int attn_min_tiles;          // fewest key tiles a workgroup should take
   float *rope_cos, *rope_sin;  // [M][rope_half]
   int32_t* dev_status;
 };
@@ -117,6 +118,7 @@ struct AttnArgs {
 };
 size_t attention_scratch_bytes(int M, int H, int hd, int max_ctx, int dtype);
 bool attention_mfma_supported(int H, int Hkv, int hd, int block_size, int dtype);
+int attention_min_tiles();  // fewest key tiles an attention workgroup should take (16; experiment switch MN_ATTN_MIN_TILES)
 size_t attention_items_capacity(int B, int M, int H, int Hkv);
 // once per step, after the row bookkeeping and before the first launch_attention: the list of workgroups
 void launch_attention_plan(const AttnArgs& a, hipStream_t st);

@@ -109,7 +109,7 @@ __global__ void __launch_bounds__(256) prepare_kernel(PrepArgs a) {
   if (tid == 0 && a.attn_tps) {
     const unsigned long long w = (unsigned long long)max(a.attn_wgs, 1);
     const unsigned long long per = (s_tiles * (unsigned long long)max(a.kv_heads, 1) + w - 1) / w;
-    a.attn_tps[0] = (int)min(max(per, 16ull), (unsigned long long)(1 << 20));
+    a.attn_tps[0] = (int)min(max(per, (unsigned long long)max(a.attn_min_tiles, 1)), (unsigned long long)(1 << 20));
   }
 }
 
