@@ -166,8 +166,26 @@ def test_proj_gemm_matches_fp64(hb, M, N, K, split):
     ("hd64-many-rows-generic", synth.LLAMA_160M.with_layers(1), [100, 40], [7, 4]),
 ])
 def test_attention_matches_oracle(hb, name, desc, ctx_lens, spec_lens):
+    _check_attention(hb, desc, ctx_lens, spec_lens)
+
+
+@pytest.mark.parametrize("seed", list(range(10)))
+def test_attention_drawn_batches(hb, seed):
+    """Drawn batches for the MFMA kernel and its work list: 1-24 sequences, contexts 0-2500 (a few of them long, so
+    that sequences of one batch get different numbers of KV splits), 0-16 speculated tokens (one or two row groups
+    with grouped-query heads), grouped-query and plain multi-head shapes."""
+    g = synth.stream(9191, seed)
+    desc = (synth.LLAMA2_70B if seed % 3 else synth.OPT_13B).with_layers(1)
+    B = int(g.integers(1, 25))
+    ctx = g.integers(0, 400, size=B)
+    longs = g.random(B) < 0.3
+    ctx[longs] = g.integers(400, 2501, size=int(longs.sum()))
+    ks = g.integers(0, 17, size=B)
+    _check_attention(hb, desc, ctx.tolist(), ks.tolist())
+
+
+def _check_attention(hb, desc, ctx_lens, spec_lens):
     harness, binding = hb
-    import ctypes as C
     B = len(ctx_lens)
     total = [int(c) + int(k) + 1 for c, k in zip(ctx_lens, spec_lens)]
     kvh = synth.make_paged_kv(desc, total, [-1] * B, 91, scatter=True)          # blocks for exactly `total` tokens
