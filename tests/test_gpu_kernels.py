@@ -85,9 +85,17 @@ def test_vote_paper_example_and_bad_spec_len(hb):
 # ---------------------------------------------------------------------------- accept + commit
 @pytest.mark.parametrize("B,k_max", [(1, 4), (16, 8), (64, 16), (300, 5), (7, 0)])
 def test_accept_commit_bit_exact(hb, B, k_max):
+    _check_accept(hb, synth.stream(78, B, k_max), B, k_max)
+
+
+def test_accept_commit_drawn_shapes_bit_exact(hb):
+    g = synth.stream(178)
+    for _ in range(30):
+        _check_accept(hb, g, int(g.integers(1, 130)), int(g.integers(0, 17)))
+
+
+def _check_accept(hb, g, B, k_max):
     harness, binding = hb
-    import ctypes as C
-    g = synth.stream(78, B, k_max)
     spec = g.integers(0, k_max + 1, size=B).astype(np.int32)
     spec[0] = k_max
     greedy = g.integers(0, 50, size=(B, k_max + 1)).astype(np.int32)
