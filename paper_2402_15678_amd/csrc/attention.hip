@@ -764,9 +764,8 @@ __global__ void __launch_bounds__(1024) attn_plan_kernel(RowInfo rows, int B, in
     reinterpret_cast<int4*>(items)[2 * (size_t)i] = make_int4(-1, 0, 0, 1);
 }
 
-// Largest number of KV splits any sequence of the batch may get (it sizes the partials and bounds the work list;
-// every sequence then takes what its own length asks for, see seq_splits): one per 16 key tiles of the longest
-// context.
+// Fewest key tiles a workgroup should take: below that the lead-in of a workgroup and the fp32 partial it
+// writes cost more than the parallelism wins (measured at 33 tiles per sequence: 2 splits beat 1, 4 and 8).
 int attention_min_tiles() {
   static int v = [] {
     const char* e = getenv("MN_ATTN_MIN_TILES");  // experiment switch
@@ -776,6 +775,9 @@ int attention_min_tiles() {
   return v;
 }
 
+// Largest number of KV splits any sequence of the batch may get (it sizes the partials and bounds the work list;
+// every sequence then takes what its own length asks for, see seq_splits): one per attention_min_tiles() key
+// tiles of the longest context, 16 at most.
 static int pick_splits(int max_ctx) {
   static int forced = [] {
     const char* e = getenv("MN_ATTN_SPLITS");  // experiment switch
