@@ -57,3 +57,17 @@ def test_nothing_committed_reads_the_reference_or_the_scratch_folder():
         text = open(path).read()
         assert "/root/reference" not in text, path
         assert "_work/" not in text and "_work\"" not in text, path
+
+
+def test_profiles_are_short_text_summaries_with_their_command():
+    prof = os.path.join(ROOT, "profiles")
+    names = sorted(os.listdir(prof))
+    assert names, "no profile summaries"
+    for n in names:
+        path = os.path.join(prof, n)
+        assert n.endswith((".txt", ".md")), n
+        assert "round" not in n.lower(), n                      # named for kernel and workload, not for a build round
+        assert os.path.getsize(path) < 64 * 1024, n
+        text = open(path).read()
+        assert "rocprofv3" in text and "bench.py" in text, n   # the full command, which runs committed files only
+        assert "_work" not in text and "gpurun" not in text, n
