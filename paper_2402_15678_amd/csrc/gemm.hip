@@ -183,8 +183,8 @@ __global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) ge
     __builtin_amdgcn_s_barrier();
 
 #ifndef MN_SCHED_MODE
-#define MN_SCHED_MODE 1  // scheduling fence 0: after every row-tile group; 1: after every k-step (1 % faster in the step
-                         // than 0 at 40 and at 144 rows); 2: none
+#define MN_SCHED_MODE 1  // scheduling fence 0: after every row-tile group; 1: after every k-step; 2: none (the three
+                         // are within run-to-run noise of each other in the step, 0.3 %)
 #endif
 // One iteration on ring slot RING, reading tile CUR and bringing the next tile into NXT.  Issue order
 // matters because loads complete in order: the tile loads go first (L2 hits, needed at the end of this
