@@ -58,7 +58,12 @@ enum {
   MN_DEV_BLOCK_TABLE = 1, /* block table does not cover ctx_b + k_b + 1 tokens, or a block id is out of range */
   MN_DEV_SPEC_LEN = 2,    /* device spec_len differs from the host copy / exceeds k_max / is negative */
   MN_DEV_TOKEN = 4,       /* an input token id or position is outside the vocabulary / position table */
-  MN_DEV_DRAFTS = 8       /* mv_vote: spec_len outside [0, k_max] */
+  MN_DEV_DRAFTS = 8,      /* mv_vote: spec_len outside [0, k_max] */
+  MN_DEV_RANGE = 16,      /* bf16 models: a weight (mn_pack_weight) or an activation handed from one kernel to the next
+                             lay outside the fp16 range +-65504 (or was not a number) and was saturated to the nearest
+                             finite value.  Nothing is disabled: no infinity or NaN is produced, the call completes, but
+                             the affected rows no longer follow the arithmetic stated at mn_verify_forward */
+  MN_DEV_CTX = 32         /* ctx_b + k_b + 1 exceeds the max_ctx the host passed (the sequence is a no-op) */
 };
 
 /* Limits (checked; MN_EINVAL / MN_EUNSUPPORTED beyond them). */
@@ -139,8 +144,10 @@ size_t mn_workspace_bytes(const mn_ctx *ctx, int B, int max_rows, int max_ctx);
  * weights pre-tiled: blocks of 128 output columns x 128 inputs, 32 KB each, consecutive along k for
  * one column block, every 1 KB inside in the order the MFMA lanes consume it, every value re-encoded
  * from bf16 to the fp16 the MFMA multiplies (still two bytes; exact for magnitudes in [2^-14, 65504],
- * smaller ones truncated to the fp16 subnormal grid, an absolute error below 2^-24).  Columns are
- * padded with zeros to a multiple of 128.  The packed form is private to this library version. */
+ * smaller ones truncated to the fp16 subnormal grid, an absolute error below 2^-24; larger ones, which
+ * trained or initialised weights do not hold, are saturated to +-65280, the largest bf16 value fp16 can
+ * hold, and reported).  Columns are padded with zeros to a multiple of 128.  The packed form is private to
+ * this library version. */
 
 /* Bytes of the packed form of an [N][K] bf16 matrix (K a multiple of 128).  0 on invalid arguments. */
 size_t mn_packed_weight_bytes(int N, int K);
@@ -149,8 +156,10 @@ size_t mn_packed_weight_bytes(int N, int K);
  * aligned, not overlapping src).  interleave_half = 0 keeps the row order.  interleave_half = F > 0
  * (N must be 2F, F a multiple of 16) is for the gate||up matrix of a SwiGLU FFN: packed column tile
  * 2t holds gate rows [16t, 16t+16) and tile 2t+1 up rows F + [16t, 16t+16), which lets the
- * projection kernel apply silu(gate) * up in its epilogue. */
-mn_status mn_pack_weight(const void *src, void *dst, int N, int K, int interleave_half, void *stream);
+ * projection kernel apply silu(gate) * up in its epilogue.
+ * dev_status (dev [1] int32, flags OR-ed in, or NULL): MN_DEV_RANGE when a weight was saturated. */
+mn_status mn_pack_weight(const void *src, void *dst, int N, int K, int interleave_half, int32_t *dev_status,
+                         void *stream);
 
 /* ---- the verification step --------------------------------------------------------------- */
 
@@ -189,7 +198,13 @@ mn_status mn_mv_vote(mn_ctx *ctx, const int32_t *drafts, const int32_t *spec_len
  * the matrix products (norm outputs, queries, softmax
  * probabilities, attention outputs, FFN activations) are rounded to fp16 (round-to-nearest-even)
  * and the products run on the fp16 MFMA with fp32 accumulation.  New K/V rows are rounded to
- * bf16 when they are written to the cache. */
+ * bf16 when they are written to the cache.
+ * Range of the fp16 stages: every such activation (and every K/V row written to the cache) is saturated to
+ * +-65504 instead of overflowing to infinity, and MN_DEV_RANGE is set in *dev_status when that happens
+ * (with N(0, 0.02)-initialised or trained weights these values stay below 10^2).  Cache entries the caller
+ * supplies must lie within +-65504 as well.
+ * max_ctx is checked on the device against ctx_lens: a sequence with ctx_b + k_b + 1 > max_ctx sets MN_DEV_CTX
+ * and becomes a no-op (the attention launch was sized for max_ctx keys). */
 mn_status mn_verify_forward(mn_ctx *ctx, const int32_t *last_tok, const int32_t *voted, const int32_t *spec_len,
                             const int32_t *h_spec_len, int B, int k_max, int max_ctx, const mn_kv *kv,
                             int32_t *greedy, float *logits, void *workspace, size_t workspace_bytes,

@@ -45,8 +45,9 @@ Pins: tests/test_oracle_*.py (worked example of the paper's figure "majority", b
 force over an explicit token tree, a PyTorch-CPU fp64 model assembled from library
 routines, closed forms for the norms and the rotary embedding, cached vs cache-less,
 multi-position vs sequential single-position, losslessness vs plain greedy decoding; for the stochastic
-rule: the generator's published known answers, the emitted-token distribution against the LLM's, the
-greedy limit, the rejection probability; for the quality metric and the selector: hand-computed cases and
+rule: the generator's published known answers, the temperature softmax against distributions it must
+return unchanged (scores T log p), the emitted-token distribution against the LLM's, the greedy limit,
+the rejection probability; for the quality metric and the selector: hand-computed cases and
 a library least-squares fit).  No function here is unpinned.
 """
 from __future__ import annotations

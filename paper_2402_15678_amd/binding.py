@@ -17,7 +17,7 @@ MN_OK, MN_EINVAL, MN_ENULL, MN_ESHAPE, MN_EUNSUPPORTED, MN_ECAPACITY, MN_EWORKSP
 MN_ARCH_OPT, MN_ARCH_LLAMA = 0, 1
 MN_DT_F32, MN_DT_BF16 = 0, 1
 MN_VOTE_TREE, MN_VOTE_COLUMN = 0, 1
-MN_DEV_BLOCK_TABLE, MN_DEV_SPEC_LEN, MN_DEV_TOKEN, MN_DEV_DRAFTS = 1, 2, 4, 8
+MN_DEV_BLOCK_TABLE, MN_DEV_SPEC_LEN, MN_DEV_TOKEN, MN_DEV_DRAFTS, MN_DEV_RANGE, MN_DEV_CTX = 1, 2, 4, 8, 16, 32
 MN_MAX_DRAFTS, MN_MAX_BATCH, MN_MAX_SPLIT_K = 64, 4096, 16
 
 EXPORTS = ("mn_create", "mn_destroy", "mn_last_error", "mn_status_str", "mn_workspace_bytes", "mn_mv_vote",
@@ -79,7 +79,7 @@ def _load() -> C.CDLL:
     lib.mn_packed_weight_bytes.restype = sz
     lib.mn_packed_weight_bytes.argtypes = [i32, i32]
     lib.mn_pack_weight.restype = i32
-    lib.mn_pack_weight.argtypes = [vp, vp, i32, i32, i32, vp]
+    lib.mn_pack_weight.argtypes = [vp, vp, i32, i32, i32, vp, vp]
     lib.mn_verify_sample.restype = i32
     lib.mn_verify_sample.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, C.c_double, C.c_uint64, C.c_uint64,
                                      vp, vp, vp]
@@ -195,8 +195,8 @@ def mn_packed_weight_bytes(N: int, K: int) -> int:
     return int(lib.mn_packed_weight_bytes(N, K))
 
 
-def mn_pack_weight(src, dst, N, K, interleave_half=0, stream=None) -> None:
-    _check(lib.mn_pack_weight(src, dst, N, K, interleave_half, stream), None)
+def mn_pack_weight(src, dst, N, K, interleave_half=0, dev_status=None, stream=None) -> None:
+    _check(lib.mn_pack_weight(src, dst, N, K, interleave_half, dev_status, stream), None)
 
 
 def mn_verify_sample(ctx, logits, voted, draft_probs, spec_len, greedy, B, k_max, M, vocab, temperature, seed, step,

@@ -173,16 +173,23 @@ static Layout make_layout(const mn_model_desc& d, int B, int M, int max_ctx) {
   L.vnew = take(Mr * d.n_kv_heads * d.head_dim * es);
   L.attn = take(Mr * d.n_heads * d.head_dim * es);
   L.act = take(Mr * d.d_ffn * es);
-  // partial sums of the widest projection at the largest split it can get
+  // Partial sums of the widest projection at the largest split it can get with M rows OR FEWER: a workspace
+  // sized for max_rows must serve every step with at most that many rows, and the k-split a projection gets is
+  // not monotone in the row count (it drops where the kernel family changes and where a further row block
+  // starts).  The split is constant between those borders, all of which are multiples of 16, so the largest
+  // need is found at the right ends: M itself and every multiple of 16 below it.
   const int nqkv = (d.n_heads + 2 * d.n_kv_heads) * d.head_dim;
   const int w1r = d.d_ffn * (d.arch == MN_ARCH_LLAMA ? 2 : 1);
   size_t pmax = 0;
   const int Ns[5] = {nqkv, d.d_model, w1r, d.d_model, d.vocab};
   const int Ks[5] = {d.d_model, d.n_heads * d.head_dim, d.d_model, d.d_ffn, d.d_model};
   for (int i = 0; i < 5; ++i) {
-    const size_t s = (size_t)gemm_pick_split(M, Ns[i], Ks[i], d.dtype);
-    const size_t b = s * Mr * Ns[i] * 4;
-    if (b > pmax) pmax = b;
+    for (int m2 = (int)Mr;; m2 = (m2 - 1) / 16 * 16) {
+      const size_t s = (size_t)gemm_pick_split(m2, Ns[i], Ks[i], d.dtype);
+      const size_t b = s * (size_t)m2 * Ns[i] * 4;
+      if (b > pmax) pmax = b;
+      if (m2 <= 16 || (size_t)MN_MAX_SPLIT_K * m2 * Ns[i] * 4 <= pmax) break;  // fewer rows cannot need more
+    }
   }
   L.partials_bytes = pmax;
   L.partials = take(pmax);
@@ -348,7 +355,8 @@ static RowInfo row_info(const Ws& w) {
 }
 
 static void run_prepare(mn_ctx* c, const Ws& w, const int32_t* last_tok, const int32_t* voted, const int32_t* spec_len,
-                        int B, int k_max, int M, const mn_kv* kv, bool tokens, int32_t* dev_status, hipStream_t st) {
+                        int B, int k_max, int M, int max_ctx, const mn_kv* kv, bool tokens, int32_t* dev_status,
+                        hipStream_t st) {
   PrepArgs p{};
   p.last_tok = tokens ? last_tok : nullptr;
   p.voted = voted;
@@ -358,6 +366,7 @@ static void run_prepare(mn_ctx* c, const Ws& w, const int32_t* last_tok, const i
   p.B = B; p.k_max = k_max; p.M = M;
   p.vocab = tokens ? c->d.vocab : 0;
   p.max_pos = c->d.max_pos;
+  p.max_ctx = max_ctx;
   p.block_size = kv->block_size; p.num_blocks = kv->num_blocks; p.max_blocks_per_seq = kv->max_blocks_per_seq;
   p.rope_half = (tokens && c->d.arch == MN_ARCH_LLAMA) ? c->d.head_dim / 2 : 0;
   p.rope_base = c->d.rope_base;
@@ -367,15 +376,7 @@ static void run_prepare(mn_ctx* c, const Ws& w, const int32_t* last_tok, const i
   p.attn_tps = w.at<int32_t>(w.L.attn_tps);
   p.kv_heads = c->d.n_kv_heads;
   p.q_per_kv = c->d.n_heads / c->d.n_kv_heads;
-  // 1.25 workgroups per CU: measured flat between 1 and 1.3 per CU, slower beyond (every further split of a
-  // sequence writes and re-reads one more fp32 partial of its rows, and workgroups beyond the 512 that are
-  // resident at once start when the first ones end)
-  static const int attn_wgs = [] {
-    const char* e = getenv("MN_ATTN_WGS");  // experiment switch
-    const int v = e ? atoi(e) : 0;
-    return v > 0 ? v : 320;
-  }();
-  p.attn_wgs = attn_wgs;
+  p.attn_wgs = attention_target_workgroups();
   p.attn_min_tiles = attention_min_tiles();
   p.rope_cos = w.at<float>(w.L.rope_cos); p.rope_sin = w.at<float>(w.L.rope_sin);
   p.dev_status = dev_status;
@@ -410,7 +411,7 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
     if (!kv->k_layers[l] || !kv->v_layers[l]) return fail(c, MN_ENULL, "%s: kv layer %d pointer is NULL", who, l);
 
   hipStream_t st = (hipStream_t)stream;
-  run_prepare(c, w, last_tok, voted, spec_len, B, k_max, M, kv, true, dev_status, st);
+  run_prepare(c, w, last_tok, voted, spec_len, B, k_max, M, max_ctx, kv, true, dev_status, st);
   const RowInfo rows = row_info(w);
   const bool llama = d.arch == MN_ARCH_LLAMA;
   const int nqkv = (d.n_heads + 2 * d.n_kv_heads) * d.head_dim;
@@ -425,6 +426,8 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
   int pend_n = 0;
   const float* pend_bias = nullptr;
 
+  hipError_t lerr = hipSuccess;  // first refusal of a launcher (a kernel attribute the runtime would not set)
+  auto keep = [&](hipError_t e) { if (e != hipSuccess && lerr == hipSuccess) lerr = e; };
   auto norm = [&](const float* gain, const float* shift, bool embed) {
     NormArgs n{};
     n.x = x; n.partials = pend; n.n_partials = pend_n; n.bias = pend_bias;
@@ -432,6 +435,7 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
     n.pos_emb = embed ? c->pos_emb : nullptr;
     n.row_tok = rows.row_tok; n.row_pos = rows.row_pos;
     n.gain = gain; n.shift = shift; n.eps = d.norm_eps; n.h = h; n.M = M; n.d = d.d_model; n.dtype = d.dtype;
+    n.dev_status = dev_status;
     Tap t(&c->prof, MN_PROF_NORM, st);
     launch_norm(n, st);
     pend = nullptr; pend_n = 0; pend_bias = nullptr;
@@ -439,8 +443,9 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
   auto gemm = [&](const void* a, const void* wt, float* out, int N, int K, int split) {
     GemmArgs g{};
     g.a = a; g.w = wt; g.out = out; g.bias = nullptr; g.M = M; g.N = N; g.K = K; g.split_k = split; g.dtype = d.dtype;
+    g.dev_status = dev_status;
     Tap t(&c->prof, MN_PROF_GEMM, st);
-    launch_gemm(g, st);
+    keep(launch_gemm(g, st));
   };
 
   for (int l = 0; l < d.n_layers; ++l) {
@@ -458,6 +463,7 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
     r.knew = d.dtype == MN_DT_BF16 ? w.at<void>(w.L.knew) : nullptr;
     r.vnew = d.dtype == MN_DT_BF16 ? w.at<void>(w.L.vnew) : nullptr;
     r.M = M; r.H = d.n_heads; r.Hkv = d.n_kv_heads; r.hd = d.head_dim; r.dtype = d.dtype;
+    r.dev_status = dev_status;
     {
       Tap t(&c->prof, MN_PROF_ROPE_APPEND, st);
       launch_rope_append(r, st);
@@ -476,7 +482,7 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
     }
     {
       Tap t(&c->prof, MN_PROF_ATTENTION, st);
-      launch_attention(at, st);
+      keep(launch_attention(at, st));
     }
     s = gemm_pick_split(M, d.d_model, hdim, d.dtype);
     gemm(at.out, c->wo[l], part, d.d_model, hdim, s);
@@ -487,21 +493,22 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
       // gate||up projection with silu(gate) * up applied in the kernel's epilogue
       GemmArgs g{};
       g.a = h; g.w = c->w1[l]; g.swiglu_act = act; g.M = M; g.N = w1r; g.K = d.d_model; g.split_k = 1; g.dtype = d.dtype;
+      g.dev_status = dev_status;
       Tap t(&c->prof, MN_PROF_GEMM, st);
-      launch_gemm(g, st);
+      keep(launch_gemm(g, st));
     } else if (!llama && d.dtype == MN_DT_BF16 && gemm_pick_split(M, w1r, d.d_model, d.dtype) == 1) {
       // one split: bias + ReLU applied in the kernel's epilogue, no partial sums and no activation kernel
       GemmArgs g{};
       g.a = h; g.w = c->w1[l]; g.relu_act = act; g.bias = (const float*)c->b1[l]; g.M = M; g.N = w1r; g.K = d.d_model;
-      g.split_k = 1; g.dtype = d.dtype;
+      g.split_k = 1; g.dtype = d.dtype; g.dev_status = dev_status;
       Tap t(&c->prof, MN_PROF_GEMM, st);
-      launch_gemm(g, st);
+      keep(launch_gemm(g, st));
     } else {
       s = gemm_pick_split(M, w1r, d.d_model, d.dtype);
       gemm(h, c->w1[l], part, w1r, d.d_model, s);
       ActArgs ac{};
       ac.partials = part; ac.n_partials = s; ac.bias = (const float*)c->b1[l]; ac.act = act;
-      ac.M = M; ac.F = d.d_ffn; ac.swiglu = llama ? 1 : 0; ac.dtype = d.dtype;
+      ac.M = M; ac.F = d.d_ffn; ac.swiglu = llama ? 1 : 0; ac.dtype = d.dtype; ac.dev_status = dev_status;
       Tap t(&c->prof, MN_PROF_ACT, st);
       launch_act(ac, st);
     }
@@ -525,6 +532,7 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
     Tap t(&c->prof, MN_PROF_ARGMAX, st);
     launch_argmax_rows(lg, M, d.vocab, rows, k_max, greedy, B, st);
   }
+  if (lerr != hipSuccess) return fail(c, MN_EHIP, "%s: kernel attribute: %s", who, hipGetErrorString(lerr));
   return hip_check(c, who);
 }
 
@@ -534,13 +542,14 @@ extern "C" size_t mn_packed_weight_bytes(int N, int K) {
   return packed_weight_elems(N, K) * 2;
 }
 
-extern "C" mn_status mn_pack_weight(const void* src, void* dst, int N, int K, int interleave_half, void* stream) {
+extern "C" mn_status mn_pack_weight(const void* src, void* dst, int N, int K, int interleave_half, int32_t* dev_status,
+                                    void* stream) {
   if (N < 1 || K < 128 || K % 128) return fail(nullptr, MN_ESHAPE, "mn_pack_weight: N=%d K=%d (K must be a positive multiple of 128)", N, K);
   if (interleave_half < 0 || (interleave_half > 0 && (N != 2 * interleave_half || interleave_half % 16)))
     return fail(nullptr, MN_ESHAPE, "mn_pack_weight: interleave_half=%d needs N == 2*half and half %% 16 == 0", interleave_half);
   if (!src || !dst) return fail(nullptr, MN_ENULL, "mn_pack_weight: src/dst is NULL");
   if ((uintptr_t)dst & 255) return fail(nullptr, MN_EINVAL, "mn_pack_weight: dst not 256-byte aligned");
-  launch_pack_weight(src, dst, N, K, interleave_half, (hipStream_t)stream);
+  launch_pack_weight(src, dst, N, K, interleave_half, dev_status, (hipStream_t)stream);
   return hip_check(nullptr, "mn_pack_weight");
 }
 
@@ -558,18 +567,20 @@ extern "C" mn_status mn_proj_gemm(mn_ctx* c, const void* a, const void* w, const
   GemmArgs g{};
   g.a = a; g.w = w; g.bias = bias; g.M = M; g.N = N; g.K = K; g.split_k = s; g.dtype = MN_DT_BF16;
   Tap t(c ? &c->prof : nullptr, MN_PROF_GEMM, st);
+  hipError_t lerr = hipSuccess;
   if (s == 1) {
     g.out = out;
-    launch_gemm(g, st);
+    lerr = launch_gemm(g, st);
   } else {
     const size_t need = (size_t)s * M * N * 4;
     if (!workspace) return fail(c, MN_ENULL, "%s: workspace is NULL (split_k = %d)", who, s);
     if ((uintptr_t)workspace & 255) return fail(c, MN_EWORKSPACE, "%s: workspace not 256-byte aligned", who);
     if (workspace_bytes < need) return fail(c, MN_EWORKSPACE, "%s: workspace %zu bytes, need %zu", who, workspace_bytes, need);
     g.out = reinterpret_cast<float*>(workspace);
-    launch_gemm(g, st);
-    launch_reduce_partials(g.out, s, (size_t)M * N, out, (size_t)M * N, st);
+    lerr = launch_gemm(g, st);
+    if (lerr == hipSuccess) launch_reduce_partials(g.out, s, (size_t)M * N, out, (size_t)M * N, st);
   }
+  if (lerr != hipSuccess) return fail(c, MN_EHIP, "%s: kernel attribute: %s", who, hipGetErrorString(lerr));
   return hip_check(c, who);
 }
 
@@ -597,7 +608,7 @@ extern "C" mn_status mn_attention(mn_ctx* c, const void* q, const int32_t* spec_
   if (workspace_bytes < w.L.total) return fail(c, MN_EWORKSPACE, "%s: workspace %zu bytes, need %zu", who, workspace_bytes, w.L.total);
   hipStream_t st = (hipStream_t)stream;
   // row bookkeeping only (no tokens): positions are ctx_b + j, the rows' K/V are already cached
-  run_prepare(c, w, nullptr, nullptr, spec_len, B, k_max, M, kv, false, dev_status, st);
+  run_prepare(c, w, nullptr, nullptr, spec_len, B, k_max, M, max_ctx, kv, false, dev_status, st);
   AttnArgs at{};
   at.q = q; at.out = out; at.rows = row_info(w);
   at.kv = KvView{kv->k_layers[layer], kv->v_layers[layer], kv->block_tables, kv->block_size, kv->num_blocks, kv->max_blocks_per_seq};
@@ -607,10 +618,12 @@ extern "C" mn_status mn_attention(mn_ctx* c, const void* q, const int32_t* spec_
   at.items = w.at<int32_t>(w.L.attn_items); at.items_capacity = w.L.attn_items_capacity;
   at.row_splits = w.at<int32_t>(w.L.attn_row_splits);
   launch_attention_plan(at, st);
+  hipError_t lerr = hipSuccess;
   {
     Tap t(&c->prof, MN_PROF_ATTENTION, st);
-    launch_attention(at, st);
+    lerr = launch_attention(at, st);
   }
+  if (lerr != hipSuccess) return fail(c, MN_EHIP, "%s: kernel attribute: %s", who, hipGetErrorString(lerr));
   return hip_check(c, who);
 }
 

@@ -15,9 +15,10 @@
 //  * attn_generic_kernel  any storage type / head_dim / block size; plain FMA, one (row, head)
 //    per workgroup.  Used by the fp32 model and as the fallback.
 #include "launch.h"
+#include "tune.h"
 #include "../../include/minions_verify.h"
 
-#include <cstdlib>
+#include <mutex>
 
 namespace mn {
 
@@ -767,22 +768,23 @@ __global__ void __launch_bounds__(1024) attn_plan_kernel(RowInfo rows, int B, in
 // Fewest key tiles a workgroup should take: below that the lead-in of a workgroup and the fp32 partial it
 // writes cost more than the parallelism wins (measured at 33 tiles per sequence: 2 splits beat 1, 4 and 8).
 int attention_min_tiles() {
-  static int v = [] {
-    const char* e = getenv("MN_ATTN_MIN_TILES");  // experiment switch
-    const int x = e ? atoi(e) : 0;
-    return x > 0 ? x : 16;
-  }();
-  return v;
+  const int x = MN_TUNE("MN_ATTN_MIN_TILES", 16);
+  return x > 0 ? x : 16;
+}
+
+// 1.25 workgroups with work per CU: measured flat between 1 and 1.3 per CU, slower beyond (every further split of
+// a sequence writes and re-reads one more fp32 partial of its rows, and workgroups beyond the 512 that are
+// resident at once start when the first ones end)
+int attention_target_workgroups() {
+  const int x = MN_TUNE("MN_ATTN_WGS", 320);
+  return x > 0 ? x : 320;
 }
 
 // Largest number of KV splits any sequence of the batch may get (it sizes the partials and bounds the work list;
 // every sequence then takes what its own length asks for, see seq_splits): one per attention_min_tiles() key
 // tiles of the longest context, 16 at most.
 static int pick_splits(int max_ctx) {
-  static int forced = [] {
-    const char* e = getenv("MN_ATTN_SPLITS");  // experiment switch
-    return e ? atoi(e) : 0;
-  }();
+  const int forced = MN_TUNE("MN_ATTN_SPLITS", 0);
   const int tiles = (max_ctx + KT - 1) / KT;
   int s = forced > 0 ? forced : tiles / attention_min_tiles();
   if (s > 16) s = 16;
@@ -791,10 +793,7 @@ static int pick_splits(int max_ctx) {
 }
 
 bool attention_mfma_supported(int H, int Hkv, int hd, int block_size, int dtype) {
-  static int off = [] {
-    const char* e = getenv("MN_ATTN_GENERIC");
-    return e ? atoi(e) : 0;
-  }();
+  const int off = MN_TUNE("MN_ATTN_GENERIC", 0);
   return !off && dtype == MN_DT_BF16 && hd == HD && block_size == BS && Hkv > 0 && H % Hkv == 0;
 }
 
@@ -845,8 +844,8 @@ void launch_attention_plan(const AttnArgs& a, hipStream_t st) {
                                        a.row_splits);
 }
 
-void launch_attention(const AttnArgs& a, hipStream_t st) {
-  if (a.M <= 0 || a.B <= 0) return;
+hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
+  if (a.M <= 0 || a.B <= 0) return hipSuccess;
   const int G = a.Hkv > 0 ? a.H / a.Hkv : 1;
   if (mfma_path(a)) {
     const MfmaShape sh = mfma_shape(a);
@@ -855,13 +854,17 @@ void launch_attention(const AttnArgs& a, hipStream_t st) {
     float* ml_part = a.scratch + (size_t)n_splits * a.M * a.H * HD;
     const int tiles_per_split = ((a.max_ctx + KT - 1) / KT + n_splits - 1) / n_splits + 1;
     const size_t smem = mfma_smem_bytes(tiles_per_split);
-    static bool attr_set = false;
-    if (!attr_set) {
-      const int most = 160 * 1024;
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, most);
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, most);
-      attr_set = true;
-    }
+    // once per process, whichever thread comes first; a refusal is returned by every call and nothing is launched
+    static std::once_flag attr_once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(attr_once, [] {
+      const void* fns[2] = {reinterpret_cast<const void*>(attn_mfma_kernel<1>), reinterpret_cast<const void*>(attn_mfma_kernel<2>)};
+      for (const void* f : fns) {
+        const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) attr_err = e;
+      }
+    });
+    if (attr_err != hipSuccess) return attr_err;
     const unsigned grid = (unsigned)a.Hkv * (unsigned)sh.grid_items;
     if (sh.ctw == 1) attn_mfma_kernel<1><<<grid, 256, smem, st>>>(a, o_part, ml_part);
     else attn_mfma_kernel<2><<<grid, 256, smem, st>>>(a, o_part, ml_part);
@@ -869,24 +872,21 @@ void launch_attention(const AttnArgs& a, hipStream_t st) {
       const int waves = a.M * a.H;
       attn_merge_kernel<<<(waves + 3) / 4, 256, 0, st>>>(o_part, ml_part, n_splits, a.M, a.H, a.row_splits, reinterpret_cast<f16_t*>(a.out));
     }
-    return;
+    return hipSuccess;
   }
-  static const int generic_only = [] {
-    const char* e = getenv("MN_ATTN_GENERIC");
-    return e ? atoi(e) : 0;
-  }();
-  if (!generic_only && fewrow_supported(a, G)) {
+  if (!MN_TUNE("MN_ATTN_GENERIC", 0) && fewrow_supported(a, G)) {
     const dim3 fg(a.Hkv, a.B);
     const int rr = G * a.max_q;
     // a single row leaves registers for 16 waves (one step of 64 keys each at 1024 keys of context)
     if (rr <= 1) attn_fewrow_kernel<1, 16><<<fg, 1024, 0, st>>>(a);
     else if (rr <= 2) attn_fewrow_kernel<2, 8><<<fg, 512, 0, st>>>(a);
     else attn_fewrow_kernel<4, 8><<<fg, 512, 0, st>>>(a);
-    return;
+    return hipSuccess;
   }
   dim3 grid(a.H, a.M);
   if (a.dtype == MN_DT_BF16) attn_generic_kernel<f16_t, bf16_t><<<grid, GEN_THREADS, 0, st>>>(a);
   else attn_generic_kernel<float, float><<<grid, GEN_THREADS, 0, st>>>(a);
+  return hipSuccess;
 }
 
 }  // namespace mn

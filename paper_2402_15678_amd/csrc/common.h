@@ -37,6 +37,16 @@ __device__ __forceinline__ uint32_t pack2h(float lo, float hi) {
   const f32x2 v = {lo, hi};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
 }
+// The fp16 range guard.  Activations handed from one kernel to the next are fp16 (see the precision note), so
+// a value beyond +-65504 would turn into an infinity and poison its row without a trace.  Every conversion
+// of a computed activation therefore saturates (NaN becomes -65504) and reports: `bad` is set when the value
+// was not within the range, and the kernel ORs MN_DEV_RANGE into the call's status word once at its end.
+constexpr float F16_MAX = 65504.f;
+__device__ __forceinline__ float sat_h(float v, bool& bad) {
+  bad |= !(__builtin_fabsf(v) <= F16_MAX);
+  return __builtin_fminf(__builtin_fmaxf(v, -F16_MAX), F16_MAX);
+}
+__device__ __forceinline__ uint32_t pack2h_sat(float lo, float hi, bool& bad) { return pack2h(sat_h(lo, bad), sat_h(hi, bad)); }
 // 8 bf16 (16 bytes) -> 8 fp16, exact for magnitudes in [2^-14, 65504]
 __device__ __forceinline__ f16x8 bf16x8_to_f16x8(u32x4 u) {
   union { f16x8 v; uint32_t w[4]; } r;

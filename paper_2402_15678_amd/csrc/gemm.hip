@@ -20,9 +20,10 @@
 // error under 2^-24, larger ones do not occur in weights), so the main loop spends no vector
 // instruction on the weight stream: the widening used to take more issue slots than the MFMAs.
 #include "launch.h"
+#include "tune.h"
 #include "../../include/minions_verify.h"
 
-#include <cstdlib>
+#include <mutex>
 #include <type_traits>
 
 namespace mn {
@@ -64,7 +65,7 @@ template <int MT, int NTW, int EPI, int NW, int RD>
 __global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) gemm_w16_kernel(const f16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                            void* __restrict__ out_, const float* __restrict__ bias,
                                                            int M, int N, int K, int k_per_split, int m_chunks, int gx,
-                                                           int n_split) {
+                                                           int n_split, int32_t* __restrict__ status) {
   // two activation-tile buffers as separate objects: the compiler then knows that a DMA into one
   // does not touch the reads of the other
   __shared__ __attribute__((aligned(1024))) f16_t s_a0[16 * MT * LDS_ROW];
@@ -182,10 +183,6 @@ __global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) ge
     MN_WAIT_VM(0);
     __builtin_amdgcn_s_barrier();
 
-#ifndef MN_SCHED_MODE
-#define MN_SCHED_MODE 1  // scheduling fence 0: after every row-tile group; 1: after every k-step; 2: none (the three
-                         // are within run-to-run noise of each other in the step, 0.3 %)
-#endif
 // One iteration on ring slot RING, reading tile CUR and bringing the next tile into NXT.  Issue order
 // matters because loads complete in order: the tile loads go first (L2 hits, needed at the end of this
 // iteration), then, k-step by k-step, the NTW*KS = 8 weight refills for iteration it+2 (HBM, needed two
@@ -218,7 +215,8 @@ __global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) ge
           _Pragma("unroll") for (int i = 0; i < G0; ++i)                                                    \
             if (i < cnt_)                                                                                   \
               acc[nt][lo_ + i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wcur_[nt], bfrag_[i], acc[nt][lo_ + i], 0, 0, 0); \
-        if (MN_SCHED_MODE == 0 || (MN_SCHED_MODE == 1 && grp == 1)) __builtin_amdgcn_sched_barrier(0);      \
+        /* scheduling fence after every k-step (after every row-tile group, or none, is the same within noise) */ \
+        if (grp == 1) __builtin_amdgcn_sched_barrier(0);                                                    \
       }                                                                                                     \
     }                                                                                                       \
     MN_WAIT_VM(NTW * KS);                                                                                   \
@@ -241,6 +239,7 @@ __global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) ge
 #undef MN_WAIT_VM
 
   // epilogue: lane holds D[n = base + 4g + i][m = mt*16 + l16]
+  bool bad = false;  // an fp16 activation left the fp16 range (saturated; reported once below)
   if constexpr (EPI == EPI_SWIGLU) {
     static_assert(NTW % 2 == 0, "gate and up tiles alternate inside a wave");
     f16_t* act = reinterpret_cast<f16_t*>(out_);
@@ -256,7 +255,7 @@ __global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) ge
         float r[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) r[i] = gt[i] / (1.f + __expf(-gt[i])) * up[i];
-        *reinterpret_cast<uint2*>(act + (size_t)m * F + f) = make_uint2(pack2h(r[0], r[1]), pack2h(r[2], r[3]));
+        *reinterpret_cast<uint2*>(act + (size_t)m * F + f) = make_uint2(pack2h_sat(r[0], r[1], bad), pack2h_sat(r[2], r[3], bad));
       }
     }
   } else if constexpr (EPI == EPI_RELU) {
@@ -274,11 +273,11 @@ __global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) ge
         for (int i = 0; i < 4; ++i) r[i] = fmaxf(v[i] + ((bias && n + i < N) ? bias[n + i] : 0.f), 0.f);
         f16_t* p = act + (size_t)m * N + n;
         if (n + 3 < N && (N & 3) == 0) {
-          *reinterpret_cast<uint2*>(p) = make_uint2(pack2h(r[0], r[1]), pack2h(r[2], r[3]));
+          *reinterpret_cast<uint2*>(p) = make_uint2(pack2h_sat(r[0], r[1], bad), pack2h_sat(r[2], r[3], bad));
         } else {
 #pragma unroll
           for (int i = 0; i < 4; ++i)
-            if (n + i < N) p[i] = (f16_t)r[i];
+            if (n + i < N) p[i] = (f16_t)sat_h(r[i], bad);
         }
       }
     }
@@ -308,6 +307,7 @@ __global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) ge
       }
     }
   }
+  if (EPI != EPI_PARTIAL && bad && status) atomicOr(status, MN_DEV_RANGE);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -336,7 +336,7 @@ template <int AT, int EPI>
 __global__ void __launch_bounds__(512, 1) gemm_big_kernel(const f16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                           void* __restrict__ out_, const float* __restrict__ bias, int M,
                                                           int N, int K, int k_per_split, int m_chunks, int gx,
-                                                          int n_split) {
+                                                          int n_split, int32_t* __restrict__ status) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   constexpr int A_TILE = 32 * AT * 128;                  // one 64-k block of activations
   constexpr int W_BASE = 2 * A_TILE;
@@ -517,6 +517,7 @@ __global__ void __launch_bounds__(512, 1) gemm_big_kernel(const f16_t* __restric
 #undef MN_BIG_DMA_W1
 
   // epilogue: lane holds D[n = 16*(wn*4 + b) + 4g + i][m = 16*(wm*AT + a) + l16] of the workgroup tile
+  bool bad = false;  // an fp16 activation left the fp16 range (saturated; reported once below)
   const int n_wg = bx * 256;
   if constexpr (EPI == EPI_SWIGLU) {
     f16_t* act = reinterpret_cast<f16_t*>(out_);
@@ -532,7 +533,7 @@ __global__ void __launch_bounds__(512, 1) gemm_big_kernel(const f16_t* __restric
         float r[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) r[i] = gt[i] / (1.f + __expf(-gt[i])) * up[i];
-        *reinterpret_cast<uint2*>(act + (size_t)m * F + f) = make_uint2(pack2h(r[0], r[1]), pack2h(r[2], r[3]));
+        *reinterpret_cast<uint2*>(act + (size_t)m * F + f) = make_uint2(pack2h_sat(r[0], r[1], bad), pack2h_sat(r[2], r[3], bad));
       }
     }
   } else if constexpr (EPI == EPI_RELU) {
@@ -550,11 +551,11 @@ __global__ void __launch_bounds__(512, 1) gemm_big_kernel(const f16_t* __restric
         for (int i = 0; i < 4; ++i) r[i] = fmaxf(v[i] + ((bias && n + i < N) ? bias[n + i] : 0.f), 0.f);
         f16_t* p = act + (size_t)m * N + n;
         if (n + 3 < N && (N & 3) == 0) {
-          *reinterpret_cast<uint2*>(p) = make_uint2(pack2h(r[0], r[1]), pack2h(r[2], r[3]));
+          *reinterpret_cast<uint2*>(p) = make_uint2(pack2h_sat(r[0], r[1], bad), pack2h_sat(r[2], r[3], bad));
         } else {
 #pragma unroll
           for (int i = 0; i < 4; ++i)
-            if (n + i < N) p[i] = (f16_t)r[i];
+            if (n + i < N) p[i] = (f16_t)sat_h(r[i], bad);
         }
       }
     }
@@ -584,13 +585,15 @@ __global__ void __launch_bounds__(512, 1) gemm_big_kernel(const f16_t* __restric
       }
     }
   }
+  if (EPI != EPI_PARTIAL && bad && status) atomicOr(status, MN_DEV_RANGE);
 }
 
 // Row-major [N][K] bf16 -> the packed layout described at the top.  One thread per 16-byte piece.
 // With half > 0 (Llama gate||up, N = 2*half) packed column tile 2t holds gate rows [16t, 16t+16)
 // and tile 2t+1 the up rows half + [16t, 16t+16).
 __global__ void __launch_bounds__(256) pack_weight_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst, int N,
-                                                          int K, int half) {
+                                                          int K, int half, int32_t* __restrict__ status) {
+  bool bad = false;
   const size_t pieces = (size_t)((N + NWG - 1) / NWG) * (K / KB) * (WBLOCK / 8);
   for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < pieces; idx += (size_t)gridDim.x * blockDim.x) {
     const size_t blk = idx / (WBLOCK / 8);
@@ -611,19 +614,30 @@ __global__ void __launch_bounds__(256) pack_weight_kernel(const bf16_t* __restri
     }
     // re-encode once, here, instead of in every pass over the matrix: the same conversion the kernels
     // apply to bf16 data in registers (exact for magnitudes in [2^-14, 65504], below that truncated to
-    // the fp16 subnormal grid, an absolute error under 2^-24)
-    const f16x8 h = bf16x8_to_f16x8(v);
+    // the fp16 subnormal grid, an absolute error under 2^-24).  A weight beyond the fp16 range (or not a
+    // number) is saturated and reported: bf16 patterns with magnitude bits above those of 65504 (0x477F)
+    const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
+    uint32_t c4[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint32_t lo = w4[i] & 0xFFFFu, hi = w4[i] >> 16;
+      if ((lo & 0x7FFFu) > 0x477Fu) { bad = true; lo = (lo & 0x8000u) | 0x477Fu; }
+      if ((hi & 0x7FFFu) > 0x477Fu) { bad = true; hi = (hi & 0x8000u) | 0x477Fu; }
+      c4[i] = lo | (hi << 16);
+    }
+    const f16x8 h = bf16x8_to_f16x8(make_uint4(c4[0], c4[1], c4[2], c4[3]));
     *reinterpret_cast<f16x8*>(dst + idx * 8) = h;
   }
+  if (bad && status) atomicOr(status, MN_DEV_RANGE);
 }
 
 size_t packed_weight_elems(int N, int K) { return (size_t)((N + NWG - 1) / NWG) * NWG * (size_t)K; }
 
-void launch_pack_weight(const void* src, void* dst, int N, int K, int half, hipStream_t st) {
+void launch_pack_weight(const void* src, void* dst, int N, int K, int half, int32_t* status, hipStream_t st) {
   const size_t pieces = packed_weight_elems(N, K) / 8;
   size_t blocks = (pieces + 255) / 256;
   if (blocks > 65536) blocks = 65536;
-  pack_weight_kernel<<<(int)blocks, 256, 0, st>>>(reinterpret_cast<const bf16_t*>(src), reinterpret_cast<bf16_t*>(dst), N, K, half);
+  pack_weight_kernel<<<(int)blocks, 256, 0, st>>>(reinterpret_cast<const bf16_t*>(src), reinterpret_cast<bf16_t*>(dst), N, K, half, status);
 }
 
 // fp32 model (the small configuration): one wave per output column, lanes split k, up to 8 rows
@@ -674,38 +688,21 @@ struct GemmTune {
   int split;    // 0 = automatic
   int target;   // workgroups to aim for
 };
-static GemmTune tune() {
-  static GemmTune t = [] {
-    GemmTune x{0, 512};
-    if (const char* e = getenv("MN_GEMM_SPLIT")) x.split = atoi(e);
-    if (const char* e = getenv("MN_GEMM_TARGET_WGS")) x.target = atoi(e);
-    return x;
-  }();
-  return t;
-}
+static GemmTune tune() { return GemmTune{MN_TUNE("MN_GEMM_SPLIT", 0), MN_TUNE("MN_GEMM_TARGET_WGS", 512)}; }
 
-static int big_min_m() {  // experiment switch: rows from which the big-tile kernel takes over (0: above 144)
-  static int v = [] {
-    const char* e = getenv("MN_GEMM_BIG_MIN_M");
-    return e ? atoi(e) : 0;
-  }();
-  return v;
-}
+// rows from which the big-tile kernel takes over (0: above 144)
+static int big_min_m() { return MN_TUNE("MN_GEMM_BIG_MIN_M", 0); }
 
 // Shape of the grid for one projection: waves per workgroup (each wave owns 32 columns; all waves of a
 // workgroup share the activation tile, so more waves mean less L2 -> LDS traffic per weight byte) and
 // k-splits.  Goal: every CU streams (a CU's share of the HBM rate is bounded by what its waves keep in
 // flight), the whole grid is resident at once, and every split runs at least 16 iterations (measured:
 // shorter splits lose more to ramp-up and partial sums than the extra workgroups win).
-// Experiment switches: MN_GEMM_NW forces the wave count, MN_GEMM_SPLIT the splits.
 struct GemmPlan {
   int nw, split;
 };
 static GemmPlan gemm_plan(int M, int N, int K, int forced_split) {
-  static int forced_nw = [] {
-    const char* e = getenv("MN_GEMM_NW");
-    return e ? atoi(e) : 0;
-  }();
+  const int forced_nw = MN_TUNE("MN_GEMM_NW", 0);
   const int slices = ((N + NWG - 1) / NWG) * 4;  // 32-column wave slices of the padded matrix
   const int iters = K / KB;
   if (forced_split < 1 && tune().split >= 1) forced_split = tune().split;
@@ -781,11 +778,11 @@ static void launch_bf16_mt(const GemmArgs& a, int m_chunks, hipStream_t st) {
   const f16_t* A = reinterpret_cast<const f16_t*>(a.a);
   const bf16_t* W = reinterpret_cast<const bf16_t*>(a.w);
   if (a.swiglu_act)
-    gemm_w16_kernel<MT, NTW, EPI_SWIGLU, NW, RD><<<grid, NW * 64, 0, st>>>(A, W, a.swiglu_act, nullptr, a.M, a.N, a.K, per * KB, m_chunks, gx, a.split_k);
+    gemm_w16_kernel<MT, NTW, EPI_SWIGLU, NW, RD><<<grid, NW * 64, 0, st>>>(A, W, a.swiglu_act, nullptr, a.M, a.N, a.K, per * KB, m_chunks, gx, a.split_k, a.dev_status);
   else if (a.relu_act)
-    gemm_w16_kernel<MT, NTW, EPI_RELU, NW, RD><<<grid, NW * 64, 0, st>>>(A, W, a.relu_act, a.bias, a.M, a.N, a.K, per * KB, m_chunks, gx, a.split_k);
+    gemm_w16_kernel<MT, NTW, EPI_RELU, NW, RD><<<grid, NW * 64, 0, st>>>(A, W, a.relu_act, a.bias, a.M, a.N, a.K, per * KB, m_chunks, gx, a.split_k, a.dev_status);
   else
-    gemm_w16_kernel<MT, NTW, EPI_PARTIAL, NW, RD><<<grid, NW * 64, 0, st>>>(A, W, a.out, a.bias, a.M, a.N, a.K, per * KB, m_chunks, gx, a.split_k);
+    gemm_w16_kernel<MT, NTW, EPI_PARTIAL, NW, RD><<<grid, NW * 64, 0, st>>>(A, W, a.out, a.bias, a.M, a.N, a.K, per * KB, m_chunks, gx, a.split_k, a.dev_status);
 }
 
 // rows per workgroup of the big-tile kernel: the AT (row tiles per wave, two waves deep) that pads M least
@@ -803,7 +800,7 @@ static int big_at(int M) {
 }
 
 template <int AT>
-static void launch_big(const GemmArgs& a, hipStream_t st) {
+static hipError_t launch_big(const GemmArgs& a, hipStream_t st) {
   const int iters = a.K / KB;
   const int per = (iters + a.split_k - 1) / a.split_k;  // 128-k blocks per split
   const int gx = ((a.N + NWG - 1) / NWG + 1) / 2;       // 256-column groups
@@ -815,28 +812,36 @@ static void launch_big(const GemmArgs& a, hipStream_t st) {
   const size_t smem = (size_t)2 * 32 * AT * 128 + (size_t)BIG_NST * BIG_W_BYTES;
   const f16_t* A = reinterpret_cast<const f16_t*>(a.a);
   const bf16_t* W = reinterpret_cast<const bf16_t*>(a.w);
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_big_kernel<AT, EPI_PARTIAL>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_big_kernel<AT, EPI_SWIGLU>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_big_kernel<AT, EPI_RELU>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    attr_set = true;
-  }
+  // once per process and instantiation, whichever thread comes first; a refusal is returned by every call
+  // and nothing is launched
+  static std::once_flag attr_once;
+  static hipError_t attr_err = hipSuccess;
+  std::call_once(attr_once, [] {
+    const void* fns[3] = {reinterpret_cast<const void*>(gemm_big_kernel<AT, EPI_PARTIAL>),
+                          reinterpret_cast<const void*>(gemm_big_kernel<AT, EPI_SWIGLU>),
+                          reinterpret_cast<const void*>(gemm_big_kernel<AT, EPI_RELU>)};
+    for (const void* f : fns) {
+      const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      if (e != hipSuccess) attr_err = e;
+    }
+  });
+  if (attr_err != hipSuccess) return attr_err;
   if (a.swiglu_act)
-    gemm_big_kernel<AT, EPI_SWIGLU><<<grid, 512, smem, st>>>(A, W, a.swiglu_act, nullptr, a.M, a.N, a.K, per * KB, rb, gx, a.split_k);
+    gemm_big_kernel<AT, EPI_SWIGLU><<<grid, 512, smem, st>>>(A, W, a.swiglu_act, nullptr, a.M, a.N, a.K, per * KB, rb, gx, a.split_k, a.dev_status);
   else if (a.relu_act)
-    gemm_big_kernel<AT, EPI_RELU><<<grid, 512, smem, st>>>(A, W, a.relu_act, a.bias, a.M, a.N, a.K, per * KB, rb, gx, a.split_k);
+    gemm_big_kernel<AT, EPI_RELU><<<grid, 512, smem, st>>>(A, W, a.relu_act, a.bias, a.M, a.N, a.K, per * KB, rb, gx, a.split_k, a.dev_status);
   else
-    gemm_big_kernel<AT, EPI_PARTIAL><<<grid, 512, smem, st>>>(A, W, a.out, a.bias, a.M, a.N, a.K, per * KB, rb, gx, a.split_k);
+    gemm_big_kernel<AT, EPI_PARTIAL><<<grid, 512, smem, st>>>(A, W, a.out, a.bias, a.M, a.N, a.K, per * KB, rb, gx, a.split_k, a.dev_status);
+  return hipSuccess;
 }
 
-void launch_gemm(const GemmArgs& a, hipStream_t st) {
-  if (a.M <= 0 || a.N <= 0) return;
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t st) {
+  if (a.M <= 0 || a.N <= 0) return hipSuccess;
   if (a.dtype != MN_DT_BF16) {
     dim3 grid((a.N + 3) / 4, (a.M + 7) / 8);
     gemm_f32_kernel<<<grid, 256, 0, st>>>(reinterpret_cast<const float*>(a.a), reinterpret_cast<const float*>(a.w),
                                           a.out, a.bias, a.M, a.N, a.K);
-    return;
+    return hipSuccess;
   }
   const int tiles = (a.M + 15) / 16;
   // row tiles per workgroup: everything in one chunk up to 9 tiles (144 rows), else chunks of 8
@@ -855,21 +860,18 @@ void launch_gemm(const GemmArgs& a, hipStream_t st) {
     }
   }
   else {
-    static int big = [] {
-      const char* e = getenv("MN_GEMM_BIG");  // experiment switch: 0 = chunks of the streaming kernel
-      return e ? atoi(e) : 1;
-    }();
-    if (!big) {
+    if (!MN_TUNE("MN_GEMM_BIG", 1)) {  // 0 = chunks of the streaming kernel
       launch_bf16_mt<8, 4>(a, (tiles + 7) / 8, st);
     } else {
       switch (big_at(a.M)) {
-        case 5: launch_big<5>(a, st); break;
-        case 10: launch_big<10>(a, st); break;
-        case 8: launch_big<8>(a, st); break;
-        default: launch_big<6>(a, st); break;
+        case 5: return launch_big<5>(a, st);
+        case 10: return launch_big<10>(a, st);
+        case 8: return launch_big<8>(a, st);
+        default: return launch_big<6>(a, st);
       }
     }
   }
+  return hipSuccess;
 }
 
 }  // namespace mn

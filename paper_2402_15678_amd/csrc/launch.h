@@ -28,6 +28,7 @@ int verify_sample_max_vocab();
 struct PrepArgs {
   const int32_t *last_tok, *voted, *spec_len, *ctx_lens, *block_tables;
   int B, k_max, M, vocab, max_pos, block_size, num_blocks, max_blocks_per_seq;
+  int max_ctx;       // the host's bound on ctx_b + k_b + 1 (it sized the attention launch)
   int rope_half;     // head_dim/2 for rotary models, 0 otherwise
   float rope_base;
   int32_t *row_seq, *row_j, *row_pos, *row_tok, *seq_row0, *seq_ctx, *seq_ok;
@@ -54,6 +55,7 @@ struct NormArgs {
   float eps;
   void* h;                // [M][d] normalised output in the activation type
   int M, d, dtype;
+  int32_t* dev_status;    // MN_DEV_RANGE is OR-ed in when an fp16 output saturates, or null
 };
 void launch_norm(const NormArgs& a, hipStream_t st);
 
@@ -67,6 +69,7 @@ struct RopeAppendArgs {
   void* q;  // [M][H][hd] activation type
   void *knew, *vnew;  // [M][Hkv][hd] activation type: this step's K/V rows before the cache rounding, or null
   int M, H, Hkv, hd, dtype;
+  int32_t* dev_status;  // MN_DEV_RANGE is OR-ed in when an fp16 output saturates, or null
 };
 void launch_rope_append(const RopeAppendArgs& a, hipStream_t st);
 
@@ -77,6 +80,7 @@ struct ActArgs {
   const float* bias;
   void* act;  // [M][F] activation type
   int M, F, swiglu, dtype;
+  int32_t* dev_status;  // MN_DEV_RANGE is OR-ed in when an fp16 output saturates, or null
 };
 void launch_act(const ActArgs& a, hipStream_t st);
 
@@ -92,11 +96,13 @@ struct GemmArgs {
   void* relu_act;    // non-null: fused bias + ReLU epilogue, fp16 [M][N] (bf16 models, split_k == 1)
   const float* bias;
   int M, N, K, split_k, dtype;
+  int32_t* dev_status;  // MN_DEV_RANGE is OR-ed in when a fused fp16 epilogue saturates a value, or null
 };
 int gemm_pick_split(int M, int N, int K, int dtype);
 size_t packed_weight_elems(int N, int K);
-void launch_pack_weight(const void* src, void* dst, int N, int K, int half, hipStream_t st);
-void launch_gemm(const GemmArgs& a, hipStream_t st);
+void launch_pack_weight(const void* src, void* dst, int N, int K, int half, int32_t* status, hipStream_t st);
+// hipSuccess, or the error of a one-time kernel attribute setting that failed (nothing is launched then)
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t st);
 void launch_reduce_partials(const float* partials, int S, size_t stride, float* out, size_t n, hipStream_t st);
 
 // ---- attention.hip ----
@@ -118,10 +124,12 @@ struct AttnArgs {
 };
 size_t attention_scratch_bytes(int M, int H, int hd, int max_ctx, int dtype);
 bool attention_mfma_supported(int H, int Hkv, int hd, int block_size, int dtype);
-int attention_min_tiles();  // fewest key tiles an attention workgroup should take (16; experiment switch MN_ATTN_MIN_TILES)
+int attention_min_tiles();  // fewest key tiles an attention workgroup should take (16)
+int attention_target_workgroups();  // attention workgroups with work the plan aims for (320)
 size_t attention_items_capacity(int B, int M, int H, int Hkv);
 // once per step, after the row bookkeeping and before the first launch_attention: the list of workgroups
 void launch_attention_plan(const AttnArgs& a, hipStream_t st);
-void launch_attention(const AttnArgs& a, hipStream_t st);
+// hipSuccess, or the error of a one-time kernel attribute setting that failed (nothing is launched then)
+hipError_t launch_attention(const AttnArgs& a, hipStream_t st);
 
 }  // namespace mn

@@ -32,6 +32,8 @@ __global__ void __launch_bounds__(256) prepare_kernel(PrepArgs a) {
       const long need = (long)ctx + k + 1;
       if (ctx < 0 || need > (long)a.max_blocks_per_seq * a.block_size) { ok = 0; flags |= MN_DEV_BLOCK_TABLE; }
       if (ok && need > a.max_pos) { ok = 0; flags |= MN_DEV_TOKEN; }
+      // the host sized the attention launch (key tiles per split, block-index staging) for max_ctx keys
+      if (ok && need > a.max_ctx) { ok = 0; flags |= MN_DEV_CTX; }
       if (ok) nb = (int)((need + a.block_size - 1) / a.block_size);
     }
     s_ok[b] = ok;
@@ -153,17 +155,29 @@ __device__ __forceinline__ float4 load4<f16_t>(const f16_t* p) {
   const f16x2 a = __builtin_bit_cast(f16x2, u.x), b = __builtin_bit_cast(f16x2, u.y);
   return make_float4((float)a[0], (float)a[1], (float)b[0], (float)b[1]);
 }
+// (fp16 stores saturate and set `bad`, see sat_h)
 template <typename T>
-__device__ __forceinline__ void store4(T* p, float4 v);
+__device__ __forceinline__ void store4(T* p, float4 v, bool& bad);
 template <>
-__device__ __forceinline__ void store4<f16_t>(f16_t* p, float4 v) {
-  *reinterpret_cast<uint2*>(p) = make_uint2(pack2h(v.x, v.y), pack2h(v.z, v.w));
+__device__ __forceinline__ void store4<f16_t>(f16_t* p, float4 v, bool& bad) {
+  *reinterpret_cast<uint2*>(p) = make_uint2(pack2h_sat(v.x, v.y, bad), pack2h_sat(v.z, v.w, bad));
 }
 template <>
-__device__ __forceinline__ void store4<float>(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+__device__ __forceinline__ void store4<float>(float* p, float4 v, bool&) { *reinterpret_cast<float4*>(p) = v; }
 template <>
-__device__ __forceinline__ void store4<bf16_t>(bf16_t* p, float4 v) {
+__device__ __forceinline__ void store4<bf16_t>(bf16_t* p, float4 v, bool&) {
   *reinterpret_cast<uint2*>(p) = make_uint2(pack2bf(v.x, v.y), pack2bf(v.z, v.w));
+}
+// one element in the activation type TA / the page storage type T; fp16 and bf16 saturate to the fp16 range (the
+// pages are widened to fp16 when attention reads them)
+template <typename T>
+__device__ __forceinline__ void store1(T* p, float v, bool& bad) { Store<T>::store(p, v); }
+template <>
+__device__ __forceinline__ void store1<f16_t>(f16_t* p, float v, bool& bad) { *p = (f16_t)sat_h(v, bad); }
+template <>
+__device__ __forceinline__ void store1<bf16_t>(bf16_t* p, float v, bool& bad) {
+  bad |= !(__builtin_fabsf(v) <= F16_MAX);
+  *p = f2bf(__builtin_fminf(__builtin_fmaxf(v, -65280.f), 65280.f));  // 65280: the largest bf16 value below 65504
 }
 
 // T: storage type of the embedding tables; TA: activation type of the normalised output
@@ -235,6 +249,7 @@ __global__ void __launch_bounds__(NORM_THREADS) norm_kernel(NormArgs a) {
   const float var = block_sum<NORM_THREADS / 64>(sq, red) * inv_d;
   const float rstd = 1.f / sqrtf(var + a.eps);
   TA* hr = reinterpret_cast<TA*>(a.h) + (size_t)m * d;
+  bool bad = false;
 #pragma unroll
   for (int it = 0; it < NORM_MAX_VEC; ++it) {
     const int i4 = it * NORM_THREADS + tid;
@@ -248,9 +263,10 @@ __global__ void __launch_bounds__(NORM_THREADS) norm_kernel(NormArgs a) {
         const float4 sh = *reinterpret_cast<const float4*>(a.shift + e);
         o.x += sh.x; o.y += sh.y; o.z += sh.z; o.w += sh.w;
       }
-      store4<TA>(hr + e, o);
+      store4<TA>(hr + e, o, bad);
     }
   }
+  if (bad && a.dev_status) atomicOr(a.dev_status, MN_DEV_RANGE);
 }
 
 void launch_norm(const NormArgs& a, hipStream_t st) {
@@ -294,21 +310,23 @@ __global__ void rope_append_kernel(RopeAppendArgs a) {
     const float r1 = v1 * c + v0 * s;
     v0 = r0; v1 = r1;
   }
+  bool bad = false;
   if (head < a.H) {
     TA* q = reinterpret_cast<TA*>(a.q) + ((size_t)m * a.H + head) * hd;
-    Store<TA>::store(q + t, v0);
-    Store<TA>::store(q + t + half, v1);
+    store1<TA>(q + t, v0, bad);
+    store1<TA>(q + t + half, v1, bad);
+    if (bad && a.dev_status) atomicOr(a.dev_status, MN_DEV_RANGE);
     return;
   }
   // this step's own copy in the activation type (not yet rounded to the cache's storage type)
   if (a.knew) {
     TA* side = reinterpret_cast<TA*>(is_v ? a.vnew : a.knew) +
                ((size_t)m * a.Hkv + (head - a.H - (is_v ? a.Hkv : 0))) * hd;
-    Store<TA>::store(side + t, v0);
-    Store<TA>::store(side + t + half, v1);
+    store1<TA>(side + t, v0, bad);
+    store1<TA>(side + t + half, v1, bad);
   }
   const int pos = a.rows.row_pos[m];
-  if (pos < 0) return;  // disabled sequence: nothing is written to the cache
+  if (pos < 0) return;  // disabled sequence: nothing is written to the cache (and nothing reported)
   const int b = a.rows.row_seq[m];
   const int bs = a.kv.block_size;
   const int pb = a.kv.block_tables[(size_t)b * a.kv.max_blocks_per_seq + pos / bs];
@@ -317,16 +335,17 @@ __global__ void rope_append_kernel(RopeAppendArgs a) {
     const int kh = head - a.H;
     T* base = reinterpret_cast<T*>(a.kv.k) + ((size_t)pb * a.Hkv + kh) * (size_t)hd * bs;
     // [hd/8][bs][8]
-    Store<T>::store(base + ((size_t)(t >> 3) * bs + off) * 8 + (t & 7), v0);
+    store1<T>(base + ((size_t)(t >> 3) * bs + off) * 8 + (t & 7), v0, bad);
     const int t1 = t + half;
-    Store<T>::store(base + ((size_t)(t1 >> 3) * bs + off) * 8 + (t1 & 7), v1);
+    store1<T>(base + ((size_t)(t1 >> 3) * bs + off) * 8 + (t1 & 7), v1, bad);
   } else {
     const int vh = head - a.H - a.Hkv;
     T* base = reinterpret_cast<T*>(a.kv.v) + ((size_t)pb * a.Hkv + vh) * (size_t)hd * bs;
     // [hd][bs]
-    Store<T>::store(base + (size_t)t * bs + off, v0);
-    Store<T>::store(base + (size_t)(t + half) * bs + off, v1);
+    store1<T>(base + (size_t)t * bs + off, v0, bad);
+    store1<T>(base + (size_t)(t + half) * bs + off, v1, bad);
   }
+  if (bad && a.dev_status) atomicOr(a.dev_status, MN_DEV_RANGE);
 }
 
 void launch_rope_append(const RopeAppendArgs& a, hipStream_t st) {
@@ -343,6 +362,7 @@ template <typename T>
 __global__ void __launch_bounds__(256) act_kernel(ActArgs a) {
   const size_t nvec = (size_t)a.M * (a.F >> 2);
   const int ncols = a.swiglu ? 2 * a.F : a.F;
+  bool bad = false;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += (size_t)gridDim.x * blockDim.x) {
     const int m = (int)(i / (a.F >> 2));
     const int f = (int)(i % (a.F >> 2)) << 2;
@@ -369,8 +389,9 @@ __global__ void __launch_bounds__(256) act_kernel(ActArgs a) {
       }
       o = make_float4(fmaxf(g.x, 0.f), fmaxf(g.y, 0.f), fmaxf(g.z, 0.f), fmaxf(g.w, 0.f));
     }
-    store4<T>(reinterpret_cast<T*>(a.act) + (size_t)m * a.F + f, o);
+    store4<T>(reinterpret_cast<T*>(a.act) + (size_t)m * a.F + f, o, bad);
   }
+  if (bad && a.dev_status) atomicOr(a.dev_status, MN_DEV_RANGE);
 }
 
 void launch_act(const ActArgs& a, hipStream_t st) {

@@ -40,14 +40,15 @@ def stream_ptr() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
-def pack_matrix(w: torch.Tensor, interleave_half: int = 0) -> torch.Tensor:
+def pack_matrix(w: torch.Tensor, interleave_half: int = 0, dev_status: Optional[torch.Tensor] = None) -> torch.Tensor:
     """Row-major bf16 [N][K] on the device -> the library's packed streaming layout (a new tensor)."""
     N, K = w.shape
     nbytes = B.mn_packed_weight_bytes(N, K)
     if nbytes == 0:
         raise ValueError("cannot pack a %dx%d matrix" % (N, K))
     out = torch.empty((nbytes // 2,), dtype=torch.bfloat16, device=w.device)
-    B.mn_pack_weight(w.data_ptr(), out.data_ptr(), N, K, interleave_half, stream_ptr())
+    B.mn_pack_weight(w.data_ptr(), out.data_ptr(), N, K, interleave_half,
+                     dev_status.data_ptr() if dev_status is not None else None, stream_ptr())
     return out
 
 

@@ -124,6 +124,36 @@ def test_step_calls_reject_bad_arguments_before_launch(binding):
     binding.mn_destroy(ctx)
 
 
+def _model_shapes():
+    """(kwargs of the model description, batch sizes) of the benchmark models and of a drafting-model shape."""
+    from paper_2402_15678_amd import synth
+    out = []
+    for d, Bs in ((synth.OPT_13B, (8,)), (synth.LLAMA2_70B, (16, 64)), (synth.LLAMA_160M, (16,)),
+                  (synth.ModelDesc(synth.ARCH_LLAMA, synth.DT_BF16, 2, 512, 8, 2, 64, 2048, 4096, 4096), (16,)),
+                  (synth.OPT_TINY, (1,))):
+        kw = dict(arch=d.arch, dtype=d.dtype, n_layers=2, d_model=d.d_model, n_heads=d.n_heads, n_kv_heads=d.n_kv_heads,
+                  head_dim=d.head_dim, d_ffn=d.d_ffn, vocab=d.vocab, max_pos=d.max_pos)
+        out.append((kw, Bs))
+    return out
+
+
+def test_workspace_for_max_rows_serves_every_smaller_step(binding):
+    """mn_workspace_bytes(max_rows) is an upper bound for every step with at most max_rows rows: the k-split of
+    a projection (and with it the room its partial sums need) is not monotone in the row count, the query is."""
+    for kw, Bs in _model_shapes():
+        w, keep = _weights(binding, 2)
+        ctx = binding.mn_create(_desc(binding, **kw), w)
+        for B in Bs:
+            top = 17 * B if B < 64 else 1100
+            sizes = [binding.mn_workspace_bytes(ctx, B, m, 2048) for m in range(0, top + 1)]
+            assert all(s > 0 for s in sizes)
+            worst = 0
+            for m, s in enumerate(sizes):
+                worst = max(worst, s)
+                assert s == worst, (kw["d_model"], B, m, s, worst)     # non-decreasing in the row count
+        binding.mn_destroy(ctx)
+
+
 def test_stochastic_entries_reject_bad_arguments_before_launch(binding):
     p = 0x1000
     vs = lambda **kw: binding.mn_verify_sample(None, kw.get("logits", p), p, p, p, p, kw.get("B", 2), kw.get("k_max", 3),

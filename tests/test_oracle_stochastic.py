@@ -49,6 +49,27 @@ def _dists(rng, k, V, spread):
     return logits, q
 
 
+def test_llm_probs_recovers_a_known_distribution_at_any_temperature():
+    """Closed form: scores T * log p (plus any constant) at temperature T are the distribution p itself; and
+    at temperature T the odds of two tokens are exp((l_a - l_b) / T)."""
+    g = np.random.default_rng(5)
+    for T in (0.5, 1.0, 2.0, 7.25):
+        p = g.random(37) + 1e-3
+        p /= p.sum()
+        for shift in (0.0, -31.5, 400.0):
+            o = orc.llm_probs(T * np.log(p) + shift, T)
+            assert np.allclose(o, p, rtol=1e-12, atol=0.0)
+            assert abs(o.sum() - 1.0) < 1e-14
+    l = np.array([0.3, -1.2, 2.0, 0.0])
+    for T in (0.5, 2.0):
+        o = orc.llm_probs(l, T)
+        assert np.isclose(o[2] / o[1], np.exp((l[2] - l[1]) / T), rtol=1e-13)
+        assert np.isclose(o[0] / o[3], np.exp(0.3 / T), rtol=1e-13)
+    # T -> infinity flattens, a masked score has no mass
+    assert np.allclose(orc.llm_probs(l, 1e9), 0.25, atol=1e-8)
+    assert orc.llm_probs(np.array([0.0, -np.inf, 0.0]), 0.5).tolist() == [0.5, 0.0, 0.5]
+
+
 def test_emitted_tokens_follow_the_llm_distribution():
     """The rule is lossless: whatever q is, the token emitted at a position is distributed as o there.
     Checked on the first position and, given that the first draft survived, on the second."""
