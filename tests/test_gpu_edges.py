@@ -196,6 +196,79 @@ def test_device_detected_errors_disable_only_the_bad_sequence(env):
     assert (ses4.greedy.cpu().numpy() == -1).all() and torch.equal(kvd4.k_pages[0], before4)
 
 
+def test_context_beyond_the_hosts_max_ctx_disables_the_sequence(env):
+    """max_ctx sizes the attention launch on the host; ctx_lens lives on the device and may have moved on.  A
+    sequence whose ctx_b + k_b + 1 exceeds max_ctx sets MN_DEV_CTX and becomes a no-op, the others are unaffected."""
+    harness, binding, W, model = env
+    ctx, ks = np.array([30, 45, 60], np.int32), np.array([3, 3, 3], np.int32)
+    g = synth.stream(8, 3)
+    t = [_i32(g.integers(0, DESC.vocab, size=3)), _i32(g.integers(0, DESC.vocab, size=(3, 3))), _i32(ks)]
+    kvh, kvd, ref = _setup(harness, model, ctx, ks)
+    ref.forward(t[0], t[2], ks.tolist(), voted=t[1])
+    torch.cuda.synchronize()
+    assert ref.dev_status.item() == 0
+    kvh2, kvd2 = synth.make_paged_kv(DESC, ctx, ks, 3), None
+    kvd2 = harness.DeviceKV.from_host(DESC, kvh2)
+    before = kvd2.k_pages[0].clone()
+    short = harness.VerifySession(model, kvd2, 3, 3, 3, 55, max_rows=12, want_logits=True)   # sequence 2 needs 64
+    short.forward(t[0], t[2], ks.tolist(), voted=t[1])
+    short.accept(t[2], voted=t[1])
+    torch.cuda.synchronize()
+    assert short.dev_status.item() == binding.MN_DEV_CTX
+    got = short.greedy.cpu().numpy()
+    assert (got[2] == -1).all() and np.array_equal(got[:2], ref.greedy.cpu().numpy()[:2])
+    assert torch.equal(short.logits[:8], ref.logits[:8])
+    assert short.n_out.cpu().tolist()[2] == 0 and kvd2.ctx_lens.cpu().tolist()[2] == 60
+    changed = (kvd2.k_pages[0] != before).flatten(1).any(dim=1).nonzero().flatten().cpu().tolist()
+    own = set(kvh2.block_tables[2][kvh2.block_tables[2] >= 0].tolist())
+    assert not (set(changed) & own)
+
+
+def test_values_beyond_the_fp16_range_saturate_and_are_reported(env):
+    """bf16 models multiply in fp16.  A weight beyond +-65504 is saturated when it is packed, an activation beyond
+    it when it is stored; both set MN_DEV_RANGE, and no infinity or NaN reaches the logits."""
+    harness, binding, W, model = env
+    # (a) weight packing: one entry of 1e5 (a bf16 value) and one of -3e38
+    g = synth.stream(8, 4)
+    w = synth.storage_round(g.standard_normal((256, 256), dtype=np.float32) * 0.05, synth.DT_BF16)
+    big_vals = synth.storage_round(np.array([1e5, -3e38], np.float32), synth.DT_BF16)
+    w[7, 130], w[200, 3] = big_vals[0], big_vals[1]
+    st = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    packed = harness.pack_matrix(harness.to_device(w, synth.DT_BF16), 0, st)
+    clean = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    harness.pack_matrix(harness.to_device(np.clip(w, -1.0, 1.0), synth.DT_BF16), 0, clean)
+    a = np.zeros((16, 256), np.float32); a[0, 130] = 1.0; a[1, 3] = 0.5; a[2, :] = 0.25
+    out = torch.full((16, 256), float("nan"), dtype=torch.float32, device="cuda:0")
+    a_d = harness.to_device_act(a, synth.DT_BF16)
+    binding.mn_proj_gemm(None, a_d.data_ptr(), packed.data_ptr(), None, out.data_ptr(), 16, 256, 256, 1, None, 0,
+                         harness.stream_ptr())
+    torch.cuda.synchronize()
+    assert st.item() == binding.MN_DEV_RANGE and clean.item() == 0
+    got = out.cpu().numpy()
+    assert np.isfinite(got).all()
+    assert got[0, 7] == 65280.0 and got[1, 200] == -32640.0         # saturated to the largest bf16 value fp16 holds
+    wc = np.clip(w.astype(np.float64), -65280.0, 65280.0)
+    assert np.abs(got - a.astype(np.float64) @ wc.T).max() < 1e-2
+    # (b) activations: first FFN matrix of layer 0 scaled up until silu(gate) * up leaves the range
+    import copy
+    W2 = copy.deepcopy(W)
+    W2["layers"][0]["w1"] = synth.storage_round(W2["layers"][0]["w1"] * 4096.0, synth.DT_BF16)
+    big = harness.DeviceModel.from_host(DESC, W2)
+    ctx, ks = np.array([30, 45], np.int32), np.array([3, 2], np.int32)
+    t = [_i32(g.integers(0, DESC.vocab, size=2)), _i32(g.integers(0, DESC.vocab, size=(2, 3))), _i32(ks)]
+    kvh, kvd, ses = _setup(harness, big, ctx, ks)
+    ses.forward(t[0], t[2], ks.tolist(), voted=t[1])
+    torch.cuda.synchronize()
+    assert ses.dev_status.item() == binding.MN_DEV_RANGE
+    assert torch.isfinite(ses.logits).all()
+    assert (ses.greedy.cpu().numpy()[0, :4] >= 0).all() and (ses.greedy.cpu().numpy()[1, :3] >= 0).all()
+    # the same batch on the unscaled model reports nothing
+    kvh, kvd, ses = _setup(harness, model, ctx, ks)
+    ses.forward(t[0], t[2], ks.tolist(), voted=t[1])
+    torch.cuda.synchronize()
+    assert ses.dev_status.item() == 0
+
+
 def test_few_row_attention_path_disables_only_the_bad_sequence():
     """The drafting models' shape (head_dim 64, one to four rows per sequence) takes its own attention kernel:
     a sequence with a damaged block table becomes a no-op there too, the others are unaffected, plain decode

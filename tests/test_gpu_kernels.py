@@ -148,11 +148,13 @@ def test_proj_gemm_matches_fp64(hb, M, N, K, split):
                          ws.data_ptr(), ws.numel(), harness.stream_ptr())
     torch.cuda.synchronize()
     got = out.cpu().numpy().astype(np.float64)
-    # the oracle's linear step: x W^T + b in fp64 (sampled columns keep the CPU side short)
-    cols = np.unique(np.concatenate([np.arange(0, min(N, 64)), np.arange(max(0, N - 64), N),
-                                     g.integers(0, N, size=256)]))
-    want = orc._linear(a.astype(np.float64), w[cols], bias[cols])
-    err = np.abs(got[:, cols] - want).max()
+    # the oracle's linear step: x W^T + b in fp64, every output element (in column chunks: the fp64 copy of a
+    # 8192 x 28672 matrix would take 2 GB at once)
+    a64 = a.astype(np.float64)
+    err = 0.0
+    for c0 in range(0, N, 2048):
+        want = orc._linear(a64, w[c0:c0 + 2048], bias[c0:c0 + 2048])
+        err = max(err, float(np.abs(got[:, c0:c0 + 2048] - want).max()))
     # exact products, fp32 accumulation over K terms of magnitude ~0.05: far below 1e-3
     assert err < 2e-3 * max(1.0, np.sqrt(K / 1024.0)), err
     assert np.isfinite(got).all()
