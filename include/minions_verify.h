@@ -342,6 +342,24 @@ mn_status mn_probe_mfma_data(int iters, double *flop, void *stream);
 mn_status mn_proj_gemm(mn_ctx *ctx, const void *a, const void *w, const float *bias, float *out, int M, int N, int K,
                        int split_k, void *workspace, size_t workspace_bytes, void *stream);
 
+/* mn_proj_gemm for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc, and callers with no device memory to spare for a workspace.  Same operation, same
+ * kernels and the same bits in `out` as mn_proj_gemm with the same arguments; the split-K partial sums go to a
+ * buffer built into the library (MN_NOALLOC_SCRATCH_BYTES of device memory per GPU, a static array of the
+ * library's device code which the runtime places when the first call on that GPU looks it up, and which
+ * stays until the process ends) instead of a workspace.  The call allocates and
+ * frees nothing, on the device or through any library, and clears nothing (every partial sum it reads it has
+ * written itself).  a, w, bias, out, M, N, K, split_k as for mn_proj_gemm.
+ * Errors: MN_ECAPACITY when split * M * N * 4 bytes exceed MN_NOALLOC_SCRATCH_BYTES (split = split_k, or the
+ * library's choice when split_k == 0; nothing is launched; pass a smaller split_k or use mn_proj_gemm);
+ * MN_EUNSUPPORTED on a device ordinal above 63; otherwise as mn_proj_gemm.
+ * All calls on one GPU share that GPU's buffer, which keeps the previous call's contents: calls that overlap on
+ * one GPU (different streams, or different host threads without ordering between their streams) race; calls on
+ * one stream, or ordered by events, are safe. */
+#define MN_NOALLOC_SCRATCH_BYTES (32u << 20)
+mn_status mn_proj_gemm_noalloc(mn_ctx *ctx, const void *a, const void *w, const float *bias, float *out, int M, int N,
+                               int K, int split_k, void *stream);
+
 /* Multi-token paged attention of one layer (section 4) on caller-supplied queries.  Rows are
  * packed as in mn_verify_forward: sequence b has q_b = h_spec_len[b] + 1 query rows at positions
  * ctx_b .. ctx_b + q_b - 1, whose K/V must already be in the cache.

@@ -19,9 +19,10 @@ MN_DT_F32, MN_DT_BF16 = 0, 1
 MN_VOTE_TREE, MN_VOTE_COLUMN = 0, 1
 MN_DEV_BLOCK_TABLE, MN_DEV_SPEC_LEN, MN_DEV_TOKEN, MN_DEV_DRAFTS, MN_DEV_RANGE, MN_DEV_CTX = 1, 2, 4, 8, 16, 32
 MN_MAX_DRAFTS, MN_MAX_BATCH, MN_MAX_SPLIT_K = 64, 4096, 16
+MN_NOALLOC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = ("mn_create", "mn_destroy", "mn_last_error", "mn_status_str", "mn_workspace_bytes", "mn_mv_vote",
-           "mn_verify_forward", "mn_accept_and_commit", "mn_proj_gemm", "mn_attention", "mn_profile_enable",
+           "mn_verify_forward", "mn_accept_and_commit", "mn_proj_gemm", "mn_proj_gemm_noalloc", "mn_attention", "mn_profile_enable",
            "mn_profile_collect", "mn_packed_weight_bytes", "mn_pack_weight", "mn_acr_update",
            "mn_verify_sample", "mn_draft_sample",
            "mn_selector_create", "mn_selector_destroy", "mn_selector_observe", "mn_selector_current",
@@ -74,6 +75,8 @@ def _load() -> C.CDLL:
     lib.mn_accept_and_commit.argtypes = [vp, vp, vp, vp, i32, i32, C.POINTER(KV), vp, vp, vp, vp, vp, vp, vp]
     lib.mn_proj_gemm.restype = i32
     lib.mn_proj_gemm.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, sz, vp]
+    lib.mn_proj_gemm_noalloc.restype = i32
+    lib.mn_proj_gemm_noalloc.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
     lib.mn_attention.restype = i32
     lib.mn_attention.argtypes = [vp, vp, vp, C.POINTER(C.c_int32), i32, i32, C.POINTER(KV), i32, vp, vp, sz, vp, vp]
     lib.mn_packed_weight_bytes.restype = sz
@@ -171,6 +174,10 @@ def mn_accept_and_commit(ctx, voted, greedy, spec_len, B, k_max, kv: KV, accepte
 
 def mn_proj_gemm(ctx, a, w, bias, out, M, N, K, split_k=0, workspace=None, workspace_bytes=0, stream=None) -> None:
     _check(lib.mn_proj_gemm(ctx, a, w, bias, out, M, N, K, split_k, workspace, workspace_bytes, stream), ctx)
+
+
+def mn_proj_gemm_noalloc(ctx, a, w, bias, out, M, N, K, split_k=0, stream=None) -> None:
+    _check(lib.mn_proj_gemm_noalloc(ctx, a, w, bias, out, M, N, K, split_k, stream), ctx)
 
 
 def mn_attention(ctx, q, spec_len, h_spec_len, B, max_ctx, kv: KV, layer, out, workspace, workspace_bytes,

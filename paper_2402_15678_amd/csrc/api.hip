@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -577,6 +578,70 @@ extern "C" mn_status mn_proj_gemm(mn_ctx* c, const void* a, const void* w, const
     if ((uintptr_t)workspace & 255) return fail(c, MN_EWORKSPACE, "%s: workspace not 256-byte aligned", who);
     if (workspace_bytes < need) return fail(c, MN_EWORKSPACE, "%s: workspace %zu bytes, need %zu", who, workspace_bytes, need);
     g.out = reinterpret_cast<float*>(workspace);
+    lerr = launch_gemm(g, st);
+    if (lerr == hipSuccess) launch_reduce_partials(g.out, s, (size_t)M * N, out, (size_t)M * N, st);
+  }
+  if (lerr != hipSuccess) return fail(c, MN_EHIP, "%s: kernel attribute: %s", who, hipGetErrorString(lerr));
+  return hip_check(c, who);
+}
+
+// ---- the projection without a workspace argument ---------------------------------------------------
+// For callers that can neither allocate nor bring device memory of their own (code under graph capture,
+// tight serving loops): the split-K partial sums live in a buffer that is part of the library's code object.
+// Each GPU the library runs on holds its own copy of the array at its own address; the name below is the
+// host-side stand-in for it, never a device address: the address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[MN_NOALLOC_SCRATCH_BYTES];
+
+static constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on device i, null until looked up
+static std::mutex g_scratch_mu;
+
+// Device address of this process's scratch array on the current device (looked up on the first call there).
+static mn_status scratch_on_current_device(mn_ctx* c, const char* who, void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(c, MN_EHIP, "%s: hipGetDevice: %s", who, hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(c, MN_EUNSUPPORTED, "%s: device ordinal %d (at most %d devices)", who, dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return fail(c, MN_EHIP, "%s: hipGetSymbolAddress: %s", who, hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MN_OK;
+}
+
+extern "C" mn_status mn_proj_gemm_noalloc(mn_ctx* c, const void* a, const void* w, const float* bias, float* out, int M,
+                                          int N, int K, int split_k, void* stream) {
+  const char* who = "mn_proj_gemm_noalloc";
+  if (M < 0 || N < 1 || K < 128 || K % 128) return fail(c, MN_ESHAPE, "%s: M=%d N=%d K=%d (K must be a positive multiple of 128)", who, M, N, K);
+  if (split_k < 0 || split_k > MN_MAX_SPLIT_K) return fail(c, MN_EINVAL, "%s: split_k = %d", who, split_k);
+  if (M == 0) return MN_OK;
+  if (!a || !w || !out) return fail(c, MN_ENULL, "%s: a/w/out is NULL", who);
+  int s = split_k ? split_k : gemm_pick_split(M, N, K, MN_DT_BF16);
+  if (s > K / 128) s = K / 128;
+  hipStream_t st = (hipStream_t)stream;
+  GemmArgs g{};
+  g.a = a; g.w = w; g.bias = bias; g.M = M; g.N = N; g.K = K; g.split_k = s; g.dtype = MN_DT_BF16;
+  hipError_t lerr = hipSuccess;
+  if (s == 1) {
+    g.out = out;   // one split writes the result itself: no scratch in use
+    Tap t(c ? &c->prof : nullptr, MN_PROF_GEMM, st);
+    lerr = launch_gemm(g, st);
+  } else {
+    const size_t need = (size_t)s * M * N * 4;
+    if (need > (size_t)MN_NOALLOC_SCRATCH_BYTES)
+      return fail(c, MN_ECAPACITY, "%s: %d splits of %d x %d partial sums need %zu bytes, the built-in buffer holds %zu "
+                  "(pass a smaller split_k, or use mn_proj_gemm with a workspace)", who, s, M, N, need,
+                  (size_t)MN_NOALLOC_SCRATCH_BYTES);
+    void* buf = nullptr;
+    if (mn_status rc = scratch_on_current_device(c, who, &buf)) return rc;
+    // Nothing has to start at zero: the projection kernel writes every element [split][m][n] the reduction reads
+    // (a split without iterations stores zeros), so what an earlier call left behind is never seen.
+    g.out = reinterpret_cast<float*>(buf);
+    Tap t(c ? &c->prof : nullptr, MN_PROF_GEMM, st);
     lerr = launch_gemm(g, st);
     if (lerr == hipSuccess) launch_reduce_partials(g.out, s, (size_t)M * N, out, (size_t)M * N, st);
   }
