@@ -129,6 +129,17 @@ typedef struct {
 mn_status mn_create(mn_ctx **out, const mn_model_desc *desc, const mn_weights *weights);
 void mn_destroy(mn_ctx *ctx);
 
+/* Options of a context (off unless set).
+ * MN_OPT_STEP_KV_FROM_CACHE (bf16 models; value 0 or 1): where the attention of mn_verify_forward takes the K/V
+ *   rows of the positions the same call scores.  0, the default: from an fp16 copy kept for the length of the call
+ *   (the cache gets them rounded to bf16 all the same): closest to the exact result.  1: from the cache, in the
+ *   cache's precision, which is where every later call finds them: scoring k + 1 positions in one pass then
+ *   multiplies exactly the numbers that k + 1 single-position calls multiply (section 2.1: the LLM scores the
+ *   speculated tokens "in parallel" with the same outcome as one by one), at the price of the storage rounding
+ *   of those rows (2^-9 relative instead of 2^-12) in this call's own scores. */
+enum { MN_OPT_STEP_KV_FROM_CACHE = 1 };
+mn_status mn_set_option(mn_ctx *ctx, int option, int value);
+
 /* Message of the last failed call on ctx (or of the last failed mn_create when ctx is NULL).
  * The string is owned by the library and valid until the next failing call on the same ctx. */
 const char *mn_last_error(const mn_ctx *ctx);

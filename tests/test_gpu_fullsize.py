@@ -1,6 +1,7 @@
 """Full-size GPU checks in the launch configuration bench.py times.  The oracle cannot run 80 layers, so
-the full-depth step is checked through properties that hold at any size (all-greedy drafts are fully
-accepted, a corruption at position i cuts acceptance at i, bit reproducibility); the attention-only
+the full-depth step is checked through properties that hold at any size (one pass over k + 1 positions against
+k + 1 sequential decodes within bounds derived from the measured growth of the logit error with depth, a
+corruption at position i cuts acceptance at i, bit reproducibility); the attention-only
 configuration (32 x 8192 keys) is checked row by row against the oracle."""
 import numpy as np
 import pytest
@@ -8,6 +9,7 @@ import torch
 
 from oracle import minions_oracle as orc
 from paper_2402_15678_amd import synth
+from tests import util
 
 pytestmark = pytest.mark.gpu
 TOL = 3e-2
@@ -18,7 +20,7 @@ def _i32(a):
 
 
 def test_llama70b_full_depth_b16_k8_properties():
-    from paper_2402_15678_amd import harness
+    from paper_2402_15678_amd import binding, harness
     wl = synth.WORKLOADS[2]
     desc = wl.desc
     free, _ = torch.cuda.mem_get_info()
@@ -32,18 +34,23 @@ def test_llama70b_full_depth_b16_k8_properties():
     ctx0 = kvd.ctx_lens.clone()
     g = synth.stream(wl.seed, 600)
     last = _i32(g.integers(0, desc.vocab, size=B))
-    # the library's own greedy continuation, one token at a time
     one = harness.VerifySession(model, kvd, B, 0, 1, max_ctx, max_rows=B, want_logits=True)
     zeros, dummy = _i32(np.zeros(B)), _i32(np.zeros((B, 1)))
-    cur, cont, seq_logits = last.clone(), [], []
-    for _ in range(k + 1):
-        one.forward(cur, zeros, [0] * B, voted=dummy)
-        one.accept(zeros, voted=dummy)
-        cur = one.next_last_tok.clone()
-        cont.append(cur.cpu().numpy())
-        seq_logits.append(one.logits.cpu().numpy().copy())
-    cont = np.stack(cont, axis=1)                                   # [B][k+1]: token after the pending one, ...
-    seq_logits = np.stack(seq_logits, axis=1)                       # [B][k+1][V]
+
+    def sequential():
+        """The library's own greedy continuation, one token at a time: tokens [B][k+1] and their logits."""
+        kvd.ctx_lens.copy_(ctx0)
+        cur, toks, lgs = last.clone(), [], []
+        for _ in range(k + 1):
+            one.forward(cur, zeros, [0] * B, voted=dummy)
+            one.accept(zeros, voted=dummy)
+            cur = one.next_last_tok.clone()
+            toks.append(cur.cpu().numpy())
+            lgs.append(one.logits.cpu().numpy().copy())
+        kvd.ctx_lens.copy_(ctx0)
+        return np.stack(toks, axis=1), np.stack(lgs, axis=1)
+
+    cont, seq_logits = sequential()
     kvd.ctx_lens.copy_(ctx0)
     ses = harness.VerifySession(model, kvd, B, k, 3, max_ctx, max_rows=B * (k + 1), want_logits=True)
     spec, w = _i32(ks), torch.ones(3, device="cuda:0")
@@ -57,32 +64,40 @@ def test_llama70b_full_depth_b16_k8_properties():
         return (ses.accepted_len.cpu().numpy().copy(), ses.out_tokens.cpu().numpy().copy(),
                 ses.logits.clone(), kvd.ctx_lens.cpu().numpy().copy())
 
-    good = np.repeat(cont[:, None, :k], 3, axis=1)                  # all three drafts = greedy continuation
-    acc, out, logits, new_ctx = run(good)
-    lg = logits.cpu().numpy().reshape(B, k + 1, -1)
-    full = 0
-    worst_rel = 0.0
-    for b in range(B):
-        a = int(acc[b])
-        assert np.array_equal(out[b, :a], cont[b, :a])
-        assert new_ctx[b] == ctx[b] + a + 1
-        # up to the first position where the two decodings part they have seen the same tokens: their logits are
-        # the same quantity computed along two rounding paths (the sequential one re-reads its own K/V from
-        # the bf16 cache); 80 layers amplify that, so the bound is looser than the 2-layer tolerance
-        diff = lg[b, :a + 1] - seq_logits[b, :a + 1]
-        drift = np.abs(diff).max()
-        rel_rms = float(np.sqrt((diff ** 2).mean()) / lg[b, :a + 1].std())
-        worst_rel = max(worst_rel, rel_rms)
-        assert rel_rms < 0.05 and drift < 0.75, (b, drift, rel_rms)   # a wrong row or mask would give O(1)
-        if a == k:
-            full += 1
-            assert out[b, k] == cont[b, k]
-        else:
-            # they may only part where the one-pass top-1 margin is within twice that drift
-            part = np.partition(lg[b, a], -2)
-            assert part[-1] - part[-2] <= 2 * drift + 1e-6, (b, a, part[-1] - part[-2], drift)
-    assert full >= B // 2, full                                   # near ties do flip at this depth
-    print("full-depth one-pass vs sequential: rms drift / logit std = %.4f, fully accepted %d/%d" % (worst_rel, full, B))
+    def one_pass_against_sequential(bound, label, cont, seq_logits):
+        """One pass over the k + 1 positions against the k + 1 single-position passes above: up to the first position
+        where the two decodings part they have seen the same tokens, so their logits are the same quantity and may
+        differ by `bound` at most; they may only part at a position whose top-1 margin is within twice that bound."""
+        good = np.repeat(cont[:, None, :k], 3, axis=1)             # all three drafts = greedy continuation
+        acc, out, logits, new_ctx = run(good)
+        lg = logits.cpu().numpy().reshape(B, k + 1, -1)
+        full, worst, worst_rel = 0, 0.0, 0.0
+        for b in range(B):
+            a = int(acc[b])
+            assert np.array_equal(out[b, :a], cont[b, :a])
+            assert new_ctx[b] == ctx[b] + a + 1
+            diff = lg[b, :a + 1] - seq_logits[b, :a + 1]
+            worst = max(worst, float(np.abs(diff).max()))
+            worst_rel = max(worst_rel, float(np.sqrt((diff ** 2).mean()) / lg[b, :a + 1].std()))
+            if a == k:
+                full += 1
+                assert out[b, k] == cont[b, k]
+            else:
+                part = np.partition(lg[b, a], -2)
+                assert part[-1] - part[-2] <= 2 * bound, (label, b, a, part[-1] - part[-2])
+        print("full depth, %s: one pass vs sequential max |dlogit| = %.3e (bound %.3e), rms / logit std = %.4f, fully "
+              "accepted %d/%d" % (label, worst, bound, worst_rel, full, B))
+        assert worst <= bound, (label, worst, bound)
+        return acc, out, logits, full
+
+    # (1) The default: the pass that scores a position attends to its K/V in fp16, every later pass finds them in the
+    # bf16 cache.  Each decoding is within its own distance of the exact result (tests/test_gpu_depth.py measures
+    # the first against the oracle; the second is CACHE_PRECISION_FACTOR times that), and so they are within the sum.
+    tol80 = util.logit_tol_at_depth(desc.n_layers)
+    acc, out, logits, full = one_pass_against_sequential((1.0 + util.CACHE_PRECISION_FACTOR) * tol80, "step K/V in fp16",
+                                                         cont, seq_logits)
+    assert full >= B // 2, full
+    good = np.repeat(cont[:, None, :k], 3, axis=1)
     # bit reproducibility of the whole step
     acc2, out2, logits2, _ = run(good)
     assert torch.equal(logits, logits2) and np.array_equal(acc, acc2) and np.array_equal(out, out2)
@@ -97,6 +112,17 @@ def test_llama70b_full_depth_b16_k8_properties():
             assert acc3[b] == cut[b], (b, acc3[b], cut[b])
             assert np.array_equal(out3[b, :cut[b] + 1], cont[b, :cut[b] + 1])
             assert ctx3[b] == ctx[b] + cut[b] + 1
+    # (2) The step's own K/V taken from the cache like everybody else's: both decodings now multiply the same
+    # numbers.  What is left is the order of the fp32 sums, which differs between a 16-row and a 144-row launch
+    # (other k-splits, other key tiles per workgroup) and tips an fp16 rounding of an activation now and then; from
+    # there on the two passes carry partly different rounding noise, each still within the depth's distance of the
+    # exact result.  Measured 5.7e-2 at 80 layers (0.5 % of the logit spread) against 3.8e-1 in the default mode,
+    # and every one of the 16 all-greedy sequences fully accepted.  Bound: that distance, once.
+    binding.mn_set_option(model.ctx, binding.MN_OPT_STEP_KV_FROM_CACHE, 1)
+    cont_c, seq_logits_c = sequential()
+    _, _, _, full_c = one_pass_against_sequential(tol80, "step K/V from the cache", cont_c, seq_logits_c)
+    binding.mn_set_option(model.ctx, binding.MN_OPT_STEP_KV_FROM_CACHE, 0)
+    assert full_c >= full
 
 
 def test_attention_only_config_full_size_against_oracle():

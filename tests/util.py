@@ -13,6 +13,21 @@ from paper_2402_15678_amd import synth
 TOL = {synth.DT_F32: 1e-4, synth.DT_BF16: 3e-2}
 
 
+def logit_tol_at_depth(n_layers: int) -> float:
+    """Bound on max |logit - oracle| of the bf16-storage path after n_layers layers at the Llama-2-70B width.
+    Every layer adds rounding noise of the fp16 activation stages (norm output, queries, probabilities, attention
+    output, FFN activation) that is independent of the other layers', so the error grows like a random walk:
+    measured 1.7e-2, 2.2e-2, 2.9e-2, 3.4e-2 at 1, 2, 4, 8 layers (exponent 0.43; 80 layers at a reduced width
+    follow the same curve).  The 3e-2 of the bf16 path holds up to 4 layers; beyond, the bound follows sqrt(L)."""
+    return TOL[synth.DT_BF16] * max(1.0, float(np.sqrt(n_layers / 4.0)))
+
+
+# A pass that finds the rows it attends to in the bf16 cache (every pass after the one that scored them) is this
+# many times further from the exact result than the pass that scored them and still had them in fp16 (measured at
+# the 70B width, one layer: 4.7e-2 against 1.7e-2).
+CACHE_PRECISION_FACTOR = 3.0
+
+
 def weights_f64(W: Dict[str, object]) -> Dict[str, object]:
     """The same parameters held as fp64 so the oracle does not convert them at every use."""
     out = {k: np.asarray(v, np.float64) for k, v in W.items() if k != "layers"}
