@@ -364,7 +364,6 @@ def main():
     draft_ms = None
     draft_graph_ms = None
     draft_seq_ms = None
-    overlap_ms = None
     if desc.arch == synth.ARCH_LLAMA and desc.dtype == synth.DT_BF16 and args.layers <= 0:
         sd = synth.LLAMA_160M
         s_models = [harness.DeviceModel.random_on_device(sd, wl.seed + 100 + j) for j in range(n)]
@@ -386,20 +385,6 @@ def main():
         dsn.draft(last, k_max, concurrent=False)
         torch.cuda.synchronize()
         draft_seq_ms = (time.perf_counter() - t_d) * 1e3
-        # the paper's pipeline (section 3.4) in its one-GPU form: the SSMs draft on their streams while the LLM
-        # verifies on another; informational (what the round costs when the two overlap, against their sum)
-        for kv, c0 in zip(s_kvs, s_ctx0):
-            kv.ctx_lens.copy_(c0)
-        llm_stream = torch.cuda.Stream()
-        torch.cuda.synchronize()
-        t_d = time.perf_counter()
-        llm_stream.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(llm_stream):
-            step()
-        dsn.draft(last, k_max)
-        torch.cuda.current_stream().wait_stream(llm_stream)
-        torch.cuda.synchronize()
-        overlap_ms = (time.perf_counter() - t_d) * 1e3
         if args.graph:
             # the drafting of all SSMs (a few thousand small launches, no host decision in between) as one graph
             for kv, c0 in zip(s_kvs, s_ctx0):
@@ -501,7 +486,6 @@ def main():
                        "selector_observe_ns_incl_binding": sel_ns,
                        "ssm_drafting_ms": draft_ms, "ssm_drafting_ms_one_after_the_other": draft_seq_ms,
                        "ssm_drafting_ms_graph_replay": draft_graph_ms,
-                       "step_and_ssm_drafting_overlapped_ms": overlap_ms,
                        "ssm_drafting_note": "n SSMs of Llama-160M shape, k_max tokens each, on this GPU, one stream per SSM"},
         "roofline": roofline, "kernel_families": families,
         "ceilings": measure_ceilings(torch, binding, harness), "cpu_baseline": cpu,

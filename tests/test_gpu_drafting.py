@@ -8,6 +8,7 @@ import torch
 from oracle import minions_oracle as orc
 from paper_2402_15678_amd import synth
 from tests import util
+from tests.generation_loop import GenerationLoop
 
 pytestmark = pytest.mark.gpu
 
@@ -102,7 +103,7 @@ def test_generation_rounds_with_ssm_resync_are_lossless():
     ssm = [build(d, 921 + i) for i, d in enumerate(ssm_descs)]
     max_ctx = int((ctx + room + 1).max())
     w = torch.ones(len(ssm), device="cuda:0")
-    loop = harness.GenerationLoop(llm_m, llm_kv, [s[1] for s in ssm], [s[2] for s in ssm], B, k, max_ctx, _i32(last), w)
+    loop = GenerationLoop(llm_m, llm_kv, [s[1] for s in ssm], [s[2] for s in ssm], B, k, max_ctx, _i32(last), w)
 
     # the oracle's side: the LLM's greedy stream, long enough for the most the rounds can emit
     T = rounds * (k + 1)
