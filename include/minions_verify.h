@@ -241,8 +241,9 @@ mn_status mn_accept_and_commit(mn_ctx *ctx, const int32_t *voted, const int32_t 
  * temperature -> 0 case).  With o_j = softmax(logits row of position j / temperature) and q_j the
  * drafting SSM's distribution at that position, the speculated token x = voted[b][j] survives when
  * q_j(x) <= o_j(x), and otherwise with probability o_j(x) / q_j(x); where it does not survive, a
- * replacement is drawn from max(0, o_j - q_j) renormalised (from o_j itself should that be zero
- * everywhere); at position k_b, after the last speculated token, a token is drawn from o_{k_b}.
+ * replacement is drawn from max(0, o_j - q_j) renormalised (should that be zero everywhere, which only a
+ * draft_probs row summing above 1 can cause: from o_j without the token x; should o_j have no other mass
+ * either, x stays); at position k_b, after the last speculated token, a token is drawn from o_{k_b}.
  * The result is written in the layout of `greedy`: sampled[b][j] = voted[b][j] where the token
  * survived, the drawn token elsewhere, -1 beyond k_b.  A replacement never equals the token it
  * replaces, so mn_accept_and_commit(voted, sampled, ...) then yields exactly the rule's output: the

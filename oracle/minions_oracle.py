@@ -485,8 +485,12 @@ def accept_stochastic(voted: Sequence[int], logits: np.ndarray, draft_probs: np.
             out.append(x)
             continue
         residual = np.maximum(0.0, o - q)
-        if not residual.sum() > 0.0:        # q covers o everywhere (possible only for a q that sums above 1)
-            residual = o
+        if not residual.sum() > 0.0:        # q covers o everywhere (possible only for a q that sums above 1):
+            residual = o.copy()             # the LLM's distribution without the rejected token, so that the
+            residual[x] = 0.0               # replacement still differs from what it replaces
+        if not residual.sum() > 0.0:        # ... and all of o sits on x: there is nothing else to emit, x stays
+            out.append(x)
+            continue
         tok, gap = sample_cdf(residual, u_res)
         margin = min(margin, gap)
         out.append(tok)

@@ -224,11 +224,19 @@ __global__ void __launch_bounds__(SV_THREADS) verify_sample_kernel(
     if (tid == 0) *out = x;
     return;
   }
-  // ---- a token from max(0, o - q); without q (position k_b), or when nothing of o lies above q, from o ----
+  // ---- a token from max(0, o - q); without q (position k_b) from o.  When nothing of o lies above q (a q that
+  // sums above 1) the replacement comes from o without the rejected token, so that it still differs from what
+  // it replaces (the acceptance reads "first entry that differs" as the first rejection); and when all of o
+  // sits on that token there is nothing else to emit: it stays ----
   int tok = -1;
-  if (Q) tok = cdf_draw([&](int v) { return fmax(0.0, exp(((double)L[v] - dmx) / temperature) / Z - (double)Q[v]); }, V,
-                        u_res, sh, tid);
-  if (tok < 0) tok = cdf_draw([&](int v) { return exp(((double)L[v] - dmx) / temperature) / Z; }, V, u_res, sh, tid);
+  if (Q) {
+    tok = cdf_draw([&](int v) { return fmax(0.0, exp(((double)L[v] - dmx) / temperature) / Z - (double)Q[v]); }, V,
+                   u_res, sh, tid);
+    if (tok < 0) tok = cdf_draw([&](int v) { return v == x ? 0.0 : exp(((double)L[v] - dmx) / temperature) / Z; }, V, u_res, sh, tid);
+    if (tok < 0) tok = x;
+  } else {
+    tok = cdf_draw([&](int v) { return exp(((double)L[v] - dmx) / temperature) / Z; }, V, u_res, sh, tid);
+  }
   if (tid == 0) *out = tok;
 }
 

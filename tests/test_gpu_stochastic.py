@@ -352,3 +352,35 @@ def test_sampled_drafting_loop_on_the_device(hb):
         assert 0 <= a <= k and n_out[b] == a + 1 and out[b, :a].tolist() == voted[b, :a].tolist()
         assert 0 <= out[b, a] < V and (a == k or out[b, a] != voted[b, a])
     assert llm_kv.ctx_lens.cpu().tolist() == (ctx + acc + 1).tolist()
+
+
+def test_draft_probs_that_cover_the_llm_distribution(hb):
+    """A draft_probs row that sums above 1 can lie above o everywhere: max(0, o - q) is then empty, the
+    replacement comes from o without the rejected token (never that token itself), and where o has no other mass
+    the token stays.  Decision by decision against the oracle."""
+    B, k_max, V, T = 12, 6, 301, 1.0
+    spec, M, logits, q, voted = _case(7, B, k_max, V, T, 1.0)
+    row = 0
+    for b in range(B):
+        for j in range(int(spec[b])):
+            o = orc.llm_probs(logits[row + j], T)
+            q[b, j] = (1.5 * o + 1e-6).astype(np.float32)             # above o everywhere
+        row += int(spec[b]) + 1
+    # one position where all of o sits on the speculated token (the other scores are masked)
+    logits[0, :] = -np.inf
+    logits[0, int(voted[0, 0])] = 0.0
+    q[0, 0, :] = 0.0
+    q[0, 0, int(voted[0, 0])] = 4.0
+    ctx0 = (np.arange(B) * 5 + 1).astype(np.int32)
+    rejections = 0
+    for step in range(6):
+        res = _run_gpu(hb, spec, M, logits, q, voted, k_max, V, T, seed=99, step=step, ctx0=ctx0)
+        _check_against_oracle(res, spec, logits, q, voted, k_max, T, 99, step, ctx0)
+        sampled, acc = res[0], res[1]
+        for b in range(B):
+            a, k = int(acc[b]), int(spec[b])
+            if a < k:
+                rejections += 1
+                assert sampled[b, a] != voted[b, a] and sampled[b, a] >= 0
+        assert sampled[0, 0] == voted[0, 0]                             # nothing else could be emitted there
+    assert rejections >= 10                                             # survival probability is 2/3 per position

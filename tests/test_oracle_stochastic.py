@@ -160,3 +160,30 @@ def test_draft_sample_distribution_and_streams():
     # a draw on a one-hot distribution is that token whatever the number
     hot = np.full(V, -1e4); hot[4] = 0.0
     assert all(orc.draft_sample(hot, 1.0, 1, s_, 0, 0, 0)[0] == 4 for s_ in range(50))
+
+
+def test_a_draft_distribution_above_the_llms_everywhere_never_re_emits_the_rejected_token():
+    """q = 1.5 o (not a distribution): max(0, o - q) is empty.  A rejected token is then replaced from o without
+    that token: the replacement differs from it, is rejected with probability 1 - o/q = 1/3, and follows
+    o(v) / (1 - o(x)); with all of o on the token, it stays."""
+    g = np.random.default_rng(11)
+    V, T, x = 6, 1.0, 2
+    logits = np.stack([g.normal(0.0, 1.0, V), g.normal(0.0, 1.0, V)])
+    o = orc.llm_probs(logits[0], T)
+    q = (1.5 * o)[None, :]
+    counts, rejected, n = np.zeros(V), 0, 6000
+    for step in range(n):
+        a, toks, _ = orc.accept_stochastic([x], logits, q, 1, T, 5, step, 0)
+        if a == 0:
+            rejected += 1
+            assert toks[0] != x
+            counts[toks[0]] += 1
+    assert abs(rejected / n - 1.0 / 3.0) < 0.02
+    want = o.copy(); want[x] = 0.0; want /= want.sum()
+    assert np.abs(counts / rejected - want).max() < 0.03
+    # all of o on x, q(x) > 1: whatever the uniform number says, x is what comes out, and the next position is reached
+    lone = np.full((2, V), -np.inf); lone[0, x] = 0.0; lone[1] = logits[1]
+    q1 = np.zeros((1, V)); q1[0, x] = 3.0
+    for step in range(50):
+        a, toks, _ = orc.accept_stochastic([x], lone, q1, 1, T, 5, step, 0)
+        assert a == 1 and toks[0] == x and len(toks) == 2
