@@ -154,7 +154,7 @@ constexpr int BS = 16;
 constexpr int KT = 32;                         // keys per tile (two blocks)
 constexpr int TILE_HALFS = 2 * KT * HD;        // fp16 elements of K + V of one tile
 constexpr int TILE_BYTES = TILE_HALFS * 2;     // 16 KB
-constexpr int NS = 4;                          // tile slots in LDS
+constexpr int NS = 4;                          // tile slots in LDS (a ring of 8, seven tiles of lead, is slower: measured)
 constexpr int MAX_CT = 2;                      // column tiles per wave; a workgroup covers 64 * MAX_CT stacked rows
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LAZY_MAX = 6.f;                // the reference moves when a score exceeds it by 2^6
@@ -210,9 +210,13 @@ __device__ __forceinline__ int seq_splits(int n_tiles, int tps, int n_splits_max
 }
 
 // Partials: o_part [split][M][H][HD] fp32 (unnormalised), ml_part [split][M][H][2] = (max in log2 units, sum)
-template <int CTW>
-__global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, float* __restrict__ o_part,
-                                                           float* __restrict__ ml_part) {
+// NW waves per workgroup.  Waves 0-3 are the loaders (the tile's 16 fragments are dealt to four waves); with 5 or
+// 6 waves the others only multiply: a stack of 65-96 query rows (5 or 6 column tiles, e.g. 8 query heads per KV
+// head x 9-12 scored positions) then gives every wave one column tile, where four waves would leave one of them
+// two tiles' worth of products and softmax per key tile while the other three wait at the barrier.
+template <int CTW, int NW>
+__global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) attn_mfma_kernel(AttnArgs a, float* __restrict__ o_part,
+                                                                             float* __restrict__ ml_part) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   f16_t* s_kv = reinterpret_cast<f16_t*>(smem);                          // [NS][16 fragments][64 lanes][8]
   int32_t* s_bidx = reinterpret_cast<int32_t*>(smem + NS * TILE_BYTES);  // physical block of every block of the split
@@ -223,7 +227,7 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, float* __
   // dense in the id space (with the split as the fast grid index a batch that used 2 of 16 possible splits
   // ran on 2 of the 8 XCDs; with an often empty second row group next to the sequence index the real
   // workgroups shared half of the CUs) and long items must not queue behind short ones.
-  // Row group rg: column tiles [4*CTW*rg, 4*CTW*(rg+1)) of the stack; sequences with more than 64*CTW stacked
+  // Row group rg: column tiles [NW*CTW*rg, NW*CTW*(rg+1)) of the stack; sequences with more than 16*NW*CTW stacked
   // rows get a workgroup per group (each streams the keys again).
   const int item = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
   const int4 rec0 = reinterpret_cast<const int4*>(a.items)[2 * item];
@@ -236,20 +240,21 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, float* __
   const int G = a.H / a.Hkv;
   const int R = G * qb;                   // query rows sharing this KV head; row r = j*G + gi
   const int NT16 = (R + 15) >> 4;         // column tiles in use
-  const int tile0 = 4 * CTW * rg;         // first column tile of this workgroup
+  const int tile0 = NW * CTW * rg;        // first column tile of this workgroup
+  const bool loader = wave < 4;           // (wave-uniform)
   if (qb <= 0 || tile0 >= NT16 || split >= my_splits) return;  // (whole workgroup; the list holds no such record)
   const int nkeys = ok ? ctx + qb : 0;
   const int n_tiles = (nkeys + KT - 1) / KT;
   const int t_begin = (int)(((long)n_tiles * split) / my_splits);
   const int t_end = (int)(((long)n_tiles * (split + 1)) / my_splits);
   const int n_my = max(0, t_end - t_begin);
-  const int nct = ok ? min(CTW, max(0, (NT16 - tile0 - wave + 3) >> 2)) : 0;  // real column tiles of this wave
+  const int nct = ok ? min(CTW, max(0, (NT16 - tile0 - wave + NW - 1) / NW)) : 0;  // real column tiles of this wave
 
   // block table of this split -> LDS (the dependent chain table -> address -> load would otherwise
   // cost an L2 round trip per tile); entries past the last mapped block repeat the last one
   const int32_t* bt = a.kv.block_tables + (size_t)b * a.kv.max_blocks_per_seq;
   const int last_blk = ok ? (nkeys - 1) / BS : 0;
-  for (int i = tid; i < 2 * n_my; i += 256) s_bidx[i] = bt[min(2 * t_begin + i, last_blk)];
+  for (int i = tid; i < 2 * n_my; i += NW * 64) s_bidx[i] = bt[min(2 * t_begin + i, last_blk)];
 
   // ---- Q fragments -> registers, scaled by log2(e)/sqrt(hd) (one more fp16 rounding of q, 2^-11), so
   // the scores come out of the first product in log2 units.  Rows past R are zero. ----
@@ -265,7 +270,7 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, float* __
     thr[ct] = -INFINITY;
     negm4[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
     L[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    const int r = (tile0 + wave + 4 * ct) * 16 + l16;
+    const int r = (tile0 + wave + NW * ct) * 16 + l16;
     lim[ct] = ctx + min(r / G, qb - 1);  // last visible key of this lane's query row
 #pragma unroll
     for (int u = 0; u < 8; ++u) O[ct][u] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -305,7 +310,7 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, float* __
     const int ti_last = n_my - 1;
     // all loads of tile TI of the split -> slot SLOT (tiles past the end repeat the last one)
 #define MN_ATT_DMA(TI, SLOT)                                                                      \
-  {                                                                                               \
+  if (loader) {                                                                                   \
     const int t_ = min((TI), ti_last);                                                            \
     /* (the clamp costs two instructions and keeps a damaged table from becoming a wild address) */ \
     const char* kp_ = kbase + (uint64_t)min((uint32_t)s_bidx[2 * t_ + ksel], blk_last) * blk_bytes; \
@@ -325,32 +330,51 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, float* __
       if (slow) {
         const int key0 = (t_begin + ti) * KT;
         if (key0 + KT > ctx) {
+          // This step's own keys.  Every load goes out first, from a row that exists whether or not the key does
+          // (clamped), and the selection follows: one memory round trip per tile.  Loads inside the conditions were
+          // a chain of eighteen dependent round trips, 6 us per tile, and the split that holds the new keys set
+          // the length of the whole launch.
+          f16x8 kn[2];
+          f16_t vn[2][8];
+          if (Kn) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+              const int r = min(max(key0 + kkey0 + 4 * t - ctx, 0), qb - 1);
+              kn[t] = *reinterpret_cast<const f16x8*>(Kn + ((size_t)(row0 + r) * a.Hkv + kvh) * HD + kchunk * 8);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+              const int hd = 16 * (wave + 4 * i) + l16;
+#pragma unroll
+              for (int e = 0; e < 8; ++e) {
+                const int r = min(max(key0 + 8 * g + e - ctx, 0), qb - 1);
+                vn[i][e] = Vn[((size_t)(row0 + r) * a.Hkv + kvh) * HD + hd];
+              }
+            }
+          }
 #pragma unroll
           for (int t = 0; t < 2; ++t) {
             const int key = key0 + kkey0 + 4 * t;
-            if (Kn && key >= ctx && key < nkeys)
-              w[t] = *reinterpret_cast<const f16x8*>(Kn + ((size_t)(row0 + key - ctx) * a.Hkv + kvh) * HD + kchunk * 8);
+            if (Kn && key >= ctx && key < nkeys) w[t] = kn[t];
           }
 #pragma unroll
           for (int i = 0; i < 2; ++i) {
-            const int hd = 16 * (wave + 4 * i) + l16;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
               const int key = key0 + 8 * g + e;
               if (key >= nkeys) w[2 + i][e] = (f16_t)0.f;
-              else if (Vn && key >= ctx) w[2 + i][e] = Vn[((size_t)(row0 + key - ctx) * a.Hkv + kvh) * HD + hd];
+              else if (Vn && key >= ctx) w[2 + i][e] = vn[i][e];
             }
           }
         }
       }
     };
     f16x8 kf[8];  // K fragments of the tile about to be multiplied
-    // prologue: tiles 0, 1, 2 on their way; tile 0 widened and its K fragments in registers
-    MN_ATT_DMA(0, 0)
-    MN_ATT_DMA(1, 1)
-    MN_ATT_DMA(2, 2)
-    wait_vm<8>();
-    {
+    // prologue: tiles 0 .. NS-2 on their way; tile 0 widened and its K fragments in registers
+#pragma unroll
+    for (int t = 0; t < NS - 1; ++t) MN_ATT_DMA(t, t)
+    wait_vm<4 * (NS - 2)>();
+    if (loader) {
       u32x4 raw[4];
       f16x8 w[4];
 #pragma unroll
@@ -364,24 +388,28 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, float* __
     for (int f = 0; f < 8; ++f) kf[f] = *reinterpret_cast<const f16x8*>(s_kv + (f * 64 + lane) * 8);
 
     // Iteration i: slot i%NS holds tile i widened (its K fragments already in kf); tile i+1 landed or
-    // landing in slot (i+1)%NS, tile i+2 in flight; slot (i+3)%NS is free since the last barrier.
+    // landing in slot (i+1)%NS, tiles i+2 .. i+NS-2 in flight; slot (i+NS-1)%NS, which held tile i-1, is free
+    // since the last barrier.
     const f16x8 ones = {1, 1, 1, 1, 1, 1, 1, 1};
     auto iter = [&](auto nct_c, auto slow_c, int i) {
       constexpr int NCT = decltype(nct_c)::value;
       constexpr bool SLOW = decltype(slow_c)::value != 0;
       constexpr int NC = NCT > 0 ? NCT : 1;
       const int cur = i & (NS - 1), nxt = (i + 1) & (NS - 1);
-      MN_ATT_DMA(i + 3, (i + 3) & (NS - 1))
+      MN_ATT_DMA(i + NS - 1, (i + NS - 1) & (NS - 1))
       f16x8 vf[8];
       if (NCT > 0) {
 #pragma unroll
         for (int u = 0; u < 8; ++u) vf[u] = *reinterpret_cast<const f16x8*>(s_kv + cur * TILE_HALFS + ((8 + u) * 64 + lane) * 8);
       }
       f16_t* const np = my_piece + nxt * TILE_HALFS;
-      wait_vm<8>();  // tile i+1 has landed (tiles i+2 and i+3 may be in flight)
+      wait_vm<4 * (NS - 2)>();  // tile i+1 has landed (the NS-2 tiles behind it may be in flight)
       u32x4 raw[4];
+      const bool widen_next = loader && i < ti_last;  // (wave-uniform; behind the last tile there is nothing to widen)
+      if (widen_next) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) raw[j] = *reinterpret_cast<const u32x4*>(np + j * 4 * 512);
+        for (int j = 0; j < 4; ++j) raw[j] = *reinterpret_cast<const u32x4*>(np + j * 4 * 512);
+      }
       __builtin_amdgcn_sched_barrier(0);
       // first product of column tile 0 beside the widening of tile i+1
       f32x4 S0[NC], S1[NC];
@@ -396,9 +424,9 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, float* __
           S1[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[4 + s], qf[0][s], S1[0], 0, 0, 0);
         }
       }
-      {
+      if (widen_next) {
         f16x8 w[4];
-        widen(raw, w, SLOW, min(i + 1, ti_last));
+        widen(raw, w, SLOW, i + 1);
 #pragma unroll
         for (int j = 0; j < 4; ++j) *reinterpret_cast<f16x8*>(np + j * 4 * 512) = w[j];
       }
@@ -460,7 +488,7 @@ __global__ void __launch_bounds__(256, 2) attn_mfma_kernel(AttnArgs a, float* __
   // ---- output: lane holds O^T[hd = 16u + 4g + i][row = tile*16 + l16]; every lane has its row's sum ----
 #pragma unroll
   for (int ct = 0; ct < CTW; ++ct) {
-    const int tile = tile0 + wave + 4 * ct;
+    const int tile = tile0 + wave + NW * ct;
     const int r = tile * 16 + l16;
     if (tile >= NT16 || r >= R) continue;
     const float l = L[ct][0];
@@ -815,16 +843,19 @@ size_t attention_items_capacity(int B, int M, int H, int Hkv) {
 
 // Shape of the MFMA launch, from what the host knows (largest row count of a sequence, longest context).
 struct MfmaShape {
-  int ctw, n_rg, n_splits, grid_items;
+  int ctw, nw, n_rg, n_splits, grid_items;
 };
 static MfmaShape mfma_shape(const AttnArgs& a) {
   const int G = a.Hkv > 0 ? a.H / a.Hkv : 1;
-  // the kernel covers 4 * CTW column tiles of 16 stacked query rows per workgroup; longer stacks are cut into
+  // the kernel covers NW * CTW column tiles of 16 stacked query rows per workgroup (4 waves with one or two tiles
+  // each, or 5-6 waves with one tile each when that gives every wave the same work); longer stacks are cut into
   // row groups
   const int nt16_max = (G * a.max_q + 15) / 16;
   MfmaShape s;
   s.ctw = nt16_max <= 4 ? 1 : MAX_CT;
-  s.n_rg = (nt16_max + 4 * s.ctw - 1) / (4 * s.ctw);
+  s.nw = 4;
+  if ((nt16_max == 5 || nt16_max == 6) && MN_TUNE("MN_ATTN_NW", 0) != 4) { s.ctw = 1; s.nw = nt16_max; }
+  s.n_rg = (nt16_max + s.nw * s.ctw - 1) / (s.nw * s.ctw);
   s.n_splits = pick_splits(a.max_ctx);
   const size_t bound = (size_t)a.B * s.n_rg * s.n_splits;
   s.grid_items = (int)(bound < a.items_capacity ? bound : a.items_capacity);
@@ -840,7 +871,7 @@ static bool mfma_path(const AttnArgs& a) {
 void launch_attention_plan(const AttnArgs& a, hipStream_t st) {
   if (a.M <= 0 || a.B <= 0 || !mfma_path(a)) return;
   const MfmaShape s = mfma_shape(a);
-  attn_plan_kernel<<<1, 1024, 0, st>>>(a.rows, a.B, a.H / a.Hkv, 4 * s.ctw, s.n_splits, s.grid_items, a.items, a.M,
+  attn_plan_kernel<<<1, 1024, 0, st>>>(a.rows, a.B, a.H / a.Hkv, s.nw * s.ctw, s.n_splits, s.grid_items, a.items, a.M,
                                        a.row_splits);
 }
 
@@ -858,7 +889,8 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
     static std::once_flag attr_once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(attr_once, [] {
-      const void* fns[2] = {reinterpret_cast<const void*>(attn_mfma_kernel<1>), reinterpret_cast<const void*>(attn_mfma_kernel<2>)};
+      const void* fns[4] = {reinterpret_cast<const void*>(attn_mfma_kernel<1, 4>), reinterpret_cast<const void*>(attn_mfma_kernel<2, 4>),
+                            reinterpret_cast<const void*>(attn_mfma_kernel<1, 5>), reinterpret_cast<const void*>(attn_mfma_kernel<1, 6>)};
       for (const void* f : fns) {
         const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) attr_err = e;
@@ -866,8 +898,10 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
     });
     if (attr_err != hipSuccess) return attr_err;
     const unsigned grid = (unsigned)a.Hkv * (unsigned)sh.grid_items;
-    if (sh.ctw == 1) attn_mfma_kernel<1><<<grid, 256, smem, st>>>(a, o_part, ml_part);
-    else attn_mfma_kernel<2><<<grid, 256, smem, st>>>(a, o_part, ml_part);
+    if (sh.nw == 5) attn_mfma_kernel<1, 5><<<grid, 320, smem, st>>>(a, o_part, ml_part);
+    else if (sh.nw == 6) attn_mfma_kernel<1, 6><<<grid, 384, smem, st>>>(a, o_part, ml_part);
+    else if (sh.ctw == 1) attn_mfma_kernel<1, 4><<<grid, 256, smem, st>>>(a, o_part, ml_part);
+    else attn_mfma_kernel<2, 4><<<grid, 256, smem, st>>>(a, o_part, ml_part);
     if (n_splits > 1) {
       const int waves = a.M * a.H;
       attn_merge_kernel<<<(waves + 3) / 4, 256, 0, st>>>(o_part, ml_part, n_splits, a.M, a.H, a.row_splits, reinterpret_cast<f16_t*>(a.out));

@@ -757,6 +757,15 @@ static GemmPlan gemm_plan(int M, int N, int K, int forced_split) {
       best_waves = waves;
     }
   }
+  // Short splits pay more for ramp-up, tail and partial sums than they win: where the plan above cuts k into
+  // pieces of fewer than 24 iterations, one 4-wave workgroup per CU with fewer, longer splits is faster if it
+  // still covers nine CUs in ten (measured at 144 rows on the 10240 x 8192 matrix: 4 waves x 80 column groups
+  // x 3 splits = 240 workgroups take 49.8 us against 52.5 for 5 x 64 x 4, and write a quarter less partial sums)
+  if (!forced_nw && forced_split < 1 && best.split > 1 && (iters + best.split - 1) / best.split < 24) {
+    const int gx4 = (slices + 3) / 4;
+    const int sp4 = 256 / gx4;
+    if (sp4 >= 1 && sp4 < best.split && gx4 * sp4 * 10 >= 256 * 9) best = GemmPlan{4, sp4};
+  }
   return best;
 }
 

@@ -278,14 +278,18 @@ void launch_norm(const NormArgs& a, hipStream_t st) {
 // ------------------------------------------------------------------------------------------
 // rotary embedding + tentative KV append
 // ------------------------------------------------------------------------------------------
-// grid (H + 2 Hkv, M), hd/2 threads: thread t owns the pair (t, t + hd/2) of one head of one row.
+// grid (ceil((H + 2 Hkv) / heads per block), M), 256 threads: a block takes 512 / hd consecutive heads of one row
+// (one-wave blocks were bound by the rate at which workgroups can be dispatched: 11520 of them at the 70B shape);
+// thread (head, t) owns the pair (t, t + hd/2) of its head.
 // TA: activation type of the query buffer; T: storage type of the KV pages
+constexpr int ROPE_THREADS = 256;
 template <typename TA, typename T>
-__global__ void rope_append_kernel(RopeAppendArgs a) {
+__global__ void __launch_bounds__(ROPE_THREADS) rope_append_kernel(RopeAppendArgs a) {
   const int m = blockIdx.y;
-  const int head = blockIdx.x;
-  const int t = threadIdx.x;
   const int hd = a.hd, half = hd >> 1;
+  const int head = blockIdx.x * (ROPE_THREADS / half) + (int)threadIdx.x / half;
+  const int t = (int)threadIdx.x % half;
+  if (head >= a.H + 2 * a.Hkv) return;
   const int ncols = (a.H + 2 * a.Hkv) * hd;
   const int c0 = head * hd + t, c1 = c0 + half;
   float v0 = 0.f, v1 = 0.f;
@@ -350,9 +354,10 @@ __global__ void rope_append_kernel(RopeAppendArgs a) {
 
 void launch_rope_append(const RopeAppendArgs& a, hipStream_t st) {
   if (a.M <= 0) return;
-  dim3 grid(a.H + 2 * a.Hkv, a.M);
-  if (a.dtype == MN_DT_BF16) rope_append_kernel<f16_t, bf16_t><<<grid, a.hd / 2, 0, st>>>(a);
-  else rope_append_kernel<float, float><<<grid, a.hd / 2, 0, st>>>(a);
+  const int per_block = ROPE_THREADS / (a.hd / 2);  // head_dim is one of 8 ... 256: hd/2 divides 256
+  dim3 grid((a.H + 2 * a.Hkv + per_block - 1) / per_block, a.M);
+  if (a.dtype == MN_DT_BF16) rope_append_kernel<f16_t, bf16_t><<<grid, ROPE_THREADS, 0, st>>>(a);
+  else rope_append_kernel<float, float><<<grid, ROPE_THREADS, 0, st>>>(a);
 }
 
 // ------------------------------------------------------------------------------------------
