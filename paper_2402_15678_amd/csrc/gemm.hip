@@ -178,16 +178,26 @@ __global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) ge
         ring0[nt][ks] = *MN_W_PTR(0, nt, ks);
         if constexpr (RD == 2) ring1[nt][ks] = *MN_W_PTR(1, nt, ks);
       }
-    // everything lands before the loop (the two ring slots arrive together with the tile anyway): the
-    // compiler sizes its in-loop waits by the worst path into the loop, and this path is then empty
+    // Everything lands before the loop.  Waiting for the tile and slot 0 only (slot 1 asked for behind slot 0,
+    // at most 8 loads outstanding) would let the first pass overlap with the arrival of slot 1, but the compiler's
+    // wait-count bookkeeping answers loads pending at the loop's entry with an s_waitcnt vmcnt(0) inside the loop
+    // (with or without the register pins below), which drains the load queue on every pass.
     MN_WAIT_VM(0);
     __builtin_amdgcn_s_barrier();
 
 // One iteration on ring slot RING, reading tile CUR and bringing the next tile into NXT.  Issue order
 // matters because loads complete in order: the tile loads go first (L2 hits, needed at the end of this
-// iteration), then, k-step by k-step, the NTW*KS = 8 weight refills for iteration it+2 (HBM, needed two
-// iterations from now).  The compiler-level fence keeps the two groups apart, so "at most 8 outstanding"
-// at the bottom means exactly "the tile has landed" without waiting for any refill.
+// iteration), then the NTW*KS = 8 weight refills for iteration it+RD (HBM, needed two iterations from now).
+// The compiler-level fences keep the groups apart, so "at most 8 outstanding" at the bottom means exactly
+// "the tile has landed" without waiting for any refill.
+// A fragment register is refilled only BEHIND the k-step that multiplies out of it (the refill of k-step ks
+// goes out at the top of k-step ks+1, the last one at the bottom of the iteration): the old value is dead by
+// then, the load can land in the same register, and the ring stays where it is from one pass of the loop to
+// the next.  With the refill issued before its k-step's MFMAs the fragment had to be copied aside first, its
+// registers moved by one set per refill, and the compiler put them back at the loop's back edge with a row of
+// moves behind an s_waitcnt vmcnt(0): a full drain of the load queue every second iteration.
+#define MN_GEMM_REFILL(RING, KS_)                                                                           \
+  _Pragma("unroll") for (int nt = 0; nt < NTW; ++nt) RING[nt][KS_] = *MN_W_PTR(it_ + RD, nt, KS_);
 #define MN_GEMM_ITER(RING, CUR, NXT, IT)                                                                    \
   {                                                                                                         \
     const int it_ = (IT);                                                                                   \
@@ -199,11 +209,7 @@ __global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) ge
     MN_DMA_A(NXT, nxt_)                                                                                     \
     asm volatile("" ::: "memory");                                                                          \
     _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                                     \
-      f16x8 wcur_[NTW];                                                                                     \
-      _Pragma("unroll") for (int nt = 0; nt < NTW; ++nt) {                                                  \
-        wcur_[nt] = __builtin_bit_cast(f16x8, RING[nt][ks]); /* packed weights are fp16 already */           \
-        RING[nt][ks] = *MN_W_PTR(it_ + RD, nt, ks);                                                         \
-      }                                                                                                     \
+      if (ks > 0) MN_GEMM_REFILL(RING, ks - 1)                                                              \
       _Pragma("unroll") for (int grp = 0; grp < 2; ++grp) {                                                 \
         constexpr int G0 = (MT + 1) / 2;                                                                    \
         const int lo_ = grp ? G0 : 0, cnt_ = grp ? MT - G0 : G0;                                            \
@@ -214,11 +220,14 @@ __global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) ge
         _Pragma("unroll") for (int nt = 0; nt < NTW; ++nt)                                                  \
           _Pragma("unroll") for (int i = 0; i < G0; ++i)                                                    \
             if (i < cnt_)                                                                                   \
-              acc[nt][lo_ + i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wcur_[nt], bfrag_[i], acc[nt][lo_ + i], 0, 0, 0); \
+              acc[nt][lo_ + i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(                                    \
+                  __builtin_bit_cast(f16x8, RING[nt][ks]) /* packed weights are fp16 already */, bfrag_[i], \
+                  acc[nt][lo_ + i], 0, 0, 0);                                                               \
         /* scheduling fence after every k-step (after every row-tile group, or none, is the same within noise) */ \
         if (grp == 1) __builtin_amdgcn_sched_barrier(0);                                                    \
       }                                                                                                     \
     }                                                                                                       \
+    MN_GEMM_REFILL(RING, KS - 1)                                                                            \
     MN_WAIT_VM(NTW * KS);                                                                                   \
     __builtin_amdgcn_s_barrier();                                                                           \
   }
@@ -233,6 +242,7 @@ __global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) ge
     }
     if (it < n_iter) MN_GEMM_ITER(ring0, s_a0, s_a1, it)
 #undef MN_GEMM_ITER
+#undef MN_GEMM_REFILL
   }
 #undef MN_DMA_A
 #undef MN_W_PTR
