@@ -759,9 +759,9 @@ static GemmPlan gemm_plan(int M, int N, int K, int forced_split) {
     const int cus = wgs < 256 ? wgs : 256;
     const int waves = (wgs < slots ? wgs : slots) * nw;
     // fewer waves per workgroup only when that puts clearly more CUs (or waves) to work (measured at 144
-    // rows: 224 -> 256 CUs gains nothing on the 57344-column matrix, 160 -> 256 gains 6 % on the
-    // 10240-column one)
-    if (best_cus == 0 || cus * 100 >= best_cus * 115 || (cus >= best_cus && waves * 100 >= best_waves * 115)) {
+    // rows: 224 -> 256 CUs, 8 -> 7 waves, gains 2 % on the 57344-column matrix since the ring keeps its
+    // registers (nothing before); 160 -> 256 gains 6 % on the 10240-column one)
+    if (best_cus == 0 || cus * 100 >= best_cus * 112 || (cus >= best_cus && waves * 100 >= best_waves * 115)) {
       best = GemmPlan{nw, sp};
       best_cus = cus;
       best_waves = waves;
