@@ -164,7 +164,7 @@ extern "C" mn_status mn_set_option(mn_ctx* c, int option, int value) {
 static size_t al(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
-  size_t row_seq, row_j, row_pos, row_tok, seq_row0, seq_ctx, seq_ok, attn_tps, rope_cos, rope_sin;
+  size_t row_seq, row_j, row_pos, row_tok, row_slot, seq_row0, seq_ctx, seq_ok, attn_tps, rope_cos, rope_sin;
   size_t x, h, q, knew, vnew, attn, act, partials, logits, attn_scratch, attn_items, attn_row_splits, total;
   size_t partials_bytes, attn_scratch_bytes, attn_items_capacity;
 };
@@ -174,8 +174,17 @@ static Layout make_layout(const mn_model_desc& d, int B, int M, int max_ctx) {
   const size_t es = d.dtype == MN_DT_BF16 ? 2 : 4;
   const size_t Mr = M > 0 ? M : 1;
   size_t at = 0;
-  auto take = [&](size_t bytes) { size_t o = at; at += al(bytes); return o; };
+  // small arrays are packed at 256 bytes; everything from 64 KB on starts at a 4 KB boundary, so that the place of
+  // the activation buffers and partial sums relative to pages and memory channels does not move with the size of
+  // the bookkeeping in front of them
+  auto take = [&](size_t bytes) {
+    if (bytes >= (64u << 10)) at = (at + 4095) & ~(size_t)4095;
+    size_t o = at;
+    at += al(bytes);
+    return o;
+  };
   L.row_seq = take(Mr * 4); L.row_j = take(Mr * 4); L.row_pos = take(Mr * 4); L.row_tok = take(Mr * 4);
+  L.row_slot = take(Mr * 4);
   L.seq_row0 = take(((size_t)B + 1) * 4); L.seq_ctx = take((size_t)B * 4 + 4); L.seq_ok = take((size_t)B * 4 + 4);
   L.attn_tps = take(4);
   L.rope_cos = take(Mr * (d.head_dim / 2) * 4); L.rope_sin = take(Mr * (d.head_dim / 2) * 4);
@@ -360,6 +369,7 @@ static RowInfo row_info(const Ws& w) {
   r.row_j = w.at<int32_t>(w.L.row_j);
   r.row_pos = w.at<int32_t>(w.L.row_pos);
   r.row_tok = w.at<int32_t>(w.L.row_tok);
+  r.row_slot = w.at<int32_t>(w.L.row_slot);
   r.seq_row0 = w.at<int32_t>(w.L.seq_row0);
   r.seq_ctx = w.at<int32_t>(w.L.seq_ctx);
   r.seq_ok = w.at<int32_t>(w.L.seq_ok);
@@ -385,6 +395,7 @@ static void run_prepare(mn_ctx* c, const Ws& w, const int32_t* last_tok, const i
   p.rope_base = c->d.rope_base;
   p.row_seq = w.at<int32_t>(w.L.row_seq); p.row_j = w.at<int32_t>(w.L.row_j);
   p.row_pos = w.at<int32_t>(w.L.row_pos); p.row_tok = w.at<int32_t>(w.L.row_tok);
+  p.row_slot = w.at<int32_t>(w.L.row_slot);
   p.seq_row0 = w.at<int32_t>(w.L.seq_row0); p.seq_ctx = w.at<int32_t>(w.L.seq_ctx); p.seq_ok = w.at<int32_t>(w.L.seq_ok);
   p.attn_tps = w.at<int32_t>(w.L.attn_tps);
   p.kv_heads = c->d.n_kv_heads;

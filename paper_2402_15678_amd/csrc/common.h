@@ -121,6 +121,7 @@ struct RowInfo {
   const int32_t* row_j;     // [M] offset inside its sequence
   const int32_t* row_pos;   // [M] absolute position ctx_b + j, or -1 when the sequence is disabled
   const int32_t* row_tok;   // [M] input token
+  const int32_t* row_slot;  // [M] where the row's K/V go: physical block * block_size + offset, or -1 (disabled)
   const int32_t* seq_row0;  // [B+1] first row of sequence b
   const int32_t* seq_ctx;   // [B] ctx_b as read at the start of the step (0 for disabled sequences)
   const int32_t* seq_ok;    // [B] 1 = enabled

@@ -31,7 +31,7 @@ struct PrepArgs {
   int max_ctx;       // the host's bound on ctx_b + k_b + 1 (it sized the attention launch)
   int rope_half;     // head_dim/2 for rotary models, 0 otherwise
   float rope_base;
-  int32_t *row_seq, *row_j, *row_pos, *row_tok, *seq_row0, *seq_ctx, *seq_ok;
+  int32_t *row_seq, *row_j, *row_pos, *row_tok, *row_slot, *seq_row0, *seq_ctx, *seq_ok;
   int32_t* attn_tps;           // [1] out: key tiles per attention workgroup (see RowInfo)
   int kv_heads;                // KV heads of the model (the attention grid has one workgroup row per KV head)
   int q_per_kv;                // query heads per KV head (a workgroup covers 128 rows of query position x head)

@@ -83,7 +83,7 @@ __global__ void __launch_bounds__(256) prepare_kernel(PrepArgs a) {
     if (tid == 0 && a.attn_tps) a.attn_tps[0] = 1 << 20;
     for (int b = tid; b <= a.B; b += blockDim.x) a.seq_row0[b] = 0;
     for (int b = tid; b < a.B; b += blockDim.x) { a.seq_ctx[b] = 0; a.seq_ok[b] = 0; }
-    for (int m = tid; m < a.M; m += blockDim.x) { a.row_seq[m] = 0; a.row_j[m] = 0; a.row_pos[m] = -1; a.row_tok[m] = 0; }
+    for (int m = tid; m < a.M; m += blockDim.x) { a.row_seq[m] = 0; a.row_j[m] = 0; a.row_pos[m] = -1; a.row_tok[m] = 0; a.row_slot[m] = -1; }
     return;
   }
   for (int b = tid; b <= a.B; b += blockDim.x) a.seq_row0[b] = s_row0[b];
@@ -97,6 +97,10 @@ __global__ void __launch_bounds__(256) prepare_kernel(PrepArgs a) {
       a.row_seq[r0 + j] = b;
       a.row_j[r0 + j] = j;
       a.row_pos[r0 + j] = ok ? ctx + j : -1;
+      // where the row's K/V are written, looked up once per step instead of once per layer and head
+      a.row_slot[r0 + j] = ok ? a.block_tables[(size_t)b * a.max_blocks_per_seq + (ctx + j) / a.block_size] * a.block_size +
+                                    (ctx + j) % a.block_size
+                              : -1;
       a.row_tok[r0 + j] = (ok && a.last_tok) ? ((j == 0) ? a.last_tok[b] : a.voted[(size_t)b * a.k_max + j - 1]) : 0;
     }
     // key tiles of 32, once per group of 128 (query position x head) rows: the work of the sequence in units of
@@ -290,6 +294,7 @@ __global__ void __launch_bounds__(ROPE_THREADS) rope_append_kernel(RopeAppendArg
   const int head = blockIdx.x * (ROPE_THREADS / half) + (int)threadIdx.x / half;
   const int t = (int)threadIdx.x % half;
   if (head >= a.H + 2 * a.Hkv) return;
+  const int slot = a.rows.row_slot[m];  // (asked for first: the stores at the end wait for nothing else)
   const int ncols = (a.H + 2 * a.Hkv) * hd;
   const int c0 = head * hd + t, c1 = c0 + half;
   float v0 = 0.f, v1 = 0.f;
@@ -329,12 +334,10 @@ __global__ void __launch_bounds__(ROPE_THREADS) rope_append_kernel(RopeAppendArg
     store1<TA>(side + t, v0, bad);
     store1<TA>(side + t + half, v1, bad);
   }
-  const int pos = a.rows.row_pos[m];
-  if (pos < 0) return;  // disabled sequence: nothing is written to the cache (and nothing reported)
-  const int b = a.rows.row_seq[m];
+  if (slot < 0) return;  // disabled sequence: nothing is written to the cache (and nothing reported)
   const int bs = a.kv.block_size;
-  const int pb = a.kv.block_tables[(size_t)b * a.kv.max_blocks_per_seq + pos / bs];
-  const int off = pos % bs;
+  const int pb = slot / bs;
+  const int off = slot % bs;
   if (!is_v) {
     const int kh = head - a.H;
     T* base = reinterpret_cast<T*>(a.kv.k) + ((size_t)pb * a.Hkv + kh) * (size_t)hd * bs;
