@@ -862,7 +862,10 @@ static MfmaShape mfma_shape(const AttnArgs& a) {
   return s;
 }
 static bool mfma_path(const AttnArgs& a) {
+  // (the block-index staging of the longest context must fit the LDS beside the tile ring: about 390 000 tokens;
+  // longer contexts take the generic kernel)
   return attention_mfma_supported(a.H, a.Hkv, a.hd, a.kv.block_size, a.dtype) && a.scratch != nullptr &&
+         mfma_smem_bytes((a.max_ctx + KT - 1) / KT + 1) <= 160 * 1024 &&
          a.scratch_bytes >= attention_scratch_bytes(a.M, a.H, a.hd, a.max_ctx, a.dtype) && a.items != nullptr &&
          a.row_splits != nullptr &&
          a.items_capacity >= attention_items_capacity(a.B, a.M, a.H, a.Hkv);
@@ -883,7 +886,11 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
     const int n_splits = sh.n_splits;
     float* o_part = a.scratch;
     float* ml_part = a.scratch + (size_t)n_splits * a.M * a.H * HD;
-    const int tiles_per_split = ((a.max_ctx + KT - 1) / KT + n_splits - 1) / n_splits + 1;
+    // The block-index staging holds every block of the longest context: how many splits a sequence gets is
+    // decided on the device from the whole batch (a large batch leaves even its longest sequence in one piece), so
+    // a workgroup may have to walk all of a sequence's key tiles.  (Sized for the most splits instead, the array
+    // was too short whenever the device chose fewer, and only the allocation granularity of the LDS covered it.)
+    const int tiles_per_split = (a.max_ctx + KT - 1) / KT + 1;
     const size_t smem = mfma_smem_bytes(tiles_per_split);
     // once per process, whichever thread comes first; a refusal is returned by every call and nothing is launched
     static std::once_flag attr_once;

@@ -174,6 +174,11 @@ def test_proj_gemm_matches_fp64(hb, M, N, K, split):
     ("fewrow-gqa2", synth.ModelDesc(synth.ARCH_LLAMA, synth.DT_BF16, 1, 512, 8, 4, 64, 1024, 64, 4096), [129, 5, 0, 1500], [1, 0, 1, 1]),
     ("fewrow-gqa4", synth.ModelDesc(synth.ARCH_LLAMA, synth.DT_BF16, 1, 512, 8, 2, 64, 1024, 64, 4096), [200, 16, 1], [0, 0, 0]),
     ("hd64-many-rows-generic", synth.LLAMA_160M.with_layers(1), [100, 40], [7, 4]),
+    # many sequences with long contexts: the device leaves every sequence in one KV split (the batch alone fills the
+    # chip), so one workgroup walks all 151 key tiles of its sequence, many more than the most-splits bound the
+    # host could assume
+    ("one-split-long-context", synth.ModelDesc(synth.ARCH_LLAMA, synth.DT_BF16, 1, 1024, 8, 8, 128, 1024, 64, 8192),
+     [4800] * 36 + [4700, 3000, 5000, 4800], [1] * 40),
 ])
 def test_attention_matches_oracle(hb, name, desc, ctx_lens, spec_lens):
     _check_attention(hb, desc, ctx_lens, spec_lens)
@@ -205,7 +210,7 @@ def _check_attention(hb, desc, ctx_lens, spec_lens):
     q = g.standard_normal((M, desc.n_heads, desc.head_dim), dtype=np.float32)
     if desc.dtype == synth.DT_BF16:
         q = q.astype(np.float16).astype(np.float32)                                   # fp16 activations
-    tiny = synth.ModelDesc(desc.arch, desc.dtype, 1, 128, desc.n_heads, desc.n_kv_heads, desc.head_dim, 128, 8, 4096)
+    tiny = synth.ModelDesc(desc.arch, desc.dtype, 1, 128, desc.n_heads, desc.n_kv_heads, desc.head_dim, 128, 8, 8192)
     model = harness.DeviceModel.from_host(tiny, synth.make_weights(tiny, 1))
     kvd = harness.DeviceKV.from_host(desc, kvh)
     kvd.ctx_lens.copy_(torch.from_numpy(kvh.ctx_lens))
