@@ -293,11 +293,14 @@ __global__ void __launch_bounds__(NW * 64, (MT * NTW > 24 || NW > 4) ? 1 : 2) ge
     }
   } else {
     float* o = reinterpret_cast<float*>(out_) + (size_t)split * M * N;
+    // (row tile outside, column tile inside: the wave's two column tiles are the two 64-byte halves of the same
+    // 128-byte lines, and stored back to back they leave the L2 as whole lines; with the column tile outside the
+    // halves were stored far apart and the down projection's 38 MB of partial sums cost 51 MB of HBM writes)
 #pragma unroll
-    for (int nt = 0; nt < NTW; ++nt) {
-      const int n = n_wg + (w4 * NTW + nt) * 16 + g * 4;
+    for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
+      for (int nt = 0; nt < NTW; ++nt) {
+        const int n = n_wg + (w4 * NTW + nt) * 16 + g * 4;
         const int m = m0 + mt * 16 + l16;
         if (m >= M || n >= N) continue;
         f32x4 v = acc[nt][mt];
@@ -571,11 +574,12 @@ __global__ void __launch_bounds__(512, 1) gemm_big_kernel(const f16_t* __restric
     }
   } else {
     float* o = reinterpret_cast<float*>(out_) + (size_t)split * M * N;
+    // (row tile outside, the wave's four column tiles inside: two whole 128-byte lines per row, back to back)
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const int n = n_wg + (wn * 4 + b) * 16 + g * 4;
+    for (int a = 0; a < AT; ++a) {
 #pragma unroll
-      for (int a = 0; a < AT; ++a) {
+      for (int b = 0; b < 4; ++b) {
+        const int n = n_wg + (wn * 4 + b) * 16 + g * 4;
         const int m = m0 + (wm * AT + a) * 16 + l16;
         if (m >= M || n >= N) continue;
         f32x4 v = acc[a][b];
