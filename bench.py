@@ -3,7 +3,7 @@
 
 A step is one pass of the whole path over one batch of synthetic input, everything resident in HBM.
 Default workload: the Llama-2-70B-shaped configuration, batch 16, context 1024, k = 8 (M = 144 scored
-positions), bf16 weights and KV pages, random-init weights, synthetic KV pages and drafts.
+positions), bf16 weights, 16-bit KV pages (bf16-valued draws held as fp16), random-init weights, synthetic KV pages and drafts.
 
 Prints one JSON line: throughput in verified positions/s, the roofline of the dominant kernel (the
 weight-streaming projection GEMM; its device time comes from HIP events the library records around
@@ -469,7 +469,7 @@ def main():
         "metric": "verified_positions_per_sec", "value": M / (ms_per_step * 1e-3), "unit": "positions/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16", "storage_dtype": "bf16 (16 bits per parameter; weights re-encoded as fp16 when packed)",
+        "dtype": "f16", "storage_dtype": "bf16 (16 bits per parameter; weights re-encoded as fp16 when packed, KV pages fp16)",
         "accumulate_dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "arch": "llama" if desc.arch == synth.ARCH_LLAMA else "opt",
                    "n_layers": desc.n_layers, "d_model": desc.d_model, "batch": B, "k_max": k_max, "rows": M,

@@ -74,8 +74,9 @@ enum {
 typedef struct {
   int arch;  /* MN_ARCH_OPT: LayerNorm, biases, ReLU FFN, learned absolute positions, n_kv_heads == n_heads.
                 MN_ARCH_LLAMA: RMSNorm, no biases, SwiGLU FFN, rotary positions, grouped-query attention. */
-  int dtype; /* storage type of matrices, embeddings and KV pages: MN_DT_F32 or MN_DT_BF16.
-                Norm gains/shifts and biases are fp32 in both. */
+  int dtype; /* storage type: MN_DT_F32 (matrices, embeddings and KV pages fp32) or MN_DT_BF16 (matrices and
+                embeddings given as bf16; KV pages 16 bits per element too, in the fp16 encoding the library's
+                products run in, see mn_kv).  Norm gains/shifts and biases are fp32 in both. */
   int n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
   int max_pos;     /* rows of pos_emb (OPT); upper bound on ctx_b + k_b + 1 in either arch */
   float norm_eps;  /* inside the square root of both norms */
@@ -104,7 +105,10 @@ typedef struct {
 
 /* Paged KV cache (section 4: every cached token is addressed by a logical block id and an
  * offset).  Token p of sequence b is in physical block block_tables[b][p / block_size] at offset
- * p % block_size.  Per layer, in the model's storage type:
+ * p % block_size.  Per layer, fp32 in MN_DT_F32 models and IEEE fp16 in MN_DT_BF16 models (the cache is the
+ * library's own state: it writes the rows and reads them back, and fp16 is what its matrix instructions multiply;
+ * a bf16 value whose magnitude lies in [2^-14, 65504] is the same number in fp16, three mantissa bits to spare,
+ * so a caller holding bf16 rows converts them without loss):
  *   K pages [num_blocks][n_kv_heads][head_dim/8][block_size][8]   (8 consecutive head-dim
  *                                                                  elements of one token together)
  *   V pages [num_blocks][n_kv_heads][head_dim][block_size]        (one head-dim element of the
@@ -128,17 +132,6 @@ typedef struct {
  * a failed create leaves a message retrievable through mn_last_error(NULL). */
 mn_status mn_create(mn_ctx **out, const mn_model_desc *desc, const mn_weights *weights);
 void mn_destroy(mn_ctx *ctx);
-
-/* Options of a context (off unless set).
- * MN_OPT_STEP_KV_FROM_CACHE (bf16 models; value 0 or 1): where the attention of mn_verify_forward takes the K/V
- *   rows of the positions the same call scores.  0, the default: from an fp16 copy kept for the length of the call
- *   (the cache gets them rounded to bf16 all the same): closest to the exact result.  1: from the cache, in the
- *   cache's precision, which is where every later call finds them: scoring k + 1 positions in one pass then
- *   multiplies exactly the numbers that k + 1 single-position calls multiply (section 2.1: the LLM scores the
- *   speculated tokens "in parallel" with the same outcome as one by one), at the price of the storage rounding
- *   of those rows (2^-9 relative instead of 2^-12) in this call's own scores. */
-enum { MN_OPT_STEP_KV_FROM_CACHE = 1 };
-mn_status mn_set_option(mn_ctx *ctx, int option, int value);
 
 /* Message of the last failed call on ctx (or of the last failed mn_create when ctx is NULL).
  * The string is owned by the library and valid until the next failing call on the same ctx. */
@@ -205,11 +198,13 @@ mn_status mn_mv_vote(mn_ctx *ctx, const int32_t *drafts, const int32_t *spec_len
  * Arithmetic: fp32 residual stream, norm statistics, softmax and logits in both storage types.
  * With MN_DT_BF16 the weights are given as bf16 and re-encoded as fp16 by mn_pack_weight (same 16 bits
  * per parameter; exact for magnitudes in [2^-14, 65504], the range weights live in), cache entries
- * are bf16 in memory and are widened exactly to fp16 on their way to the MFMA; the activations fed to
- * the matrix products (norm outputs, queries, softmax
+ * are fp16; the activations fed to the matrix products (norm outputs, queries, softmax
  * probabilities, attention outputs, FFN activations) are rounded to fp16 (round-to-nearest-even)
  * and the products run on the fp16 MFMA with fp32 accumulation.  New K/V rows are rounded to
- * bf16 when they are written to the cache.
+ * fp16 when they are written to the cache, and the attention of the same call reads them from there, as
+ * every later call does: scoring k + 1 positions in one pass multiplies exactly the numbers that k + 1
+ * single-position calls multiply (section 2.1: the LLM scores the speculated tokens in parallel with the
+ * outcome of scoring them one by one); what is left between the two is the order of the fp32 sums.
  * Range of the fp16 stages: every such activation (and every K/V row written to the cache) is saturated to
  * +-65504 instead of overflowing to infinity, and MN_DEV_RANGE is set in *dev_status when that happens
  * (with N(0, 0.02)-initialised or trained weights these values stay below 10^2).  Cache entries the caller

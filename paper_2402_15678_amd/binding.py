@@ -21,9 +21,8 @@ MN_DEV_BLOCK_TABLE, MN_DEV_SPEC_LEN, MN_DEV_TOKEN, MN_DEV_DRAFTS, MN_DEV_RANGE, 
 MN_MAX_DRAFTS, MN_MAX_BATCH, MN_MAX_SPLIT_K = 64, 4096, 16
 MN_NOALLOC_SCRATCH_BYTES = 32 << 20
 
-MN_OPT_STEP_KV_FROM_CACHE = 1
 
-EXPORTS = ("mn_create", "mn_destroy", "mn_set_option", "mn_last_error", "mn_status_str", "mn_workspace_bytes", "mn_mv_vote",
+EXPORTS = ("mn_create", "mn_destroy", "mn_last_error", "mn_status_str", "mn_workspace_bytes", "mn_mv_vote",
            "mn_verify_forward", "mn_accept_and_commit", "mn_proj_gemm", "mn_proj_gemm_noalloc", "mn_attention", "mn_profile_enable",
            "mn_profile_collect", "mn_packed_weight_bytes", "mn_pack_weight", "mn_acr_update",
            "mn_verify_sample", "mn_draft_sample",
@@ -61,8 +60,6 @@ def _load() -> C.CDLL:
     vp, i32, sz = C.c_void_p, C.c_int, C.c_size_t
     lib.mn_create.restype = i32
     lib.mn_create.argtypes = [C.POINTER(vp), C.POINTER(ModelDesc), C.POINTER(Weights)]
-    lib.mn_set_option.restype = i32
-    lib.mn_set_option.argtypes = [vp, i32, i32]
     lib.mn_destroy.restype = None
     lib.mn_destroy.argtypes = [vp]
     lib.mn_last_error.restype = C.c_char_p
@@ -151,8 +148,6 @@ def mn_create(desc: ModelDesc, weights: Weights) -> int:
     return out.value
 
 
-def mn_set_option(ctx: int, option: int, value: int) -> None:
-    _check(lib.mn_set_option(ctx, option, value), ctx)
 
 
 def mn_destroy(ctx: Optional[int]) -> None:

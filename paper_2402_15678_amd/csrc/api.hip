@@ -45,7 +45,6 @@ struct Tap {  // RAII bracket around one launch
 
 struct mn_ctx {
   mn_model_desc d;
-  bool step_kv_from_cache = false;  // MN_OPT_STEP_KV_FROM_CACHE
   Prof prof;
   const void *tok_emb, *pos_emb, *final_norm_g, *final_norm_b, *lm_head;
   std::vector<const void*> ln1_g, ln1_b, wqkv, bqkv, wo, bo, ln2_g, ln2_b, w1, b1, w2, b2;
@@ -149,23 +148,12 @@ extern "C" mn_status mn_create(mn_ctx** out, const mn_model_desc* d, const mn_we
 
 extern "C" void mn_destroy(mn_ctx* ctx) { delete ctx; }
 
-extern "C" mn_status mn_set_option(mn_ctx* c, int option, int value) {
-  if (!c) return MN_ENULL;
-  switch (option) {
-    case MN_OPT_STEP_KV_FROM_CACHE:
-      if (value != 0 && value != 1) return fail(c, MN_EINVAL, "mn_set_option: MN_OPT_STEP_KV_FROM_CACHE takes 0 or 1, got %d", value);
-      c->step_kv_from_cache = value != 0;
-      return MN_OK;
-  }
-  return fail(c, MN_EINVAL, "mn_set_option: unknown option %d", option);
-}
-
 // ---- workspace layout ---------------------------------------------------------------------------
 static size_t al(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
   size_t row_seq, row_j, row_pos, row_tok, row_slot, seq_row0, seq_ctx, seq_ok, attn_tps, rope_cos, rope_sin;
-  size_t x, h, q, knew, vnew, attn, act, partials, logits, attn_scratch, attn_items, attn_row_splits, total;
+  size_t x, h, q, attn, act, partials, logits, attn_scratch, attn_items, attn_row_splits, total;
   size_t partials_bytes, attn_scratch_bytes, attn_items_capacity;
 };
 
@@ -191,8 +179,6 @@ static Layout make_layout(const mn_model_desc& d, int B, int M, int max_ctx) {
   L.x = take(Mr * d.d_model * 4);
   L.h = take(Mr * d.d_model * es);
   L.q = take(Mr * d.n_heads * d.head_dim * es);
-  L.knew = take(Mr * d.n_kv_heads * d.head_dim * es);
-  L.vnew = take(Mr * d.n_kv_heads * d.head_dim * es);
   L.attn = take(Mr * d.n_heads * d.head_dim * es);
   L.act = take(Mr * d.d_ffn * es);
   // Partial sums of the widest projection at the largest split it can get with M rows OR FEWER: a workspace
@@ -483,15 +469,9 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
     r.rows = rows;
     r.kv = KvView{kv->k_layers[l], kv->v_layers[l], kv->block_tables, kv->block_size, kv->num_blocks, kv->max_blocks_per_seq};
     r.q = w.at<void>(w.L.q);
-    // bf16 models keep this step's K/V rows in fp16 beside the bf16 cache for the step's own attention.  Reading
-    // them back from the cache instead (MN_OPT_STEP_KV_FROM_CACHE; later steps must anyway) makes one pass over
-    // k + 1 positions multiply exactly the numbers k + 1 single-position passes multiply, but the storage
-    // rounding of the new rows (2^-9 against 2^-12) then triples the step's distance from the exact result
-    // (measured at the 70B width, one layer: max |dlogit| 4.7e-2 against 1.7e-2), because with freshly
-    // initialised weights a row's own keys carry much of its attention weight.
-    const bool side = d.dtype == MN_DT_BF16 && !c->step_kv_from_cache;
-    r.knew = side ? w.at<void>(w.L.knew) : nullptr;
-    r.vnew = side ? w.at<void>(w.L.vnew) : nullptr;
+    // (the K/V rows of the scored tokens go to the pages in the precision the step's own attention reads them
+    // back in, and every later step after it: one pass over k + 1 positions multiplies exactly the numbers k + 1
+    // single-position passes multiply)
     r.M = M; r.H = d.n_heads; r.Hkv = d.n_kv_heads; r.hd = d.head_dim; r.dtype = d.dtype;
     r.dev_status = dev_status;
     {
@@ -500,7 +480,6 @@ extern "C" mn_status mn_verify_forward(mn_ctx* c, const int32_t* last_tok, const
     }
     AttnArgs at{};
     at.q = r.q; at.out = w.at<void>(w.L.attn); at.rows = rows; at.kv = r.kv;
-    at.knew = r.knew; at.vnew = r.vnew;
     at.B = B; at.M = M; at.H = d.n_heads; at.Hkv = d.n_kv_heads; at.hd = d.head_dim; at.dtype = d.dtype;
     at.max_ctx = max_ctx; at.max_q = max_q;
     at.scratch = w.at<float>(w.L.attn_scratch); at.scratch_bytes = w.L.attn_scratch_bytes;

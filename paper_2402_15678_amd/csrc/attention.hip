@@ -2,15 +2,18 @@
 // extended to more than one input token per sequence once a cache exists).  Query row j of
 // sequence b sees the cached keys [0, ctx_b) and the new keys 0..j of its own sequence.
 //
+// The keys and values of the scored tokens themselves are in the pages already: the tentative append
+// (rope_append_kernel) runs before attention, so the kernels here read nothing but pages.
+//
 // Three kernels:
-//  * attn_mfma_kernel  bf16 pages / fp16 queries, head_dim 128, 16-token blocks.  The G*q_b query rows that share one
+//  * attn_mfma_kernel  fp16 pages / fp16 queries, head_dim 128, 16-token blocks.  The G*q_b query rows that share one
 //    KV head (grouped-query attention stacks the group's heads on top of the speculated tokens)
 //    are the column index of every MFMA, so each K/V byte is read once per KV head.  Key tiles go
-//    HBM -> LDS by direct loads, are widened in place (bf16 to fp16, exact) and feed the MFMAs of all
-//    four waves: the page layouts put 8 consecutive contraction elements in 16 bytes for both
+//    HBM -> LDS by direct loads, already in the operand order of the MFMAs of all the
+//    waves: the page layouts put 8 consecutive contraction elements in 16 bytes for both
 //    products (head-dim chunks for K, tokens for V).  The KV range of a sequence is split across
 //    workgroups; partial (max, sum, output) triples are merged by attn_merge_kernel.
-//  * attn_fewrow_kernel  bf16 pages / fp16 queries, head_dim 64, at most 4 stacked query rows per KV head
+//  * attn_fewrow_kernel  fp16 pages / fp16 queries, head_dim 64, at most 4 stacked query rows per KV head
 //    (a small drafting model decoding token by token): wide loads, plain FMA.
 //  * attn_generic_kernel  any storage type / head_dim / block size; plain FMA, one (row, head)
 //    per workgroup.  Used by the fp32 model and as the fallback.
@@ -45,9 +48,6 @@ __global__ void __launch_bounds__(GEN_THREADS) attn_generic_kernel(AttnArgs a) {
     return;
   }
   const int nkeys = pos + 1;
-  const int ctx = a.rows.seq_ctx[b], row0 = a.rows.seq_row0[b];
-  const TA* Kn = reinterpret_cast<const TA*>(a.knew);
-  const TA* Vn = reinterpret_cast<const TA*>(a.vnew);
   const int kh = h / (a.H / a.Hkv);
   const float scale = rsqrtf((float)hd);
   const TA* q = reinterpret_cast<const TA*>(a.q) + ((size_t)m * a.H + h) * hd;
@@ -67,16 +67,11 @@ __global__ void __launch_bounds__(GEN_THREADS) attn_generic_kernel(AttnArgs a) {
       pb = bt[key / bs];
       const int off = key % bs;
       float d = 0.f;
-      if (Kn && key >= ctx) {
-        const TA* kk = Kn + ((size_t)(row0 + key - ctx) * a.Hkv + kh) * hd;
-        for (int e = 0; e < hd; ++e) d = fmaf(s_q[e], Store<TA>::load(kk + e), d);
-      } else {
-        const T* kb = Kp + ((size_t)pb * a.Hkv + kh) * (size_t)hd * bs;
-        for (int c = 0; c < hd / 8; ++c) {
-          const T* kk = kb + ((size_t)c * bs + off) * 8;
+      const T* kb = Kp + ((size_t)pb * a.Hkv + kh) * (size_t)hd * bs;
+      for (int c = 0; c < hd / 8; ++c) {
+        const T* kk = kb + ((size_t)c * bs + off) * 8;
 #pragma unroll
-          for (int i = 0; i < 8; ++i) d = fmaf(s_q[c * 8 + i], Store<T>::load(kk + i), d);
-        }
+        for (int i = 0; i < 8; ++i) d = fmaf(s_q[c * 8 + i], Store<T>::load(kk + i), d);
       }
       s = d;
     }
@@ -99,14 +94,8 @@ __global__ void __launch_bounds__(GEN_THREADS) attn_generic_kernel(AttnArgs a) {
     if (kg < ng) {
       for (int i = kg; i < cnt; i += ng) {
         const int key2 = k0 + i;
-        float v;
-        if (Vn && key2 >= ctx) {
-          v = Store<TA>::load(Vn + ((size_t)(row0 + key2 - ctx) * a.Hkv + kh) * hd + e_own);
-        } else {
-          const T* vb = Vp + ((size_t)s_pb[i] * a.Hkv + kh) * (size_t)hd * bs;
-          v = Store<T>::load(vb + (size_t)e_own * bs + key2 % bs);
-        }
-        acc = fmaf(s_p[i], v, acc);
+        const T* vb = Vp + ((size_t)s_pb[i] * a.Hkv + kh) * (size_t)hd * bs;
+        acc = fmaf(s_p[i], Store<T>::load(vb + (size_t)e_own * bs + key2 % bs), acc);
       }
     }
     __syncthreads();
@@ -121,7 +110,7 @@ __global__ void __launch_bounds__(GEN_THREADS) attn_generic_kernel(AttnArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
-// MFMA kernel (bf16 pages, fp16 queries, head_dim 128, block 16)
+// MFMA kernel (fp16 pages, fp16 queries, head_dim 128, block 16)
 // ------------------------------------------------------------------------------------------
 // Workgroup (4 waves) = one (KV head, sequence, row group, KV split).  The R = G*q_b query rows that share the
 // KV head are cut into 16-row column tiles; wave w owns tiles w, w+4, (w+8) and keeps their query
@@ -134,21 +123,19 @@ __global__ void __launch_bounds__(GEN_THREADS) attn_generic_kernel(AttnArgs a) {
 //
 // Data path of a key tile (32 keys = two blocks, 16 KB): HBM -> LDS by direct loads (no staging
 // registers) into one of NS slots, already in MFMA fragment order (a wave load drops lane i's 16 bytes
-// at slot base + 16 i, so lane i asks for the piece that belongs there); the wave that brought a
-// fragment in widens it in place from bf16 to fp16 (both are two bytes); after a barrier every wave's
-// MFMAs read it.  Three tiles are in flight or landed ahead of the one being multiplied, and the loads
-// of tile i+3 are issued before the wait for tile i+1, so the memory queue never runs dry while the
-// waves wait for one another.
+// at slot base + 16 i, so lane i asks for the piece that belongs there); after the issuing waves' wait and
+// a barrier every wave's MFMAs read it as it came.  Three tiles are in flight or landed ahead of the one being
+// multiplied, and the loads of tile i+3 are issued before the wait for tile i+1, so the memory queue never runs
+// dry while the waves wait for one another.
 //
 // The kernel is bound by instruction issue and LDS latency, not by HBM, at 128 query rows per KV head,
-// hence: tiles that lie wholly inside the cached context take a branch-free body (no mask, no
-// patching); the accumulators of the first product start at minus the running reference, so the
+// hence: tiles that lie wholly inside the cached context take a branch-free body (no mask);
+// the accumulators of the first product start at minus the running reference, so the
 // scores come out already shifted; the reference moves lazily; the row sums are one more MFMA with
 // an all-ones operand (they add exactly the fp16 probabilities the second product uses, and need no
 // cross-lane reduction); the K fragments of the next tile and the V fragments of this one are read
 // into registers early, and the phases are ordered so that every batch of MFMAs has independent
-// vector work beside it (widening beside the first product of column tile 0, the softmax of tile
-// ct beside the products of its neighbour).
+// vector work beside it (the softmax of tile ct beside the products of its neighbour).
 constexpr int HD = 128;
 constexpr int BS = 16;
 constexpr int KT = 32;                         // keys per tile (two blocks)
@@ -286,8 +273,6 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) attn_mfma_kernel(Att
     }
   }
 
-  const f16_t* Kn = reinterpret_cast<const f16_t*>(a.knew);
-  const f16_t* Vn = reinterpret_cast<const f16_t*>(a.vnew);
   // Loader role of this thread: the pieces of its own lane in K fragments (t = 0, 1; head-dim step s = wave)
   // and V fragments (u = wave, wave + 4).  K: S^T row l16 = 4g'+r of half t <-> key 8g' + 4t + r of the
   // tile, head-dim chunk 4*wave + g (t = 1: +64 bytes).  V: head-dim row 16u + l16, keys 8g..8g+7
@@ -295,15 +280,14 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) attn_mfma_kernel(Att
   const int kkey0 = 8 * (l16 >> 2) + (l16 & 3);  // key inside the tile for t = 0 (t = 1: + 4)
   const int kchunk = 4 * wave + g;
   const int ksel = l16 >> 3, vsel = g >> 1;      // which of the tile's two blocks the pieces live in
-  const uint32_t blk_bytes = (uint32_t)a.Hkv * (HD * BS) * (uint32_t)sizeof(bf16_t);
+  const uint32_t blk_bytes = (uint32_t)a.Hkv * (HD * BS) * (uint32_t)sizeof(f16_t);
   const uint32_t blk_last = (uint32_t)max(a.kv.num_blocks - 1, 0);
-  const size_t head_bytes = (size_t)kvh * (HD * BS) * sizeof(bf16_t);
-  const char* kbase = reinterpret_cast<const char*>(a.kv.k) + head_bytes + ((size_t)kchunk * BS + (kkey0 & (BS - 1))) * 8 * sizeof(bf16_t);
-  const char* vbase = reinterpret_cast<const char*>(a.kv.v) + head_bytes + ((size_t)(16 * wave + l16) * BS + 8 * (g & 1)) * sizeof(bf16_t);
+  const size_t head_bytes = (size_t)kvh * (HD * BS) * sizeof(f16_t);
+  const char* kbase = reinterpret_cast<const char*>(a.kv.k) + head_bytes + ((size_t)kchunk * BS + (kkey0 & (BS - 1))) * 8 * sizeof(f16_t);
+  const char* vbase = reinterpret_cast<const char*>(a.kv.v) + head_bytes + ((size_t)(16 * wave + l16) * BS + 8 * (g & 1)) * sizeof(f16_t);
   // LDS byte address of fragment `wave` of slot 0 (wave-uniform)
   const uint32_t lds_w = __builtin_amdgcn_readfirstlane(
       (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem + (uint32_t)wave * 1024u);
-  f16_t* const my_piece = s_kv + (wave * 64 + lane) * 8;  // this thread's piece of fragment `wave` in slot 0
   __syncthreads();  // block indices are in LDS; every load issued so far has been consumed
 
   if (ok && n_my > 0) {
@@ -321,75 +305,20 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) attn_mfma_kernel(Att
     dma16<0>(vp_, l_ + 8 * 1024);                                                                 \
     dma16<64 * BS * 2>(vp_, l_ + 12 * 1024);                                                      \
   }
-    // this thread's four raw pieces of slot SLOT, widened; SLOW: the tile may reach past ctx, then this
-    // step's own keys come from the fp16 side buffers and V slots past the sequence end are zeroed (stale
-    // slots may hold anything: 0 * garbage must stay 0; garbage scores are masked)
-    auto widen = [&](const u32x4 (&raw)[4], f16x8 (&w)[4], bool slow, int ti) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) w[i] = bf16x8_to_f16x8(raw[i]);
-      if (slow) {
-        const int key0 = (t_begin + ti) * KT;
-        if (key0 + KT > ctx) {
-          // This step's own keys.  Every load goes out first, from a row that exists whether or not the key does
-          // (clamped), and the selection follows: one memory round trip per tile.  Loads inside the conditions were
-          // a chain of eighteen dependent round trips, 6 us per tile, and the split that holds the new keys set
-          // the length of the whole launch.
-          f16x8 kn[2];
-          f16_t vn[2][8];
-          if (Kn) {
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-              const int r = min(max(key0 + kkey0 + 4 * t - ctx, 0), qb - 1);
-              kn[t] = *reinterpret_cast<const f16x8*>(Kn + ((size_t)(row0 + r) * a.Hkv + kvh) * HD + kchunk * 8);
-            }
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-              const int hd = 16 * (wave + 4 * i) + l16;
-#pragma unroll
-              for (int e = 0; e < 8; ++e) {
-                const int r = min(max(key0 + 8 * g + e - ctx, 0), qb - 1);
-                vn[i][e] = Vn[((size_t)(row0 + r) * a.Hkv + kvh) * HD + hd];
-              }
-            }
-          }
-#pragma unroll
-          for (int t = 0; t < 2; ++t) {
-            const int key = key0 + kkey0 + 4 * t;
-            if (Kn && key >= ctx && key < nkeys) w[t] = kn[t];
-          }
-#pragma unroll
-          for (int i = 0; i < 2; ++i) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-              const int key = key0 + 8 * g + e;
-              if (key >= nkeys) w[2 + i][e] = (f16_t)0.f;
-              else if (Vn && key >= ctx) w[2 + i][e] = vn[i][e];
-            }
-          }
-        }
-      }
-    };
     f16x8 kf[8];  // K fragments of the tile about to be multiplied
-    // prologue: tiles 0 .. NS-2 on their way; tile 0 widened and its K fragments in registers
+    // prologue: tiles 0 .. NS-2 on their way; tile 0 landed and its K fragments in registers
 #pragma unroll
     for (int t = 0; t < NS - 1; ++t) MN_ATT_DMA(t, t)
     wait_vm<4 * (NS - 2)>();
-    if (loader) {
-      u32x4 raw[4];
-      f16x8 w[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) raw[i] = *reinterpret_cast<const u32x4*>(my_piece + i * 4 * 512);
-      widen(raw, w, true, 0);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) *reinterpret_cast<f16x8*>(my_piece + i * 4 * 512) = w[i];
-    }
     __syncthreads();
 #pragma unroll
     for (int f = 0; f < 8; ++f) kf[f] = *reinterpret_cast<const f16x8*>(s_kv + (f * 64 + lane) * 8);
 
-    // Iteration i: slot i%NS holds tile i widened (its K fragments already in kf); tile i+1 landed or
+    // Iteration i: slot i%NS holds tile i (its K fragments already in kf); tile i+1 landed or
     // landing in slot (i+1)%NS, tiles i+2 .. i+NS-2 in flight; slot (i+NS-1)%NS, which held tile i-1, is free
-    // since the last barrier.
+    // since the last barrier.  SLOW: the tile reaches past ctx: the scores are masked (causal order among
+    // the scored tokens, keys past the sequence end), and the V slots past the sequence end, which may hold anything
+    // (0 * garbage must stay 0), are read as zeros.
     const f16x8 ones = {1, 1, 1, 1, 1, 1, 1, 1};
     auto iter = [&](auto nct_c, auto slow_c, int i) {
       constexpr int NCT = decltype(nct_c)::value;
@@ -402,16 +331,18 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) attn_mfma_kernel(Att
 #pragma unroll
         for (int u = 0; u < 8; ++u) vf[u] = *reinterpret_cast<const f16x8*>(s_kv + cur * TILE_HALFS + ((8 + u) * 64 + lane) * 8);
       }
-      f16_t* const np = my_piece + nxt * TILE_HALFS;
-      wait_vm<4 * (NS - 2)>();  // tile i+1 has landed (the NS-2 tiles behind it may be in flight)
-      u32x4 raw[4];
-      const bool widen_next = loader && i < ti_last;  // (wave-uniform; behind the last tile there is nothing to widen)
-      if (widen_next) {
+      if (SLOW && NCT > 0) {
+        const int past = (t_begin + i) * KT + 8 * g + 8 - nkeys;  // how many of this lane's 8 keys lie past the end
+        if (past > 0) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) raw[j] = *reinterpret_cast<const u32x4*>(np + j * 4 * 512);
+          for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              if (e >= 8 - past) vf[u][e] = (f16_t)0.f;
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
-      // first product of column tile 0 beside the widening of tile i+1
+      // first product of column tile 0
       f32x4 S0[NC], S1[NC];
       f16x8 P[NC];
       const int keyg = (t_begin + i) * KT + 8 * g;
@@ -423,12 +354,6 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) attn_mfma_kernel(Att
           S0[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[s], qf[0][s], S0[0], 0, 0, 0);
           S1[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[4 + s], qf[0][s], S1[0], 0, 0, 0);
         }
-      }
-      if (widen_next) {
-        f16x8 w[4];
-        widen(raw, w, SLOW, i + 1);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) *reinterpret_cast<f16x8*>(np + j * 4 * 512) = w[j];
       }
       __builtin_amdgcn_sched_barrier(0);
       // first product of column tile ct beside the softmax of tile ct-1
@@ -444,7 +369,9 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) attn_mfma_kernel(Att
         P[ct - 1] = softmax_tile<SLOW>(S0[ct - 1], S1[ct - 1], run_m[ct - 1], negm4[ct - 1], thr[ct - 1], O[ct - 1], L[ct - 1], keyg, lim[ct - 1]);
         __builtin_amdgcn_sched_barrier(0);
       }
-      // every LDS read of tile i has been issued and tile i+1 is widened: hand over
+      // every LDS read of tile i has been issued; tile i+1 has landed once every loader's own wait is over
+      // (the NS-2 tiles behind it may stay in flight): hand over
+      wait_vm<4 * (NS - 2)>();
       __syncthreads();
 #pragma unroll
       for (int f = 0; f < 8; ++f) kf[f] = *reinterpret_cast<const f16x8*>(s_kv + nxt * TILE_HALFS + (f * 64 + lane) * 8);
@@ -464,9 +391,8 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) attn_mfma_kernel(Att
         L[NCT - 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones, P[NCT - 1], L[NCT - 1], 0, 0, 0);
       }
     };
-    // fast iterations: tiles i and i+1 lie wholly below ctx
-    const int n_clean = min(n_my, max(0, ctx / KT - t_begin));
-    const int n_fast = max(0, n_clean - 1);
+    // fast iterations: tiles that lie wholly below ctx
+    const int n_fast = min(n_my, max(0, ctx / KT - t_begin));
     int i = 0;
     if (nct == CTW) {
       for (; i < n_fast; ++i) iter(IntC<CTW>{}, IntC<0>{}, i);
@@ -546,7 +472,7 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(const float* __restrict
 }
 
 // ------------------------------------------------------------------------------------------
-// few-row kernel (bf16 pages, fp16 queries, head_dim 64, 16-token blocks, at most 4 stacked rows per KV head)
+// few-row kernel (fp16 pages, fp16 queries, head_dim 64, 16-token blocks, at most 4 stacked rows per KV head)
 // ------------------------------------------------------------------------------------------
 // The shape of a small model decoding one token per sequence (the SSMs that draft for the vote): one or
 // a few query rows against the whole context.  There is nothing for a matrix instruction to share, the
@@ -559,12 +485,12 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(const float* __restrict
 //  * softmax: running maximum per wave (log2 units), per-lane partial sums of the probabilities;
 //  * V: lane = head dimension; the 64 probabilities go through LDS (read back as broadcasts) and meet
 //    the 16 tokens x 4 blocks of that dimension (32 contiguous bytes per block).
-// This step's own keys (side buffers) are added by wave 0 one by one; the waves' (max, sum, output)
-// are merged through LDS.
+// The waves' (max, sum, output) are merged through LDS.
 constexpr int FR_HD = 64;
 
-__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+// the two fp16 values of a 32-bit word of a page
+__device__ __forceinline__ float h_lo(uint32_t w) { return (float)__builtin_bit_cast(f16x2, w)[0]; }
+__device__ __forceinline__ float h_hi(uint32_t w) { return (float)__builtin_bit_cast(f16x2, w)[1]; }
 
 template <int RR, int FR_NW>  // rows held, waves per workgroup
 __global__ void __launch_bounds__(FR_NW * 64) attn_fewrow_kernel(AttnArgs a) {
@@ -588,13 +514,10 @@ __global__ void __launch_bounds__(FR_NW * 64) attn_fewrow_kernel(AttnArgs a) {
     return;
   }
   const f16_t* Q = reinterpret_cast<const f16_t*>(a.q);
-  const f16_t* Kn = reinterpret_cast<const f16_t*>(a.knew);
-  const f16_t* Vn = reinterpret_cast<const f16_t*>(a.vnew);
-  const int n_pk = Kn ? ctx : ctx + qb;      // keys that live in the pages
+  const int n_pk = ctx + qb;                 // the cached keys and this step's own
   const float sscale = rsqrtf((float)FR_HD) * LOG2E;
 
   float qf[RR][16];   // q of row r, head-dim chunks g and g + 4 (the lane's share of a dot product)
-  float qe[RR];       // q of row r, head dimension `lane`
   float m[RR], l[RR], acc[RR];
   int lim[RR];        // keys [0, lim) of the pages are visible to row r
 #pragma unroll
@@ -602,7 +525,6 @@ __global__ void __launch_bounds__(FR_NW * 64) attn_fewrow_kernel(AttnArgs a) {
     m[r] = -INFINITY;
     l[r] = 0.f;
     acc[r] = 0.f;
-    qe[r] = 0.f;
     lim[r] = 0;
 #pragma unroll
     for (int i = 0; i < 16; ++i) qf[r][i] = 0.f;
@@ -615,7 +537,6 @@ __global__ void __launch_bounds__(FR_NW * 64) attn_fewrow_kernel(AttnArgs a) {
         qf[r][i] = (float)p0[i] * sscale;
         qf[r][8 + i] = (float)p1[i] * sscale;
       }
-      qe[r] = (float)qp[lane] * sscale;
       lim[r] = min(n_pk, ctx + r / G + 1);
     }
   }
@@ -623,9 +544,9 @@ __global__ void __launch_bounds__(FR_NW * 64) attn_fewrow_kernel(AttnArgs a) {
   const int32_t* bt = a.kv.block_tables + (size_t)b * a.kv.max_blocks_per_seq;
   const int last_blk = max(0, (n_pk - 1) / BS);
   const uint32_t blk_last = (uint32_t)max(a.kv.num_blocks - 1, 0);
-  const size_t head_stride = (size_t)FR_HD * BS * sizeof(bf16_t);  // one (block, KV head) of K or of V
+  const size_t head_stride = (size_t)FR_HD * BS * sizeof(f16_t);  // one (block, KV head) of K or of V
   const char* Kb = reinterpret_cast<const char*>(a.kv.k) + (size_t)kvh * head_stride + (size_t)(g * BS + t) * 16;
-  const char* Vb = reinterpret_cast<const char*>(a.kv.v) + (size_t)kvh * head_stride + (size_t)lane * (BS * sizeof(bf16_t));
+  const char* Vb = reinterpret_cast<const char*>(a.kv.v) + (size_t)kvh * head_stride + (size_t)lane * (BS * sizeof(f16_t));
   const int n_steps = (n_pk + 63) >> 6;
   for (int s = wave; s < n_steps; s += FR_NW) {
     uint4 kp[4][2], vp[4][2];
@@ -638,6 +559,20 @@ __global__ void __launch_bounds__(FR_NW * 64) attn_fewrow_kernel(AttnArgs a) {
       vp[i][0] = *reinterpret_cast<const uint4*>(Vb + off);
       vp[i][1] = *reinterpret_cast<const uint4*>(Vb + off + 16);
     }
+    if ((s + 1) * 64 > n_pk) {               // (wave-uniform) V slots past the sequence end may hold anything, and
+#pragma unroll                               // 0 * garbage must stay 0: read them as zeros
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          uint32_t w[4] = {vp[i][c].x, vp[i][c].y, vp[i][c].z, vp[i][c].w};
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int tok = (4 * s + i) * BS + 8 * c + 2 * j;
+            w[j] &= (tok < n_pk ? 0x0000ffffu : 0u) | (tok + 1 < n_pk ? 0xffff0000u : 0u);
+          }
+          vp[i][c] = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    }
     const int key = (4 * s + g) * BS + t;    // the key whose score this lane keeps
 #pragma unroll
     for (int r = 0; r < RR; ++r) {
@@ -649,10 +584,10 @@ __global__ void __launch_bounds__(FR_NW * 64) attn_fewrow_kernel(AttnArgs a) {
         for (int c = 0; c < 2; ++c) {
           const uint4 w = kp[i][c];
           const float* qq = &qf[r][8 * c];
-          d = fmaf(qq[0], bf_lo(w.x), d); d = fmaf(qq[1], bf_hi(w.x), d);
-          d = fmaf(qq[2], bf_lo(w.y), d); d = fmaf(qq[3], bf_hi(w.y), d);
-          d = fmaf(qq[4], bf_lo(w.z), d); d = fmaf(qq[5], bf_hi(w.z), d);
-          d = fmaf(qq[6], bf_lo(w.w), d); d = fmaf(qq[7], bf_hi(w.w), d);
+          d = fmaf(qq[0], h_lo(w.x), d); d = fmaf(qq[1], h_hi(w.x), d);
+          d = fmaf(qq[2], h_lo(w.y), d); d = fmaf(qq[3], h_hi(w.y), d);
+          d = fmaf(qq[4], h_lo(w.z), d); d = fmaf(qq[5], h_hi(w.z), d);
+          d = fmaf(qq[6], h_lo(w.w), d); d = fmaf(qq[7], h_hi(w.w), d);
         }
         d += __shfl_xor(d, 16);
         d += __shfl_xor(d, 32);
@@ -676,36 +611,16 @@ __global__ void __launch_bounds__(FR_NW * 64) attn_fewrow_kernel(AttnArgs a) {
         const float4* pp = reinterpret_cast<const float4*>(&s_p[wave][r][16 * i]);
         const float4 p0 = pp[0], p1 = pp[1], p2 = pp[2], p3 = pp[3];
         const uint4 v0 = vp[i][0], v1 = vp[i][1];
-        o = fmaf(p0.x, bf_lo(v0.x), o); o = fmaf(p0.y, bf_hi(v0.x), o);
-        o = fmaf(p0.z, bf_lo(v0.y), o); o = fmaf(p0.w, bf_hi(v0.y), o);
-        o = fmaf(p1.x, bf_lo(v0.z), o); o = fmaf(p1.y, bf_hi(v0.z), o);
-        o = fmaf(p1.z, bf_lo(v0.w), o); o = fmaf(p1.w, bf_hi(v0.w), o);
-        o = fmaf(p2.x, bf_lo(v1.x), o); o = fmaf(p2.y, bf_hi(v1.x), o);
-        o = fmaf(p2.z, bf_lo(v1.y), o); o = fmaf(p2.w, bf_hi(v1.y), o);
-        o = fmaf(p3.x, bf_lo(v1.z), o); o = fmaf(p3.y, bf_hi(v1.z), o);
-        o = fmaf(p3.z, bf_lo(v1.w), o); o = fmaf(p3.w, bf_hi(v1.w), o);
+        o = fmaf(p0.x, h_lo(v0.x), o); o = fmaf(p0.y, h_hi(v0.x), o);
+        o = fmaf(p0.z, h_lo(v0.y), o); o = fmaf(p0.w, h_hi(v0.y), o);
+        o = fmaf(p1.x, h_lo(v0.z), o); o = fmaf(p1.y, h_hi(v0.z), o);
+        o = fmaf(p1.z, h_lo(v0.w), o); o = fmaf(p1.w, h_hi(v0.w), o);
+        o = fmaf(p2.x, h_lo(v1.x), o); o = fmaf(p2.y, h_hi(v1.x), o);
+        o = fmaf(p2.z, h_lo(v1.y), o); o = fmaf(p2.w, h_hi(v1.y), o);
+        o = fmaf(p3.x, h_lo(v1.z), o); o = fmaf(p3.y, h_hi(v1.z), o);
+        o = fmaf(p3.z, h_lo(v1.w), o); o = fmaf(p3.w, h_hi(v1.w), o);
       }
       acc[r] = o;
-    }
-  }
-
-  // this step's own keys: row (j, gi) sees the new keys 0..j
-  if (Kn && wave == 0) {
-    for (int jn = 0; jn < qb; ++jn) {
-      const size_t src = ((size_t)(row0 + jn) * a.Hkv + kvh) * FR_HD + lane;
-      const float kk = (float)Kn[src], vv = (float)Vn[src];
-#pragma unroll
-      for (int r = 0; r < RR; ++r) {
-        if (r < R && jn <= r / G) {          // (uniform over the wave)
-          const float sv = wave_sum(qe[r] * kk);
-          const float new_m = fmaxf(m[r], sv);
-          const float alpha = (m[r] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m[r] - new_m);
-          const float p = __builtin_amdgcn_exp2f(sv - new_m);
-          m[r] = new_m;
-          l[r] = l[r] * alpha + (lane == 0 ? p : 0.f);
-          acc[r] = acc[r] * alpha + p * vv;
-        }
-      }
     }
   }
 
@@ -925,7 +840,7 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
     return hipSuccess;
   }
   dim3 grid(a.H, a.M);
-  if (a.dtype == MN_DT_BF16) attn_generic_kernel<f16_t, bf16_t><<<grid, GEN_THREADS, 0, st>>>(a);
+  if (a.dtype == MN_DT_BF16) attn_generic_kernel<f16_t, f16_t><<<grid, GEN_THREADS, 0, st>>>(a);
   else attn_generic_kernel<float, float><<<grid, GEN_THREADS, 0, st>>>(a);
   return hipSuccess;
 }

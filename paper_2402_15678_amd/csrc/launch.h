@@ -67,7 +67,6 @@ struct RopeAppendArgs {
   RowInfo rows;
   KvView kv;
   void* q;  // [M][H][hd] activation type
-  void *knew, *vnew;  // [M][Hkv][hd] activation type: this step's K/V rows before the cache rounding, or null
   int M, H, Hkv, hd, dtype;
   int32_t* dev_status;  // MN_DEV_RANGE is OR-ed in when an fp16 output saturates, or null
 };
@@ -110,10 +109,7 @@ struct AttnArgs {
   const void* q;  // [M][H][hd] activation type
   void* out;      // [M][H*hd] activation type
   RowInfo rows;
-  KvView kv;
-  // this step's own K/V rows [M][Hkv][hd] in the activation type (keys at positions >= ctx_b are read
-  // from here instead of the cache), or null: every key is read from the cache
-  const void *knew, *vnew;
+  KvView kv;      // every key is read from the pages, this step's own (appended before the call) included
   int B, M, H, Hkv, hd, dtype, max_ctx;
   int max_q;       // largest number of rows of one sequence (host knowledge)
   float* scratch;  // split-KV partials

@@ -179,11 +179,6 @@ template <typename T>
 __device__ __forceinline__ void store1(T* p, float v, bool& bad) { Store<T>::store(p, v); }
 template <>
 __device__ __forceinline__ void store1<f16_t>(f16_t* p, float v, bool& bad) { *p = (f16_t)sat_h(v, bad); }
-template <>
-__device__ __forceinline__ void store1<bf16_t>(bf16_t* p, float v, bool& bad) {
-  bad |= !(__builtin_fabsf(v) <= F16_MAX);
-  *p = f2bf(__builtin_fminf(__builtin_fmaxf(v, -65280.f), 65280.f));  // 65280: the largest bf16 value below 65504
-}
 
 // T: storage type of the embedding tables; TA: activation type of the normalised output
 template <typename T, typename TA>
@@ -328,13 +323,6 @@ __global__ void __launch_bounds__(ROPE_THREADS) rope_append_kernel(RopeAppendArg
     if (bad && a.dev_status) atomicOr(a.dev_status, MN_DEV_RANGE);
     return;
   }
-  // this step's own copy in the activation type (not yet rounded to the cache's storage type)
-  if (a.knew) {
-    TA* side = reinterpret_cast<TA*>(is_v ? a.vnew : a.knew) +
-               ((size_t)m * a.Hkv + (head - a.H - (is_v ? a.Hkv : 0))) * hd;
-    store1<TA>(side + t, v0, bad);
-    store1<TA>(side + t + half, v1, bad);
-  }
   if (slot < 0) return;  // disabled sequence: nothing is written to the cache (and nothing reported)
   const int bs = a.kv.block_size;
   const int pb = slot / bs;
@@ -360,7 +348,7 @@ void launch_rope_append(const RopeAppendArgs& a, hipStream_t st) {
   if (a.M <= 0) return;
   const int per_block = ROPE_THREADS / (a.hd / 2);  // head_dim is one of 8 ... 256: hd/2 divides 256
   dim3 grid((a.H + 2 * a.Hkv + per_block - 1) / per_block, a.M);
-  if (a.dtype == MN_DT_BF16) rope_append_kernel<f16_t, bf16_t><<<grid, ROPE_THREADS, 0, st>>>(a);
+  if (a.dtype == MN_DT_BF16) rope_append_kernel<f16_t, f16_t><<<grid, ROPE_THREADS, 0, st>>>(a);
   else rope_append_kernel<float, float><<<grid, ROPE_THREADS, 0, st>>>(a);
 }
 

@@ -29,7 +29,8 @@ def to_device(a: np.ndarray, dtype: int) -> torch.Tensor:
 
 
 def to_device_act(a: np.ndarray, dtype: int) -> torch.Tensor:
-    """Host values -> device tensor in the activation type of the model (fp32, or fp16 in bf16 models)."""
+    """Host values -> device tensor in the activation type of the model (fp32, or fp16 in bf16 models), which is
+    also the type of its KV pages."""
     a = np.ascontiguousarray(a, dtype=np.float32)
     if dtype == synth.DT_BF16:
         return torch.from_numpy(a.astype(np.float16)).to(_dev())
@@ -169,8 +170,8 @@ class DeviceKV:
 
     @classmethod
     def from_host(cls, desc: synth.ModelDesc, kv: synth.PagedKV) -> "DeviceKV":
-        ks = [to_device(a, desc.dtype) for a in kv.k_pages]
-        vs = [to_device(a, desc.dtype) for a in kv.v_pages]
+        ks = [to_device_act(a, desc.dtype) for a in kv.k_pages]   # (bf16-valued draws: the same numbers in fp16)
+        vs = [to_device_act(a, desc.dtype) for a in kv.v_pages]
         return cls(desc, kv.block_size, kv.num_blocks, kv.block_tables, kv.ctx_lens, ks, vs)
 
     @classmethod
@@ -180,12 +181,13 @@ class DeviceKV:
         dev = _dev()
         gen = torch.Generator(device=dev)
         gen.manual_seed(int(seed) + 77)
-        st = torch.bfloat16 if desc.dtype == synth.DT_BF16 else torch.float32
+        # 16-bit models: draws rounded to bf16 (the values the host recipe gives), held as fp16 pages
+        page = ((lambda t: t.to(torch.bfloat16).to(torch.float16)) if desc.dtype == synth.DT_BF16 else (lambda t: t))
         hk, hd = desc.n_kv_heads, desc.head_dim
         ks, vs = [], []
         for _ in range(desc.n_layers):
-            ks.append((torch.randn((nb, hk, hd // 8, block_size, 8), generator=gen, device=dev) * std).to(st))
-            vs.append((torch.randn((nb, hk, hd, block_size), generator=gen, device=dev) * std).to(st))
+            ks.append(page(torch.randn((nb, hk, hd // 8, block_size, 8), generator=gen, device=dev) * std))
+            vs.append(page(torch.randn((nb, hk, hd, block_size), generator=gen, device=dev) * std))
         return cls(desc, block_size, nb, bt, ctx_lens, ks, vs)
 
     def download(self, layer: int):

@@ -22,11 +22,6 @@ def logit_tol_at_depth(n_layers: int) -> float:
     return TOL[synth.DT_BF16] * max(1.0, float(np.sqrt(n_layers / 4.0)))
 
 
-# A pass that finds the rows it attends to in the bf16 cache (every pass after the one that scored them) is this
-# many times further from the exact result than the pass that scored them and still had them in fp16 (measured at
-# the 70B width, one layer: 4.7e-2 against 1.7e-2).
-CACHE_PRECISION_FACTOR = 3.0
-
 
 def weights_f64(W: Dict[str, object]) -> Dict[str, object]:
     """The same parameters held as fp64 so the oracle does not convert them at every use."""
