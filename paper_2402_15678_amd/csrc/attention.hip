@@ -300,10 +300,10 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) attn_mfma_kernel(Att
     const char* kp_ = kbase + (uint64_t)min((uint32_t)s_bidx[2 * t_ + ksel], blk_last) * blk_bytes; \
     const char* vp_ = vbase + (uint64_t)min((uint32_t)s_bidx[2 * t_ + vsel], blk_last) * blk_bytes; \
     const uint32_t l_ = __builtin_amdgcn_readfirstlane(lds_w + (uint32_t)(SLOT) * TILE_BYTES);    \
-    dma16<0>(kp_, l_);                                                                            \
-    dma16<4 * 8 * 2>(kp_, l_ + 4 * 1024);                                                         \
-    dma16<0>(vp_, l_ + 8 * 1024);                                                                 \
-    dma16<64 * BS * 2>(vp_, l_ + 12 * 1024);                                                      \
+    dma16<0, true>(kp_, l_);                                                                  \
+    dma16<4 * 8 * 2, true>(kp_, l_ + 4 * 1024);                                               \
+    dma16<0, true>(vp_, l_ + 8 * 1024);                                                       \
+    dma16<64 * BS * 2, true>(vp_, l_ + 12 * 1024);                                            \
   }
     f16x8 kf[8];  // K fragments of the tile about to be multiplied
     // prologue: tiles 0 .. NS-2 on their way; tile 0 landed and its K fragments in registers

@@ -103,9 +103,14 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
 // immediate offset to BOTH addresses, so the LDS base handed to it is lowered by the same amount.  The load
 // is invisible to the compiler's wait-count bookkeeping: the kernel waits for these loads itself
 // (wait_vm) and issues no other memory load while one of them may still be needed.
-template <int OFFSET>
+// STREAM: the data is read once (weights, KV pages): the load carries the non-temporal hint, so the line does not
+// push out of the L2 what the kernels share and re-read (activation tiles, partial sums, code).
+template <int OFFSET, bool STREAM = false>
 __device__ __forceinline__ void dma16(const char* g, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off offset:%2" ::"v"(g), "s"(lds_base - (uint32_t)OFFSET), "n"(OFFSET) : "memory");
+  if constexpr (STREAM)
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off offset:%2 nt" ::"v"(g), "s"(lds_base - (uint32_t)OFFSET), "n"(OFFSET) : "memory");
+  else
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off offset:%2" ::"v"(g), "s"(lds_base - (uint32_t)OFFSET), "n"(OFFSET) : "memory");
 }
 // wait until at most N of this wave's memory loads are outstanding (they complete in order)
 template <int N>
