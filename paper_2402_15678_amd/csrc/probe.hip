@@ -6,12 +6,14 @@
 
 namespace mn {
 
-// every thread reads 4 x 16 bytes per trip, 1 KB per wave instruction, the whole grid striding over the buffer
+// every thread reads 4 x 16 bytes per trip, 1 KB per wave instruction, the whole grid striding over the buffer;
+// the loads carry the non-temporal hint, as the weight and KV streams of the library do
 __global__ void __launch_bounds__(256) probe_stream_kernel(const u32x4* __restrict__ p, size_t n16, uint32_t* sink) {
   u32x4 acc = {0u, 0u, 0u, 0u};
   const size_t stride = (size_t)gridDim.x * 1024;
   for (size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x; i + 768 < n16; i += stride) {
-    const u32x4 v0 = p[i], v1 = p[i + 256], v2 = p[i + 512], v3 = p[i + 768];
+    const u32x4 v0 = __builtin_nontemporal_load(p + i), v1 = __builtin_nontemporal_load(p + i + 256),
+                v2 = __builtin_nontemporal_load(p + i + 512), v3 = __builtin_nontemporal_load(p + i + 768);
     acc ^= v0 ^ v1 ^ v2 ^ v3;
   }
   if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u && sink) *sink = acc[0];  // (keeps the loads alive)
