@@ -745,6 +745,9 @@ static GemmPlan gemm_plan(int M, int N, int K, int forced_split) {
     return (iters + per - 1) / per;
   };
   GemmPlan best{4, 1};
+  // (tuning builds: the plan of the projection with N output columns by hand)
+  if (MN_TUNE("MN_GEMM_PLAN_N", 0) == N && MN_TUNE("MN_GEMM_PLAN_K", 0) == K && M > 96 && M <= 144)
+    return GemmPlan{MN_TUNE("MN_GEMM_PLAN_NW", 4), MN_TUNE("MN_GEMM_PLAN_SPLIT", 1)};
   if (M > 144 || (big_min_m() > 0 && M >= big_min_m())) {  // big-tile kernel: 256-column groups x row blocks, one workgroup per CU
     const int gx = (slices / 4 + 1) / 2;
     int rb = 1 << 30;
