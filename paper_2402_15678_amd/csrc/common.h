@@ -5,21 +5,21 @@
 
 namespace mn {
 
-typedef uint16_t bf16_t;  // raw bf16 pattern (storage type of weights and KV pages in bf16 models)
-typedef _Float16 f16_t;   // activation type in bf16 models (see the note below)
+typedef uint16_t bf16_t;  // raw bf16 pattern (the type weights and embeddings of bf16 models arrive in)
+typedef _Float16 f16_t;   // activation type and KV page type in bf16 models (see the note below)
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// Precision note.  In bf16 models the weights and the KV pages arrive as bf16.  Every bf16 value
+// Precision note.  In bf16 models the weights arrive as bf16.  Every bf16 value
 // in the normal fp16 range is exactly representable in fp16 (8 significant bits into 11), so the
-// weights are re-encoded as fp16 once, when they are packed, the cache fragments are widened to fp16
-// on their way to the MFMA, and all products run on the fp16 MFMA with fp32 accumulation, while the
+// weights are re-encoded as fp16 once, when they are packed, the KV pages hold fp16 (the library writes
+// them and reads them back), and all products run on the fp16 MFMA with fp32 accumulation, while the
 // activations between kernels (norm output, queries, attention output, FFN activation, softmax
 // probabilities) are kept in fp16: 8x less rounding error per stage than bf16 activations at the
-// same MFMA rate and the same HBM traffic.  bf16 magnitudes below 2^-14 lose low bits in the widening
+// same MFMA rate and the same HBM traffic.  bf16 magnitudes below 2^-14 lose low bits in the re-encoding
 // (absolute error below 2^-24), which is far below every tolerance.
 
 constexpr int WAVE = 64;
@@ -31,7 +31,6 @@ __device__ __forceinline__ bf16_t f2bf(float f) {
   return (bf16_t)(u >> 16);
 }
 __device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
-__device__ __forceinline__ uint32_t pack2bf(float lo, float hi) { return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16); }
 // two fp32 -> packed fp16, round to nearest even
 __device__ __forceinline__ uint32_t pack2h(float lo, float hi) {
   const f32x2 v = {lo, hi};

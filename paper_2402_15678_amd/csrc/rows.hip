@@ -169,12 +169,7 @@ __device__ __forceinline__ void store4<f16_t>(f16_t* p, float4 v, bool& bad) {
 }
 template <>
 __device__ __forceinline__ void store4<float>(float* p, float4 v, bool&) { *reinterpret_cast<float4*>(p) = v; }
-template <>
-__device__ __forceinline__ void store4<bf16_t>(bf16_t* p, float4 v, bool&) {
-  *reinterpret_cast<uint2*>(p) = make_uint2(pack2bf(v.x, v.y), pack2bf(v.z, v.w));
-}
-// one element in the activation type TA / the page storage type T; fp16 and bf16 saturate to the fp16 range (the
-// pages are widened to fp16 when attention reads them)
+// one element in the activation type TA / the page storage type T; fp16 saturates to the fp16 range
 template <typename T>
 __device__ __forceinline__ void store1(T* p, float v, bool& bad) { Store<T>::store(p, v); }
 template <>
