@@ -708,11 +708,13 @@ __global__ void __launch_bounds__(1024) attn_plan_kernel(RowInfo rows, int B, in
     reinterpret_cast<int4*>(items)[2 * (size_t)i] = make_int4(-1, 0, 0, 1);
 }
 
-// Fewest key tiles a workgroup should take: below that the lead-in of a workgroup and the fp32 partial it
-// writes cost more than the parallelism wins (measured at 33 tiles per sequence: 2 splits beat 1, 4 and 8).
+// Fewest key tiles a workgroup should take: below that the lead-in of a workgroup, the fp32 partial it writes and the
+// merge launch behind cost as much as the parallelism wins (measured at 33 tiles per sequence and 128 (sequence, KV
+// head) pairs: one split 2.10 ms of attention per step, two splits + merge 2.13-2.17, three or four 2.8-2.9; 16 and
+// 32 give the same times at the other benchmark shapes, where the batch size decides the splits).
 int attention_min_tiles() {
-  const int x = MN_TUNE("MN_ATTN_MIN_TILES", 16);
-  return x > 0 ? x : 16;
+  const int x = MN_TUNE("MN_ATTN_MIN_TILES", 32);
+  return x > 0 ? x : 32;
 }
 
 // 1.25 workgroups with work per CU: measured flat between 1 and 1.3 per CU, slower beyond (every further split of

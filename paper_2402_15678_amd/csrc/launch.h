@@ -120,7 +120,7 @@ struct AttnArgs {
 };
 size_t attention_scratch_bytes(int M, int H, int hd, int max_ctx, int dtype);
 bool attention_mfma_supported(int H, int Hkv, int hd, int block_size, int dtype);
-int attention_min_tiles();  // fewest key tiles an attention workgroup should take (16)
+int attention_min_tiles();  // fewest key tiles an attention workgroup should take (32)
 int attention_target_workgroups();  // attention workgroups with work the plan aims for (320)
 size_t attention_items_capacity(int B, int M, int H, int Hkv);
 // once per step, after the row bookkeeping and before the first launch_attention: the list of workgroups

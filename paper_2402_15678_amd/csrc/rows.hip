@@ -110,7 +110,7 @@ __global__ void __launch_bounds__(1024) prepare_kernel(PrepArgs a) {
   }
   __syncthreads();
   // Balance of the attention grid: a workgroup should take about (all key tiles x KV heads) / (the number of
-  // workgroups aimed for) tiles, at least 16 (below that the lead-in of a workgroup and the partial sums cost more than
+  // workgroups aimed for) tiles, at least 32 (below that the lead-in of a workgroup and the partial sums cost more than
   // the parallelism wins).  Long sequences of a ragged batch are then cut into more splits than short ones.
   if (tid == 0 && a.attn_tps) {
     const unsigned long long w = (unsigned long long)max(a.attn_wgs, 1);
