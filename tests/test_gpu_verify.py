@@ -234,3 +234,44 @@ def test_llama160m_width_few_rows(hb):
     ks = [0, 3, 1, 2, 0, 3, 3, 0, 1, 2]
     err, dec = _reduced_case(hb, wl, 2, 10, 4, ctx_override=ctx, k_override=ks)
     print("llama160m-width few rows max |dlogit| = %.2e, decisive %d/10" % (err, dec))
+
+
+def test_one_pass_equals_sequential_decodes_two_layers(hb):
+    """Scoring k + 1 positions in one pass against k + 1 single-position passes of the library itself (section 2.1:
+    the speculated tokens are scored in parallel with the outcome of scoring them one by one), at the 70B width and
+    two layers.  Both decodings multiply the same numbers (the scored rows' K/V are in the pages in fp16 for both);
+    what is left is the order of the fp32 sums in launches of other shapes, an fp16 rounding tipped now and then:
+    a third of the bf16-path tolerance."""
+    harness, binding = hb
+    wl = synth.WORKLOADS[2]
+    desc = wl.desc.with_layers(2)
+    B, k = 6, 5
+    g = synth.stream(9876, 1)
+    ctx = g.integers(40, 400, size=B).astype(np.int32)
+    ks = np.full(B, k, np.int32)
+    model = harness.DeviceModel.from_host(desc, synth.make_weights(desc, 77))
+    kvd = harness.DeviceKV.from_host(desc, synth.make_paged_kv(desc, ctx, ks, 77))
+    ctx0 = kvd.ctx_lens.clone()
+    max_ctx = int((ctx + ks + 1).max())
+    last = _i32(g.integers(0, desc.vocab, size=B))
+    toks = _i32(g.integers(0, desc.vocab, size=(B, k)))                 # the tokens both decodings are fed
+    ses = harness.VerifySession(model, kvd, B, k, 1, max_ctx, max_rows=B * (k + 1), want_logits=True)
+    ses.forward(last, _i32(ks), ks.tolist(), voted=toks)
+    torch.cuda.synchronize()
+    assert ses.dev_status.item() == 0
+    one_pass = ses.logits.cpu().numpy().reshape(B, k + 1, -1).copy()
+    one = harness.VerifySession(model, kvd, B, 0, 1, max_ctx, max_rows=B, want_logits=True)
+    zeros, dummy = _i32(np.zeros(B)), _i32(np.zeros((B, 1)))
+    seq = []
+    for j in range(k + 1):
+        cur = last if j == 0 else toks[:, j - 1].contiguous()
+        kvd.ctx_lens.copy_(ctx0 + j)                                    # the rows scored so far are committed
+        one.forward(cur, zeros, [0] * B, voted=dummy)
+        torch.cuda.synchronize()
+        assert one.dev_status.item() == 0
+        seq.append(one.logits.cpu().numpy().copy())
+    kvd.ctx_lens.copy_(ctx0)
+    seq = np.stack(seq, axis=1)
+    worst = float(np.abs(one_pass - seq).max())
+    print("one pass vs sequential, 2 layers at the 70B width: max |dlogit| = %.2e" % worst)
+    assert worst < util.TOL[synth.DT_BF16] / 3, worst
